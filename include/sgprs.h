@@ -1,0 +1,237 @@
+/*
+ * sgprs.h -- C ABI of the MI355X (gfx950) stage-computation library under SGPRS.
+ *
+ * SGPRS (the paper's "Task Model" and "Real-Time Scheduler Design" sections)
+ * splits each periodic DNN task tau_i into stages tau_i^j and runs the stages
+ * on a context pool CP = {cp_1 .. cp_np} of n_p spatial GPU partitions with a
+ * fixed number of compute units each.  This library is the part the
+ * partitions execute: the pool itself (CU-masked HIP streams) and the six
+ * stages of the paper's benchmark task, ResNet18 on a 224x224 input
+ * ("Simulation Results"), as hand-written HIP kernels.  The scheduler that
+ * decides which stage goes to which partition is not part of this library.
+ *
+ * Conventions
+ *  - Every call returns an int status: SGPRS_OK (0) or a negative SGPRS_ERR_*.
+ *    Nothing throws across the ABI.  sgprs_last_error() gives a thread-local
+ *    text for the last failure on the calling thread.
+ *  - Handles (sgprs_pool_t, sgprs_task_t) are opaque, owned by the library,
+ *    released by the matching *_destroy.
+ *  - "DEVICE" pointers are device memory owned by the caller (for instance
+ *    torch.Tensor.data_ptr()); they must stay valid until the partition the
+ *    work was queued on has been synchronised.  "HOST" pointers are ordinary
+ *    host memory, read or written before the call returns.
+ *  - All *_run and per-operator calls only ENQUEUE work on the partition's
+ *    stream and return; arguments are validated first, so a failing call
+ *    enqueues nothing.
+ *  - Activation layout is NHWC (channels fastest) in the call's dtype.
+ *    SGPRS_BF16 means bf16 storage with fp32 accumulation and an fp32
+ *    epilogue; results are rounded to bf16 (nearest, ties to even) on store.
+ *  - A CU mask never changes results, only speed: for a given tensor shape the
+ *    arithmetic order depends on the partition's CU count only through the
+ *    split-K factor, whose second pass sums in a fixed order.
+ */
+#ifndef SGPRS_H
+#define SGPRS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sgprs_pool sgprs_pool_t;
+typedef struct sgprs_task sgprs_task_t;
+
+typedef enum { SGPRS_F32 = 0, SGPRS_BF16 = 1 } sgprs_dtype_t;
+
+enum {
+    SGPRS_OK = 0,
+    SGPRS_ERR_INVALID_ARG = -1,
+    SGPRS_ERR_NO_DEVICE = -2,
+    SGPRS_ERR_HIP = -3,
+    SGPRS_ERR_OOM = -4,
+    SGPRS_ERR_UNSUPPORTED = -5,
+    SGPRS_ERR_OVERSUBSCRIBED = -6
+};
+
+/* pool flags */
+enum {
+    SGPRS_POOL_OVERSUBSCRIBE = 1u, /* allow n_p * cus > total CUs: masks wrap and overlap */
+    SGPRS_POOL_BLOCKED_LAYOUT = 2u /* mask bit = xcd * cus_per_xcd + cu instead of the
+                                      default cu * n_xcd + xcd (see sgprs_build_cu_mask) */
+};
+
+#define SGPRS_MAX_MASK_WORDS 16 /* 512 CUs */
+#define SGPRS_RESNET18_CONVS 20
+#define SGPRS_RESNET18_STAGES 6
+
+const char *sgprs_status_string(int status);
+const char *sgprs_last_error(void);
+/* major*10000 + minor*100 + patch */
+int sgprs_version(void);
+
+/* ------------------------------------------------------------------ pool --
+ * Context pool CP of the paper's task model: n_p partitions, each restricted
+ * to `cus_per_partition` compute units through hipExtStreamCreateWithCUMask.
+ * The paper's "sm SMs for each" context becomes "cus CUs for each" stream.
+ * Over-subscription (sum of partition sizes above the GPU's CU count, the
+ * paper's SGPRS_os variants) needs SGPRS_POOL_OVERSUBSCRIBE. */
+
+/* HOST-only helper, needs no GPU.  Fills `words` (n_words uint32, bit i of the
+ * whole vector = CU-mask bit i) with the mask of partition `partition`.
+ * Every partition takes cus/n_xcd CUs on EACH of the n_xcd accelerator dies,
+ * slots [partition*cus/n_xcd, (partition+1)*cus/n_xcd) modulo the die's CU
+ * count, so that the hardware's round-robin of workgroups over dies stays
+ * balanced.  blocked_layout selects how (die, slot) maps to a bit.
+ * Errors: INVALID_ARG if total_cus % n_xcd, cus % n_xcd, cus outside
+ * [n_xcd, total_cus], partition < 0, or n_words too small. */
+int sgprs_build_cu_mask(int total_cus, int n_xcd, int cus, int partition, int blocked_layout,
+                        uint32_t *words, int n_words);
+
+/* Creates n_p partitions of cus_per_partition CUs on `device`.  cus must be a
+ * multiple of the die count.  NO_DEVICE if there is no usable GPU,
+ * OVERSUBSCRIBED if n_p*cus exceeds the device without the flag. */
+int sgprs_pool_create(int device, int n_p, int cus_per_partition, unsigned flags,
+                      sgprs_pool_t **out);
+/* Same with caller-chosen masks: masks[p*words_per_mask .. +words_per_mask) HOST. */
+int sgprs_pool_create_masks(int device, int n_p, const uint32_t *masks, int words_per_mask,
+                            sgprs_pool_t **out);
+/* Synchronises and destroys all partition streams. */
+int sgprs_pool_destroy(sgprs_pool_t *pool);
+/* Any output pointer may be NULL. */
+int sgprs_pool_info(const sgprs_pool_t *pool, int *n_p, int *cus_per_partition, int *total_cus,
+                    int *n_xcd);
+/* Number of CUs in one partition's mask. */
+int sgprs_pool_partition_cus(const sgprs_pool_t *pool, int partition, int *cus);
+int sgprs_pool_get_mask(const sgprs_pool_t *pool, int partition, uint32_t *words, int n_words);
+/* The partition's hipStream_t (for events or torch.cuda.ExternalStream); NULL on error. */
+void *sgprs_pool_stream(const sgprs_pool_t *pool, int partition);
+int sgprs_partition_sync(sgprs_pool_t *pool, int partition);
+int sgprs_pool_sync(sgprs_pool_t *pool);
+/* Diagnostic: runs `n_blocks` (<= 65536) one-wave workgroups on the partition,
+ * each spinning ~spin_cycles clock ticks, and records where each ran:
+ * out[2*b] = accelerator die id, out[2*b+1] = hardware id register (CU, shader
+ * array and engine fields).  out: DEVICE uint32[2*n_blocks].  Used to check
+ * the mask-bit -> die mapping by measurement. */
+int sgprs_partition_probe(sgprs_pool_t *pool, int partition, int n_blocks, int spin_cycles,
+                          uint32_t *out);
+
+/* -------------------------------------------------------- per-operator ----
+ * The operators of the paper's "GPU Speedup Analysis": convolution, max
+ * pooling and the remaining ResNet18 operations.  All tensors DEVICE, NHWC. */
+
+typedef struct {
+    int n, h, w;        /* batch, input height, width */
+    int cin, cout;      /* channels */
+    int r, s;           /* kernel height, width (r == s: 1, 3 or 7) */
+    int stride, pad;
+    int dtype;          /* sgprs_dtype_t */
+    int relu;           /* 1: ReLU after scale/shift(+residual) */
+} sgprs_conv_desc_t;
+
+/* HOST helper: folded inference BN, scale = gamma/sqrt(var+eps),
+ * shift = beta - mean*scale, computed in fp64, returned as fp32. */
+int sgprs_fold_bn(const float *gamma, const float *beta, const float *mean, const float *var,
+                  float eps, int c, float *scale, float *shift);
+/* HOST helpers: size of, and conversion to, the packed weight layout the conv
+ * kernels read.  w_oihw: [cout][cin][r][s] fp32.  Packed: [cout][K'] in the
+ * call's dtype (bf16 rounded to nearest even), K' ordered (r, s, c) for
+ * cin % 32 == 0, and a zero-padded 7 x 32 tap-row layout for the 3-channel
+ * 7x7 stride-2 stem.  UNSUPPORTED for any other shape. */
+int sgprs_conv_packed_weight_bytes(const sgprs_conv_desc_t *d, size_t *bytes);
+int sgprs_pack_conv_weights(const sgprs_conv_desc_t *d, const float *w_oihw, void *w_packed,
+                            size_t bytes);
+int sgprs_unpack_conv_weights(const sgprs_conv_desc_t *d, const void *w_packed, size_t bytes,
+                              float *w_oihw);
+/* Split-K scratch needed on a partition of partition_cus CUs (0 when the
+ * launch is not split). */
+int sgprs_conv2d_workspace(const sgprs_conv_desc_t *d, int partition_cus, size_t *bytes);
+/* y = act( scale[k] * conv(x, w)[.,k] + shift[k] (+ residual) ).
+ * x: [n][h][w][cin]; w_packed: DEVICE copy of the packed weights; scale, shift:
+ * DEVICE fp32[cout]; residual: NULL or [n][p][q][cout] in dtype; y: same shape.
+ * workspace: DEVICE, at least sgprs_conv2d_workspace() bytes (may be NULL if 0).
+ * x, residual and y must not overlap. */
+int sgprs_conv2d(const sgprs_conv_desc_t *d, const void *x, const void *w_packed,
+                 const float *scale, const float *shift, const void *residual, void *y,
+                 void *workspace, size_t workspace_bytes, sgprs_pool_t *pool, int partition);
+/* Max pooling 3x3, stride 2, pad 1 (padding never wins): [n][h][w][c] ->
+ * [n][(h-1)/2+1][(w-1)/2+1][c].  c % 8 == 0 (bf16) or c % 4 == 0 (fp32). */
+int sgprs_maxpool2d(int dtype, int n, int h, int w, int c, const void *x, void *y,
+                    sgprs_pool_t *pool, int partition);
+/* y = max(0, scale[c]*x + shift[c]) over `pixels` rows of c channels. */
+int sgprs_bn_relu(int dtype, size_t pixels, int c, const void *x, const float *scale,
+                  const float *shift, void *y, sgprs_pool_t *pool, int partition);
+/* y = a + b, followed by ReLU if relu != 0; `count` elements (multiple of 8). */
+int sgprs_add_relu(int dtype, size_t count, const void *a, const void *b, void *y, int relu,
+                   sgprs_pool_t *pool, int partition);
+/* Global average pool over hw positions, then FC: x [n][hw][cin] (dtype),
+ * w [cout][cin] (dtype, DEVICE), bias NULL or fp32[cout], logits fp32 [n][cout].
+ * workspace: DEVICE fp32[n*cin] for the pooled vectors.  cin % 64 == 0, cin <= 1024. */
+int sgprs_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void *x, const void *w,
+                     const float *bias, float *logits, float *workspace, sgprs_pool_t *pool,
+                     int partition);
+
+/* ------------------------------------------------------------------ task --
+ * Task tau_i = one ResNet18 instance, split into the paper's six stages:
+ *   0 conv7x7/2+BN+ReLU+maxpool3x3/2, 1..4 layer1..layer4 (two BasicBlocks
+ *   each, 1x1/2 projection shortcut at the head of layers 2-4), 5 global
+ *   average pool + FC.
+ * Creating a task is the offline phase: BN folding, rounding to dtype, weight
+ * packing and upload happen there. */
+
+typedef struct {
+    /* HOST fp32, forward order: stem; layer1.{0,1}.conv{1,2}; then for layers
+     * 2..4: L.0.conv1, L.0.conv2, L.0.downsample, L.1.conv1, L.1.conv2 */
+    const float *conv_w[SGPRS_RESNET18_CONVS]; /* OIHW */
+    const float *bn_gamma[SGPRS_RESNET18_CONVS];
+    const float *bn_beta[SGPRS_RESNET18_CONVS];
+    const float *bn_mean[SGPRS_RESNET18_CONVS];
+    const float *bn_var[SGPRS_RESNET18_CONVS];
+    const float *fc_w; /* [1000][512] */
+    const float *fc_b; /* [1000] or NULL */
+    float bn_eps;
+} sgprs_resnet18_params_t;
+
+/* Allocates device weights and an activation workspace for up to max_batch
+ * images.  A task is not re-entrant: one run in flight at a time. */
+int sgprs_task_create_resnet18(int device, int dtype, int max_batch,
+                               const sgprs_resnet18_params_t *host_params, sgprs_task_t **out);
+int sgprs_task_destroy(sgprs_task_t *task);
+/* Number of stages (6), or a negative status. */
+int sgprs_task_num_stages(const sgprs_task_t *task);
+/* Byte sizes and logical N,C,H,W of a stage's input and output at `batch`.
+ * Stage 5's output is fp32 [batch][1000] whatever the dtype.  Outputs nullable. */
+int sgprs_task_stage_io(const sgprs_task_t *task, int stage, int batch, size_t *in_bytes,
+                        size_t *out_bytes, int in_nchw[4], int out_nchw[4]);
+/* Stage tau_i^j on partition cp_p: in/out DEVICE, NHWC in the task's dtype. */
+int sgprs_stage_run(sgprs_task_t *task, int stage, int batch, const void *in, void *out,
+                    sgprs_pool_t *pool, int partition);
+/* All six stages in order.  partition_per_stage == NULL: all on `partition`;
+ * otherwise HOST int[6] and consecutive stages on different partitions are
+ * chained with events.  in: [batch][224][224][3]; logits: fp32 [batch][1000].
+ * The call returns once everything is queued; completion is observed on the
+ * last stage's partition. */
+int sgprs_task_run(sgprs_task_t *task, int batch, const void *in, float *logits,
+                   sgprs_pool_t *pool, int partition, const int *partition_per_stage);
+/* DEVICE pointer to the task-owned buffer holding stage j's output (j in 0..4)
+ * after sgprs_task_run; NULL on error. */
+const void *sgprs_task_stage_output(const sgprs_task_t *task, int stage);
+/* Per-kernel timing for measurement.  With profiling on, every kernel launch
+ * of a stage is bracketed by events on the partition stream (this adds
+ * latency; keep it off when timing throughput).  After synchronising,
+ * sgprs_task_kernel_times returns, for the last run of each stage, one record
+ * per launch: HOST arrays of length *count (in: capacity).  kind: 0 conv
+ * implicit GEMM, 1 stem conv, 2 split-K reduce, 3 max-pool, 4 avg-pool, 5 FC.
+ * flops/bytes are the algorithmic work of the launch. */
+int sgprs_task_set_profiling(sgprs_task_t *task, int on);
+int sgprs_task_kernel_times(sgprs_task_t *task, int stage, int *count, int *kind, int *variant,
+                            float *ms, double *flops, double *bytes);
+/* Name of the kernel instantiation behind (kind, variant), for matching
+ * profiler rows; static storage. */
+const char *sgprs_kernel_name(int kind, int variant);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SGPRS_H */

@@ -1,0 +1,329 @@
+// Convolution as implicit GEMM on the gfx950 matrix cores.
+//
+// The paper's "GPU Speedup Analysis" singles out convolution as the operation
+// that dominates ResNet18; it really is a dense contraction, so it goes to
+// MFMA:  C[m][n] = sum_k A[m][k] * B[n][k]  with
+//   m = output pixel (image, p, q), n = output channel, k = (r, s, c),
+//   A gathered on the fly from the NHWC input (zero outside the image),
+//   B = weights packed [cout][r][s][cin].
+// A k-tile is 128 bytes of one filter tap (64 bf16 / 32 fp32 channels), so a
+// tile row is one contiguous run of channels of one input pixel.
+//
+// Per workgroup (256 threads = 4 wavefronts of 64): a BM x BN output tile,
+// A and B k-tiles staged in LDS (double buffered, register prefetch of the
+// next k-tile while the current one feeds the MFMAs), XOR-swizzled 16-byte
+// chunks so that fragment reads are bank-conflict free.  The epilogue applies
+// the folded BN scale/shift, the residual and ReLU in fp32 and stores in the
+// activation dtype.  With split-K each z-slice of the grid writes fp32 partial
+// tiles and a second kernel sums the slices in a fixed order and applies the
+// same epilogue, which keeps results bitwise reproducible.
+#include "internal.h"
+
+namespace sgprs {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+struct IgemmArgs {
+    const unsigned char* x;
+    const unsigned char* w;
+    unsigned char* y;
+    const float* scale;
+    const float* shift;
+    const unsigned char* res;
+    float* partial;
+    int H, W, Cin, Cout, P, Q, S, stride, pad;
+    int M, PQ;
+    int ktiles, kt_per_split, cin_tiles;
+    int relu;
+};
+
+__device__ __forceinline__ float bf16_to_f32(unsigned short b) { return __uint_as_float((unsigned)b << 16); }
+__device__ __forceinline__ unsigned short f32_to_bf16(float f)
+{
+    __bf16 h = (__bf16)f;  // round to nearest even
+    return __builtin_bit_cast(unsigned short, h);
+}
+
+template <int DT> struct Store;
+template <> struct Store<SGPRS_F32> {
+    static __device__ __forceinline__ float load(const unsigned char* p, size_t i) { return ((const float*)p)[i]; }
+    static __device__ __forceinline__ void store(unsigned char* p, size_t i, float v) { ((float*)p)[i] = v; }
+};
+template <> struct Store<SGPRS_BF16> {
+    static __device__ __forceinline__ float load(const unsigned char* p, size_t i)
+    {
+        return bf16_to_f32(((const unsigned short*)p)[i]);
+    }
+    static __device__ __forceinline__ void store(unsigned char* p, size_t i, float v)
+    {
+        ((unsigned short*)p)[i] = f32_to_bf16(v);
+    }
+};
+
+__device__ __forceinline__ int swz(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
+
+template <int DT, int BM, int BN, int WM, int WN, bool SPLIT>
+__global__ __launch_bounds__(256) void conv_igemm_kernel(const IgemmArgs a)
+{
+    constexpr int ES = DT == SGPRS_BF16 ? 2 : 4;  // element size
+    constexpr int KT = 128 / ES;                  // elements per k-tile row
+    constexpr int CH = 16 / ES;                   // elements per 16-byte chunk
+    constexpr int WTM = BM / WM, WTN = BN / WN;   // wavefront tile
+    constexpr int TM = WTM / 32, TN = WTN / 32;   // 32x32 MFMA tiles per wavefront
+    constexpr int A_IT = BM / 32, B_IT = BN / 32; // rows loaded per thread
+    constexpr int STAGE = (BM + BN) * 128;
+    static_assert(WM * WN == 4 && TM >= 1 && TN >= 1, "tile shape");
+
+    extern __shared__ __align__(16) unsigned char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    const int kt_begin = blockIdx.z * a.kt_per_split;
+    const int kt_end = min(kt_begin + a.kt_per_split, a.ktiles);
+    const int K = a.ktiles * KT;
+
+    // ---- loader bookkeeping: this thread moves chunk lchunk of rows lrow+32*i
+    const int lchunk = tid & 7, lrow = tid >> 3;
+    int a_base[A_IT], a_h0[A_IT], a_w0[A_IT];
+#pragma unroll
+    for (int i = 0; i < A_IT; ++i) {
+        const int m = m0 + lrow + 32 * i;
+        if (m < a.M) {
+            const int n = m / a.PQ, rem = m - n * a.PQ;
+            const int p = rem / a.Q, q = rem - p * a.Q;
+            a_h0[i] = p * a.stride - a.pad;
+            a_w0[i] = q * a.stride - a.pad;
+            a_base[i] = ((n * a.H + a_h0[i]) * a.W + a_w0[i]) * a.Cin + lchunk * CH;
+        } else {
+            a_h0[i] = -(1 << 20);  // every tap falls outside the image
+            a_w0[i] = 0;
+            a_base[i] = 0;
+        }
+    }
+    const unsigned char* wrow = a.w + ((size_t)(n0 + lrow) * K + lchunk * CH) * ES;
+
+    u32x4_t areg[A_IT], breg[B_IT];
+    auto load_global = [&](int kt) {
+        const int tap = kt / a.cin_tiles;
+        const int c0 = (kt - tap * a.cin_tiles) * KT;
+        const int r = tap / a.S, s = tap - r * a.S;
+        const int tap_off = (r * a.W + s) * a.Cin + c0;
+#pragma unroll
+        for (int i = 0; i < A_IT; ++i) {
+            const int ih = a_h0[i] + r, iw = a_w0[i] + s;
+            const bool ok = (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+            u32x4_t v = {0u, 0u, 0u, 0u};
+            if (ok) v = *(const u32x4_t*)(a.x + (size_t)(a_base[i] + tap_off) * ES);
+            areg[i] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < B_IT; ++i)
+            breg[i] = *(const u32x4_t*)(wrow + ((size_t)i * 32 * K + (size_t)kt * KT) * ES);
+    };
+    auto store_lds = [&](int buf) {
+        unsigned char* As = smem + buf * STAGE;
+        unsigned char* Bs = As + BM * 128;
+#pragma unroll
+        for (int i = 0; i < A_IT; ++i) *(u32x4_t*)(As + swz(lrow + 32 * i, lchunk)) = areg[i];
+#pragma unroll
+        for (int i = 0; i < B_IT; ++i) *(u32x4_t*)(Bs + swz(lrow + 32 * i, lchunk)) = breg[i];
+    };
+
+    f32x16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    const int frow = lane & 31, fhalf = lane >> 5;
+
+    if (kt_begin < kt_end) {
+        load_global(kt_begin);
+        store_lds(0);
+    }
+    __syncthreads();
+    int buf = 0;
+    for (int kt = kt_begin; kt < kt_end; ++kt) {
+        const bool more = kt + 1 < kt_end;
+        if (more) load_global(kt + 1);
+        const unsigned char* As = smem + buf * STAGE;
+        const unsigned char* Bs = As + BM * 128;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const int chunk = 2 * ks + fhalf;
+            u32x4_t af[TM], bf[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) af[i] = *(const u32x4_t*)(As + swz(wm * WTM + i * 32 + frow, chunk));
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bf[j] = *(const u32x4_t*)(Bs + swz(wn * WTN + j * 32 + frow, chunk));
+            if constexpr (DT == SGPRS_BF16) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8_t, af[i]), __builtin_bit_cast(bf16x8_t, bf[j]),
+                            acc[i][j], 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                                __uint_as_float(af[i][u]), __uint_as_float(bf[j][u]), acc[i][j], 0, 0, 0);
+            }
+        }
+        if (more) store_lds(buf ^ 1);
+        __syncthreads();
+        buf ^= 1;
+    }
+
+    // ---- epilogue.  32x32 accumulator layout: column = lane % 32,
+    // row = 8*(e/4) + 4*(lane/32) + e%4 for register e.
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = n0 + wn * WTN + j * 32 + frow;
+        float sc = 1.f, sh = 0.f;
+        if constexpr (!SPLIT) { sc = a.scale[n]; sh = a.shift[n]; }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int m = m0 + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * fhalf + (e & 3);
+                if (m >= a.M) continue;
+                if constexpr (SPLIT) {
+                    a.partial[((size_t)blockIdx.z * a.M + m) * a.Cout + n] = acc[i][j][e];
+                } else {
+                    const size_t o = (size_t)m * a.Cout + n;
+                    float v = acc[i][j][e] * sc + sh;
+                    if (a.res) v += Store<DT>::load(a.res, o);
+                    if (a.relu) v = fmaxf(v, 0.f);
+                    Store<DT>::store(a.y, o, v);
+                }
+            }
+    }
+}
+
+// Second pass of split-K: sums the slices in index order, then scale/shift,
+// residual, ReLU.  One thread per 4 consecutive output channels.
+template <int DT>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int splits,
+                                                            size_t total, int Cout,
+                                                            const float* __restrict__ scale,
+                                                            const float* __restrict__ shift,
+                                                            const unsigned char* __restrict__ res,
+                                                            unsigned char* __restrict__ y, int relu)
+{
+    const size_t i4 = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i4 >= total) return;
+    f32x4_t s = *(const f32x4_t*)(partial + i4);
+    for (int z = 1; z < splits; ++z) {
+        const f32x4_t t = *(const f32x4_t*)(partial + (size_t)z * total + i4);
+        s += t;
+    }
+    const int n = (int)(i4 % Cout);
+    const f32x4_t sc = *(const f32x4_t*)(scale + n), sh = *(const f32x4_t*)(shift + n);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        float v = s[e] * sc[e] + sh[e];
+        if (res) v += Store<DT>::load(res, i4 + e);
+        if (relu) v = fmaxf(v, 0.f);
+        Store<DT>::store(y, i4 + e, v);
+    }
+}
+
+// ---- launch ----------------------------------------------------------------
+template <int DT, int BM, int BN, int WM, int WN>
+static int launch_variant(const IgemmArgs& a, const ConvPlan& p, hipStream_t stream)
+{
+    const dim3 grid(p.grid_m, p.grid_n, p.splits), block(256);
+    const size_t lds = 2 * (BM + BN) * 128;
+    if (p.splits > 1)
+        hipLaunchKernelGGL((conv_igemm_kernel<DT, BM, BN, WM, WN, true>), grid, block, lds, stream, a);
+    else
+        hipLaunchKernelGGL((conv_igemm_kernel<DT, BM, BN, WM, WN, false>), grid, block, lds, stream, a);
+    SGPRS_HIP(hipGetLastError());
+    return SGPRS_OK;
+}
+
+template <int DT>
+static int launch_dtype(const IgemmArgs& a, const ConvPlan& p, hipStream_t stream)
+{
+    switch (p.variant) {
+        case 0: return launch_variant<DT, 128, 128, 2, 2>(a, p, stream);
+        case 1: return launch_variant<DT, 128, 64, 2, 2>(a, p, stream);
+        case 2: return launch_variant<DT, 64, 64, 2, 2>(a, p, stream);
+        case 3: return launch_variant<DT, 32, 128, 1, 4>(a, p, stream);
+        default: return fail(SGPRS_ERR_INVALID_ARG, "bad igemm variant %d", p.variant);
+    }
+}
+
+const char* igemm_variant_name(int dtype, int variant)
+{
+    static const char* names[2][4] = {
+        {"conv_igemm_kernel<0, 128, 128, 2, 2", "conv_igemm_kernel<0, 128, 64, 2, 2",
+         "conv_igemm_kernel<0, 64, 64, 2, 2", "conv_igemm_kernel<0, 32, 128, 1, 4"},
+        {"conv_igemm_kernel<1, 128, 128, 2, 2", "conv_igemm_kernel<1, 128, 64, 2, 2",
+         "conv_igemm_kernel<1, 64, 64, 2, 2", "conv_igemm_kernel<1, 32, 128, 1, 4"}};
+    if (!dtype_ok(dtype) || variant < 0 || variant >= 4) return "?";
+    return names[dtype][variant];
+}
+
+int launch_conv(const sgprs_conv_desc_t& d, const void* x, const void* w, const float* scale,
+                const float* shift, const void* residual, void* y, void* ws, size_t ws_bytes,
+                hipStream_t stream, int cus, Profiler* prof)
+{
+    const ConvPlan p = plan_conv(d, cus);
+    if (p.bm == 0) return fail(SGPRS_ERR_UNSUPPORTED, "no tile shape fits cout %d", d.cout);
+    const size_t need = conv_workspace_bytes(d, p);
+    if (need > ws_bytes || (need && !ws))
+        return fail(SGPRS_ERR_INVALID_ARG, "split-K workspace %zu bytes needed, %zu given", need, ws_bytes);
+    const int es = (int)dtype_size(d.dtype), kt_el = 128 / es;
+    IgemmArgs a;
+    a.x = (const unsigned char*)x; a.w = (const unsigned char*)w; a.y = (unsigned char*)y;
+    a.scale = scale; a.shift = shift; a.res = (const unsigned char*)residual; a.partial = (float*)ws;
+    a.H = d.h; a.W = d.w; a.Cin = d.cin; a.Cout = d.cout;
+    a.P = out_dim(d.h, d.r, d.stride, d.pad); a.Q = out_dim(d.w, d.s, d.stride, d.pad);
+    a.S = d.s; a.stride = d.stride; a.pad = d.pad;
+    a.PQ = a.P * a.Q; a.M = d.n * a.PQ;
+    a.ktiles = p.ktiles; a.kt_per_split = (p.ktiles + p.splits - 1) / p.splits;
+    a.cin_tiles = d.cin / kt_el; a.relu = d.relu;
+    // host-side shape checks the kernel relies on
+    if (d.cin % kt_el || d.cout % p.bn || p.grid_m != (a.M + p.bm - 1) / p.bm || p.grid_n != d.cout / p.bn ||
+        (long long)(p.splits - 1) * a.kt_per_split >= p.ktiles)
+        return fail(SGPRS_ERR_INVALID_ARG, "internal: launch plan does not match the shape");
+    const double flops = 2.0 * a.M * d.cout * (double)d.r * d.s * d.cin;
+    const double bytes = ((double)d.n * d.h * d.w * d.cin + (double)d.cout * d.r * d.s * d.cin +
+                          (double)a.M * d.cout * (residual ? 2 : 1)) * es;
+    int rc;
+    if (prof && prof->on && (rc = prof->begin(stream, kKindIgemm, d.dtype * 4 + p.variant, flops, bytes))) return rc;
+    rc = d.dtype == SGPRS_BF16 ? launch_dtype<SGPRS_BF16>(a, p, stream) : launch_dtype<SGPRS_F32>(a, p, stream);
+    if (rc) return rc;
+    if (prof && prof->on && (rc = prof->end(stream))) return rc;
+    if (p.splits > 1) {
+        const size_t total = (size_t)a.M * d.cout;
+        const unsigned blocks = (unsigned)((total / 4 + 255) / 256);
+        if (prof && prof->on &&
+            (rc = prof->begin(stream, kKindReduce, d.dtype, 0.0, (double)total * 4.0 * p.splits + total * es)))
+            return rc;
+        if (d.dtype == SGPRS_BF16)
+            hipLaunchKernelGGL(splitk_reduce_kernel<SGPRS_BF16>, dim3(blocks), dim3(256), 0, stream, a.partial,
+                               p.splits, total, d.cout, scale, shift, a.res, a.y, d.relu);
+        else
+            hipLaunchKernelGGL(splitk_reduce_kernel<SGPRS_F32>, dim3(blocks), dim3(256), 0, stream, a.partial,
+                               p.splits, total, d.cout, scale, shift, a.res, a.y, d.relu);
+        SGPRS_HIP(hipGetLastError());
+        if (prof && prof->on && (rc = prof->end(stream))) return rc;
+    }
+    return SGPRS_OK;
+}
+
+}  // namespace sgprs

@@ -1,0 +1,141 @@
+// Internal declarations shared by the host and kernel translation units of
+// libsgprs.  Nothing here is part of the ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <string>
+#include <vector>
+
+#include "sgprs.h"
+
+namespace sgprs {
+
+// ---- error reporting -------------------------------------------------------
+int fail(int status, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
+#define SGPRS_HIP(call)                                                                   \
+    do {                                                                                  \
+        hipError_t e_ = (call);                                                           \
+        if (e_ != hipSuccess)                                                             \
+            return ::sgprs::fail(SGPRS_ERR_HIP, "%s failed: %s (%s:%d)", #call,           \
+                                 hipGetErrorString(e_), __FILE__, __LINE__);              \
+    } while (0)
+
+// ---- pool ------------------------------------------------------------------
+struct Partition {
+    hipStream_t stream = nullptr;
+    std::vector<uint32_t> mask;
+    int cus = 0;
+};
+
+}  // namespace sgprs
+
+struct sgprs_pool {
+    int device = 0;
+    int total_cus = 0;
+    int n_xcd = 1;
+    int cus_per_partition = 0;  // 0 when created from explicit masks of mixed size
+    std::vector<sgprs::Partition> parts;
+};
+
+namespace sgprs {
+
+// validates pool/partition, returns the stream and CU count
+int resolve(sgprs_pool_t* pool, int partition, hipStream_t* stream, int* cus);
+
+inline size_t dtype_size(int dtype) { return dtype == SGPRS_BF16 ? 2 : 4; }
+inline bool dtype_ok(int dtype) { return dtype == SGPRS_F32 || dtype == SGPRS_BF16; }
+
+// host bf16 conversion, round to nearest even
+inline uint16_t f32_to_bf16_bits(float f)
+{
+    uint32_t u;
+    __builtin_memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // quiet NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+inline float bf16_bits_to_f32(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    __builtin_memcpy(&f, &u, 4);
+    return f;
+}
+
+// ---- convolution -----------------------------------------------------------
+// Stem layout constants: 7 tap rows, each 7 taps x 4 channel slots (3 real
+// channels + 1 zero) = 28 elements padded to 32.
+constexpr int kStemTapRow = 32;
+constexpr int kStemK = 7 * kStemTapRow;  // 224
+
+inline bool is_stem(const sgprs_conv_desc_t& d)
+{
+    return d.cin == 3 && d.r == 7 && d.s == 7 && d.stride == 2 && d.pad == 3;
+}
+inline bool is_igemm(const sgprs_conv_desc_t& d)
+{
+    return d.cin % 32 == 0 && d.r == d.s && (d.r == 1 || d.r == 3) && (d.stride == 1 || d.stride == 2);
+}
+int check_conv_desc(const sgprs_conv_desc_t* d);
+inline int out_dim(int in, int k, int stride, int pad) { return (in + 2 * pad - k) / stride + 1; }
+
+// Tile configuration of one implicit-GEMM launch.
+struct ConvPlan {
+    int variant = 0;   // index into the tile table
+    int bm = 0, bn = 0;
+    int splits = 1;    // split-K factor (grid.z)
+    int ktiles = 0;    // total k-tiles of 128 bytes
+    int grid_m = 0, grid_n = 0;
+};
+// Chooses tile shape and split-K factor from the GEMM shape and the CU count of
+// the partition the launch will run on.
+ConvPlan plan_conv(const sgprs_conv_desc_t& d, int partition_cus);
+size_t conv_workspace_bytes(const sgprs_conv_desc_t& d, const ConvPlan& p);
+
+struct KernelRecord {
+    int kind = 0, variant = 0;
+    double flops = 0, bytes = 0;
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+// Optional per-launch timing hook: when non-null, launchers bracket each
+// kernel with events and append a record.
+struct Profiler {
+    bool on = false;
+    std::vector<KernelRecord> recs;      // records of the stage being run
+    std::vector<hipEvent_t> event_pool;  // reused events
+    size_t next_event = 0;
+    int begin(hipStream_t s, int kind, int variant, double flops, double bytes);
+    int end(hipStream_t s);
+    void reset() { recs.clear(); next_event = 0; }
+    ~Profiler();
+};
+
+enum KernelKind { kKindIgemm = 0, kKindStem = 1, kKindReduce = 2, kKindMaxpool = 3, kKindAvgpool = 4,
+                  kKindFc = 5, kKindBnRelu = 6, kKindAdd = 7 };
+
+// launchers (device pointers; validated by callers)
+int launch_conv(const sgprs_conv_desc_t& d, const void* x, const void* w, const float* scale,
+                const float* shift, const void* residual, void* y, void* ws, size_t ws_bytes,
+                hipStream_t stream, int cus, Profiler* prof);
+int launch_stem(const sgprs_conv_desc_t& d, const void* x, const void* w, const float* scale,
+                const float* shift, void* y, hipStream_t stream, int cus, Profiler* prof);
+int launch_maxpool(int dtype, int n, int h, int w, int c, const void* x, void* y, hipStream_t stream,
+                   int cus, Profiler* prof);
+int launch_bn_relu(int dtype, size_t pixels, int c, const void* x, const float* scale,
+                   const float* shift, void* y, hipStream_t stream, int cus, Profiler* prof);
+int launch_add_relu(int dtype, size_t count, const void* a, const void* b, void* y, int relu,
+                    hipStream_t stream, int cus, Profiler* prof);
+int launch_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void* x, const void* w,
+                      const float* bias, float* logits, float* ws, hipStream_t stream, int cus,
+                      Profiler* prof);
+int launch_probe(int n_blocks, int spin_cycles, uint32_t* out, hipStream_t stream);
+
+const char* igemm_variant_name(int dtype, int variant);
+int igemm_num_variants();
+
+}  // namespace sgprs

@@ -1,0 +1,120 @@
+// Per-operator entry points: argument validation, then enqueue on the
+// partition's stream.  A call that fails validation enqueues nothing.
+#include "internal.h"
+
+namespace sgprs {
+
+Profiler::~Profiler()
+{
+    for (hipEvent_t e : event_pool) (void)hipEventDestroy(e);
+}
+
+int Profiler::begin(hipStream_t s, int kind, int variant, double flops, double bytes)
+{
+    while (event_pool.size() < next_event + 2) {
+        hipEvent_t e;
+        SGPRS_HIP(hipEventCreate(&e));
+        event_pool.push_back(e);
+    }
+    KernelRecord r;
+    r.kind = kind; r.variant = variant; r.flops = flops; r.bytes = bytes;
+    r.start = event_pool[next_event++];
+    r.stop = event_pool[next_event++];
+    SGPRS_HIP(hipEventRecord(r.start, s));
+    recs.push_back(r);
+    return SGPRS_OK;
+}
+
+int Profiler::end(hipStream_t s)
+{
+    SGPRS_HIP(hipEventRecord(recs.back().stop, s));
+    return SGPRS_OK;
+}
+
+static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+}  // namespace sgprs
+
+using namespace sgprs;
+
+extern "C" {
+
+int sgprs_conv2d(const sgprs_conv_desc_t* d, const void* x, const void* w_packed, const float* scale,
+                 const float* shift, const void* residual, void* y, void* workspace, size_t workspace_bytes,
+                 sgprs_pool_t* pool, int partition)
+{
+    int rc = check_conv_desc(d);
+    if (rc) return rc;
+    hipStream_t stream;
+    int cus = 0;
+    if ((rc = resolve(pool, partition, &stream, &cus))) return rc;
+    if (!x || !w_packed || !scale || !shift || !y) return fail(SGPRS_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (!aligned16(x) || !aligned16(w_packed) || !aligned16(y) || !aligned16(residual) || !aligned16(scale) ||
+        !aligned16(shift) || !aligned16(workspace))
+        return fail(SGPRS_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    if (x == y || (residual && residual == y)) return fail(SGPRS_ERR_INVALID_ARG, "y must not alias x or residual");
+    if (is_stem(*d)) {
+        if (residual) return fail(SGPRS_ERR_UNSUPPORTED, "stem conv takes no residual");
+        return launch_stem(*d, x, w_packed, scale, shift, y, stream, cus, nullptr);
+    }
+    return launch_conv(*d, x, w_packed, scale, shift, residual, y, workspace, workspace_bytes, stream, cus, nullptr);
+}
+
+int sgprs_maxpool2d(int dtype, int n, int h, int w, int c, const void* x, void* y, sgprs_pool_t* pool,
+                    int partition)
+{
+    hipStream_t stream;
+    int cus = 0, rc;
+    if ((rc = resolve(pool, partition, &stream, &cus))) return rc;
+    if (!dtype_ok(dtype)) return fail(SGPRS_ERR_UNSUPPORTED, "dtype %d", dtype);
+    if (n <= 0 || h <= 0 || w <= 0 || c <= 0) return fail(SGPRS_ERR_INVALID_ARG, "non-positive dimension");
+    if (c % (dtype == SGPRS_BF16 ? 8 : 4)) return fail(SGPRS_ERR_UNSUPPORTED, "c %d not a multiple of the vector width", c);
+    if ((long long)n * h * w * c >= (1ll << 31)) return fail(SGPRS_ERR_UNSUPPORTED, "tensor with 2^31 or more elements");
+    if (!x || !y || !aligned16(x) || !aligned16(y) || x == y)
+        return fail(SGPRS_ERR_INVALID_ARG, "x and y must be distinct, non-NULL and 16-byte aligned");
+    return launch_maxpool(dtype, n, h, w, c, x, y, stream, cus, nullptr);
+}
+
+int sgprs_bn_relu(int dtype, size_t pixels, int c, const void* x, const float* scale, const float* shift,
+                  void* y, sgprs_pool_t* pool, int partition)
+{
+    hipStream_t stream;
+    int cus = 0, rc;
+    if ((rc = resolve(pool, partition, &stream, &cus))) return rc;
+    if (!dtype_ok(dtype)) return fail(SGPRS_ERR_UNSUPPORTED, "dtype %d", dtype);
+    if (pixels == 0 || c <= 0) return fail(SGPRS_ERR_INVALID_ARG, "empty tensor");
+    if (c % (dtype == SGPRS_BF16 ? 8 : 4)) return fail(SGPRS_ERR_UNSUPPORTED, "c %d not a multiple of the vector width", c);
+    if (!x || !y || !scale || !shift || !aligned16(x) || !aligned16(y))
+        return fail(SGPRS_ERR_INVALID_ARG, "pointers must be non-NULL and 16-byte aligned");
+    return launch_bn_relu(dtype, pixels, c, x, scale, shift, y, stream, cus, nullptr);
+}
+
+int sgprs_add_relu(int dtype, size_t count, const void* a, const void* b, void* y, int relu, sgprs_pool_t* pool,
+                   int partition)
+{
+    hipStream_t stream;
+    int cus = 0, rc;
+    if ((rc = resolve(pool, partition, &stream, &cus))) return rc;
+    if (!dtype_ok(dtype)) return fail(SGPRS_ERR_UNSUPPORTED, "dtype %d", dtype);
+    if (count == 0 || count % 8) return fail(SGPRS_ERR_INVALID_ARG, "count %zu must be a positive multiple of 8", count);
+    if (!a || !b || !y || !aligned16(a) || !aligned16(b) || !aligned16(y))
+        return fail(SGPRS_ERR_INVALID_ARG, "pointers must be non-NULL and 16-byte aligned");
+    return launch_add_relu(dtype, count, a, b, y, relu, stream, cus, nullptr);
+}
+
+int sgprs_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void* x, const void* w, const float* bias,
+                     float* logits, float* workspace, sgprs_pool_t* pool, int partition)
+{
+    hipStream_t stream;
+    int cus = 0, rc;
+    if ((rc = resolve(pool, partition, &stream, &cus))) return rc;
+    if (!dtype_ok(dtype)) return fail(SGPRS_ERR_UNSUPPORTED, "dtype %d", dtype);
+    if (n <= 0 || hw <= 0 || cout <= 0) return fail(SGPRS_ERR_INVALID_ARG, "non-positive dimension");
+    if (cin != 512 && cin != 1024 && cin != 2048)
+        return fail(SGPRS_ERR_UNSUPPORTED, "cin %d: supported are 512, 1024, 2048", cin);
+    if (!x || !w || !logits || !workspace || !aligned16(x) || !aligned16(w) || !aligned16(workspace))
+        return fail(SGPRS_ERR_INVALID_ARG, "pointers must be non-NULL and 16-byte aligned");
+    return launch_avgpool_fc(dtype, n, hw, cin, cout, x, w, bias, logits, workspace, stream, cus, nullptr);
+}
+
+}  // extern "C"

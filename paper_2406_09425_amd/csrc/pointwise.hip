@@ -1,0 +1,319 @@
+// Memory-bound operators of the ResNet18 stages: max pooling, folded BN+ReLU,
+// residual add, global average pool and the fully connected layer (the
+// "max pooling" and "other operations" of the paper's "GPU Speedup
+// Analysis"), plus the partition placement probe.  All of them move 16 bytes
+// per lane per access, coalesced along the NHWC channel axis; none of them is
+// a contraction worth the matrix cores except the batched FC, which is tiny.
+#include "internal.h"
+
+namespace sgprs {
+
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+// 16 bytes of activations as floats: 4 (fp32) or 8 (bf16) lanes.
+template <int DT> struct Vec;
+template <> struct Vec<SGPRS_F32> {
+    static constexpr int N = 4;
+    float v[4];
+    __device__ __forceinline__ void load(const void* p, size_t vec_index)
+    {
+        const f32x4_t t = ((const f32x4_t*)p)[vec_index];
+        v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
+    }
+    __device__ __forceinline__ void store(void* p, size_t vec_index) const
+    {
+        f32x4_t t = {v[0], v[1], v[2], v[3]};
+        ((f32x4_t*)p)[vec_index] = t;
+    }
+};
+template <> struct Vec<SGPRS_BF16> {
+    static constexpr int N = 8;
+    float v[8];
+    __device__ __forceinline__ void load(const void* p, size_t vec_index)
+    {
+        const u32x4_t t = ((const u32x4_t*)p)[vec_index];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(t[i] << 16);
+            v[2 * i + 1] = __uint_as_float(t[i] & 0xffff0000u);
+        }
+    }
+    __device__ __forceinline__ void store(void* p, size_t vec_index) const
+    {
+        u32x4_t t;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const __bf16 lo = (__bf16)v[2 * i], hi = (__bf16)v[2 * i + 1];  // nearest even
+            t[i] = (unsigned)__builtin_bit_cast(unsigned short, lo) |
+                   ((unsigned)__builtin_bit_cast(unsigned short, hi) << 16);
+        }
+        ((u32x4_t*)p)[vec_index] = t;
+    }
+};
+
+// ---- max pool 3x3 stride 2 pad 1 -------------------------------------------
+template <int DT>
+__global__ __launch_bounds__(256) void maxpool3x3s2_kernel(const void* __restrict__ x, void* __restrict__ y,
+                                                           int H, int W, int C, int P, int Q, size_t total_vec)
+{
+    constexpr int N = Vec<DT>::N;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total_vec) return;
+    const int cv = C / N;
+    const int c = (int)(idx % cv);
+    size_t pix = idx / cv;
+    const int q = (int)(pix % Q);
+    pix /= Q;
+    const int p = (int)(pix % P);
+    const int n = (int)(pix / P);
+    Vec<DT> m;
+#pragma unroll
+    for (int i = 0; i < N; ++i) m.v[i] = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+        const int ih = 2 * p - 1 + r;
+        if ((unsigned)ih >= (unsigned)H) continue;
+#pragma unroll
+        for (int s = 0; s < 3; ++s) {
+            const int iw = 2 * q - 1 + s;
+            if ((unsigned)iw >= (unsigned)W) continue;
+            Vec<DT> t;
+            t.load(x, ((size_t)(n * H + ih) * W + iw) * cv + c);
+#pragma unroll
+            for (int i = 0; i < N; ++i) m.v[i] = fmaxf(m.v[i], t.v[i]);
+        }
+    }
+    m.store(y, idx);
+}
+
+// ---- y = max(0, scale*x + shift) -------------------------------------------
+template <int DT>
+__global__ __launch_bounds__(256) void bn_relu_kernel(const void* __restrict__ x, void* __restrict__ y,
+                                                      const float* __restrict__ scale,
+                                                      const float* __restrict__ shift, int C, size_t total_vec)
+{
+    constexpr int N = Vec<DT>::N;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total_vec) return;
+    const int c0 = (int)(idx % (C / N)) * N;
+    Vec<DT> t;
+    t.load(x, idx);
+#pragma unroll
+    for (int i = 0; i < N; ++i) t.v[i] = fmaxf(t.v[i] * scale[c0 + i] + shift[c0 + i], 0.f);
+    t.store(y, idx);
+}
+
+// ---- y = a + b (ReLU optional) ---------------------------------------------
+template <int DT>
+__global__ __launch_bounds__(256) void add_relu_kernel(const void* __restrict__ a, const void* __restrict__ b,
+                                                       void* __restrict__ y, int relu, size_t total_vec)
+{
+    constexpr int N = Vec<DT>::N;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total_vec) return;
+    Vec<DT> s, t;
+    s.load(a, idx);
+    t.load(b, idx);
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        s.v[i] += t.v[i];
+        if (relu) s.v[i] = fmaxf(s.v[i], 0.f);
+    }
+    s.store(y, idx);
+}
+
+// ---- global average pool: x [n][hw][c] -> v [n][c] fp32 ---------------------
+template <int DT>
+__global__ __launch_bounds__(256) void avgpool_kernel(const void* __restrict__ x, float* __restrict__ v, int HW,
+                                                      int C, size_t total_vec)
+{
+    constexpr int N = Vec<DT>::N;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total_vec) return;
+    const int cv = C / N;
+    const int c = (int)(idx % cv);
+    const size_t n = idx / cv;
+    float s[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) s[i] = 0.f;
+    for (int j = 0; j < HW; ++j) {
+        Vec<DT> t;
+        t.load(x, (n * HW + j) * cv + c);
+#pragma unroll
+        for (int i = 0; i < N; ++i) s[i] += t.v[i];
+    }
+    const float hw = (float)HW;
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[(n * cv + c) * N + i] = s[i] / hw;
+}
+
+// ---- FC: logits[n][o] = sum_c w[o][c] v[n][c] + b[o] ------------------------
+// One wavefront per output row o; its weights stay in registers (8 per lane per
+// 512 inputs) while it walks a chunk of images; wavefront reduction by
+// cross-lane shuffles.
+template <int DT, int CPL /* 512-element passes */>
+__global__ __launch_bounds__(256) void fc_kernel(const float* __restrict__ v, const void* __restrict__ w,
+                                                 const float* __restrict__ bias, float* __restrict__ y, int Nimg,
+                                                 int Cin, int Cout, int img_per_block)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int o = blockIdx.x * 4 + wave;
+    if (o >= Cout) return;
+    float wr[CPL][8];
+#pragma unroll
+    for (int j = 0; j < CPL; ++j) {
+        const size_t e0 = (size_t)o * Cin + j * 512 + lane * 8;
+        if constexpr (DT == SGPRS_BF16) {
+            Vec<SGPRS_BF16> t;
+            t.load(w, e0 / 8);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) wr[j][i] = t.v[i];
+        } else {
+            Vec<SGPRS_F32> t0, t1;
+            t0.load(w, e0 / 4);
+            t1.load(w, e0 / 4 + 1);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { wr[j][i] = t0.v[i]; wr[j][4 + i] = t1.v[i]; }
+        }
+    }
+    const float b = bias ? bias[o] : 0.f;
+    const int n_begin = blockIdx.y * img_per_block;
+    const int n_end = min(n_begin + img_per_block, Nimg);
+    for (int n = n_begin; n < n_end; ++n) {
+        float s = 0.f;
+#pragma unroll
+        for (int j = 0; j < CPL; ++j) {
+            const f32x4_t* vp = (const f32x4_t*)(v + (size_t)n * Cin + j * 512 + lane * 8);
+            const f32x4_t v0 = vp[0], v1 = vp[1];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) s += wr[j][i] * v0[i];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) s += wr[j][4 + i] * v1[i];
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
+        if (lane == 0) y[(size_t)n * Cout + o] = s + b;
+    }
+}
+
+// ---- placement probe --------------------------------------------------------
+__global__ __launch_bounds__(64) void probe_kernel(uint32_t* out, int spin)
+{
+    const long long t0 = clock64();
+    while (clock64() - t0 < (long long)spin) {}
+    if (threadIdx.x == 0) {
+        out[2 * blockIdx.x] = __builtin_amdgcn_s_getreg((3 << 11) | 20);      // XCC_ID[3:0]
+        out[2 * blockIdx.x + 1] = __builtin_amdgcn_s_getreg((31 << 11) | 4);  // HW_ID
+    }
+}
+
+// ---- launchers --------------------------------------------------------------
+#define PROF_BEGIN(kind, variant, flops, bytes)                                                     \
+    do {                                                                                            \
+        int rc_ = SGPRS_OK;                                                                         \
+        if (prof && prof->on && (rc_ = prof->begin(stream, kind, variant, flops, bytes))) return rc_; \
+    } while (0)
+#define PROF_END()                                                          \
+    do {                                                                    \
+        int rc_ = SGPRS_OK;                                                 \
+        if (prof && prof->on && (rc_ = prof->end(stream))) return rc_;      \
+    } while (0)
+
+static unsigned blocks_for(size_t n) { return (unsigned)((n + 255) / 256); }
+
+int launch_maxpool(int dtype, int n, int h, int w, int c, const void* x, void* y, hipStream_t stream, int,
+                   Profiler* prof)
+{
+    const int P = (h - 1) / 2 + 1, Q = (w - 1) / 2 + 1;
+    const int vec = dtype == SGPRS_BF16 ? 8 : 4;
+    const size_t total = (size_t)n * P * Q * (c / vec);
+    const double bytes = ((double)n * h * w * c + (double)n * P * Q * c) * dtype_size(dtype);
+    PROF_BEGIN(kKindMaxpool, dtype, 0.0, bytes);
+    if (dtype == SGPRS_BF16)
+        hipLaunchKernelGGL(maxpool3x3s2_kernel<SGPRS_BF16>, dim3(blocks_for(total)), dim3(256), 0, stream, x, y, h, w,
+                           c, P, Q, total);
+    else
+        hipLaunchKernelGGL(maxpool3x3s2_kernel<SGPRS_F32>, dim3(blocks_for(total)), dim3(256), 0, stream, x, y, h, w,
+                           c, P, Q, total);
+    SGPRS_HIP(hipGetLastError());
+    PROF_END();
+    return SGPRS_OK;
+}
+
+int launch_bn_relu(int dtype, size_t pixels, int c, const void* x, const float* scale, const float* shift,
+                   void* y, hipStream_t stream, int, Profiler* prof)
+{
+    const int vec = dtype == SGPRS_BF16 ? 8 : 4;
+    const size_t total = pixels * (c / vec);
+    PROF_BEGIN(kKindBnRelu, dtype, 2.0 * pixels * c, 2.0 * pixels * c * dtype_size(dtype));
+    if (dtype == SGPRS_BF16)
+        hipLaunchKernelGGL(bn_relu_kernel<SGPRS_BF16>, dim3(blocks_for(total)), dim3(256), 0, stream, x, y, scale,
+                           shift, c, total);
+    else
+        hipLaunchKernelGGL(bn_relu_kernel<SGPRS_F32>, dim3(blocks_for(total)), dim3(256), 0, stream, x, y, scale,
+                           shift, c, total);
+    SGPRS_HIP(hipGetLastError());
+    PROF_END();
+    return SGPRS_OK;
+}
+
+int launch_add_relu(int dtype, size_t count, const void* a, const void* b, void* y, int relu,
+                    hipStream_t stream, int, Profiler* prof)
+{
+    const int vec = dtype == SGPRS_BF16 ? 8 : 4;
+    const size_t total = count / vec;
+    PROF_BEGIN(kKindAdd, dtype, (double)count, 3.0 * count * dtype_size(dtype));
+    if (dtype == SGPRS_BF16)
+        hipLaunchKernelGGL(add_relu_kernel<SGPRS_BF16>, dim3(blocks_for(total)), dim3(256), 0, stream, a, b, y, relu,
+                           total);
+    else
+        hipLaunchKernelGGL(add_relu_kernel<SGPRS_F32>, dim3(blocks_for(total)), dim3(256), 0, stream, a, b, y, relu,
+                           total);
+    SGPRS_HIP(hipGetLastError());
+    PROF_END();
+    return SGPRS_OK;
+}
+
+int launch_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void* x, const void* w,
+                      const float* bias, float* logits, float* ws, hipStream_t stream, int, Profiler* prof)
+{
+    const int vec = dtype == SGPRS_BF16 ? 8 : 4;
+    const size_t es = dtype_size(dtype);
+    const size_t total = (size_t)n * (cin / vec);
+    PROF_BEGIN(kKindAvgpool, dtype, (double)n * hw * cin, (double)n * hw * cin * es + (double)n * cin * 4);
+    if (dtype == SGPRS_BF16)
+        hipLaunchKernelGGL(avgpool_kernel<SGPRS_BF16>, dim3(blocks_for(total)), dim3(256), 0, stream, x, ws, hw, cin,
+                           total);
+    else
+        hipLaunchKernelGGL(avgpool_kernel<SGPRS_F32>, dim3(blocks_for(total)), dim3(256), 0, stream, x, ws, hw, cin,
+                           total);
+    SGPRS_HIP(hipGetLastError());
+    PROF_END();
+
+    const int img_per_block = 16;
+    const dim3 grid((cout + 3) / 4, (n + img_per_block - 1) / img_per_block);
+    const int cpl = cin / 512;
+    PROF_BEGIN(kKindFc, dtype, 2.0 * n * cin * cout, (double)cin * cout * es + (double)n * (cin + cout) * 4);
+#define FC_LAUNCH(DT, CPL)                                                                                  \
+    hipLaunchKernelGGL((fc_kernel<DT, CPL>), grid, dim3(256), 0, stream, (const float*)ws, w, bias, logits, n, cin, \
+                       cout, img_per_block)
+    if (dtype == SGPRS_BF16) {
+        if (cpl == 1) FC_LAUNCH(SGPRS_BF16, 1); else if (cpl == 2) FC_LAUNCH(SGPRS_BF16, 2); else FC_LAUNCH(SGPRS_BF16, 4);
+    } else {
+        if (cpl == 1) FC_LAUNCH(SGPRS_F32, 1); else if (cpl == 2) FC_LAUNCH(SGPRS_F32, 2); else FC_LAUNCH(SGPRS_F32, 4);
+    }
+#undef FC_LAUNCH
+    SGPRS_HIP(hipGetLastError());
+    PROF_END();
+    return SGPRS_OK;
+}
+
+int launch_probe(int n_blocks, int spin_cycles, uint32_t* out, hipStream_t stream)
+{
+    hipLaunchKernelGGL(probe_kernel, dim3(n_blocks), dim3(64), 0, stream, out, spin_cycles);
+    SGPRS_HIP(hipGetLastError());
+    return SGPRS_OK;
+}
+
+}  // namespace sgprs

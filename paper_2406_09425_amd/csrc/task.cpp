@@ -1,0 +1,387 @@
+// Task tau_i = one ResNet18 instance and its six stages tau_i^0..5 (paper,
+// "Task Model" and "Simulation Results": ResNet18 on a 224x224 input, each
+// task divided into six stages).  Creating the task is the offline phase
+// (fold BN, round, pack, upload); sgprs_stage_run / sgprs_task_run only
+// enqueue kernels on partition streams.
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "internal.h"
+
+namespace {
+
+using namespace sgprs;
+
+// cin, cout, kernel, stride, pad, input height -- forward order
+struct ConvSpec { int cin, cout, k, stride, pad, h; };
+const ConvSpec kConvs[SGPRS_RESNET18_CONVS] = {
+    {3, 64, 7, 2, 3, 224},
+    {64, 64, 3, 1, 1, 56},   {64, 64, 3, 1, 1, 56},   {64, 64, 3, 1, 1, 56},   {64, 64, 3, 1, 1, 56},
+    {64, 128, 3, 2, 1, 56},  {128, 128, 3, 1, 1, 28}, {64, 128, 1, 2, 0, 56},  {128, 128, 3, 1, 1, 28}, {128, 128, 3, 1, 1, 28},
+    {128, 256, 3, 2, 1, 28}, {256, 256, 3, 1, 1, 14}, {128, 256, 1, 2, 0, 28}, {256, 256, 3, 1, 1, 14}, {256, 256, 3, 1, 1, 14},
+    {256, 512, 3, 2, 1, 14}, {512, 512, 3, 1, 1, 7},  {256, 512, 1, 2, 0, 14}, {512, 512, 3, 1, 1, 7},  {512, 512, 3, 1, 1, 7},
+};
+// per-image C,H,W at each stage boundary: [j] = input of stage j, [j+1] = its output
+const int kStageDims[7][3] = {{3, 224, 224}, {64, 56, 56}, {64, 56, 56}, {128, 28, 28},
+                              {256, 14, 14}, {512, 7, 7},  {1000, 1, 1}};
+constexpr int kFcIn = 512, kFcOut = 1000;
+
+struct ConvLayer {
+    sgprs_conv_desc_t d;
+    void* w = nullptr;
+    float* scale = nullptr;
+    float* shift = nullptr;
+};
+
+}  // namespace
+
+struct sgprs_task {
+    int device = 0, dtype = 0, max_batch = 0;
+    ConvLayer conv[SGPRS_RESNET18_CONVS];
+    void* fc_w = nullptr;
+    float* fc_b = nullptr;
+    void* stem_out = nullptr;
+    void* tmp[3] = {nullptr, nullptr, nullptr};
+    void* stage_out[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+    float* pooled = nullptr;
+    void* splitk = nullptr;
+    size_t splitk_bytes = 0;
+    std::vector<void*> allocs;
+    sgprs::Profiler prof[SGPRS_RESNET18_STAGES];
+    bool profiling = false;
+    hipEvent_t chain[SGPRS_RESNET18_STAGES] = {};
+};
+
+namespace {
+
+int dev_alloc(sgprs_task* t, size_t bytes, void** out)
+{
+    void* p = nullptr;
+    hipError_t e = hipMalloc(&p, bytes ? bytes : 16);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(e == hipErrorOutOfMemory ? SGPRS_ERR_OOM : SGPRS_ERR_HIP, "hipMalloc(%zu): %s", bytes,
+                    hipGetErrorString(e));
+    }
+    t->allocs.push_back(p);
+    *out = p;
+    return SGPRS_OK;
+}
+
+int upload(sgprs_task* t, const void* host, size_t bytes, void** out)
+{
+    int rc = dev_alloc(t, bytes, out);
+    if (rc) return rc;
+    SGPRS_HIP(hipMemcpy(*out, host, bytes, hipMemcpyHostToDevice));
+    return SGPRS_OK;
+}
+
+void destroy_task(sgprs_task* t)
+{
+    for (void* p : t->allocs) (void)hipFree(p);
+    if (t->splitk) (void)hipFree(t->splitk);
+    for (hipEvent_t e : t->chain)
+        if (e) (void)hipEventDestroy(e);
+    delete t;
+}
+
+size_t splitk_need(const sgprs_task* t, int first, int last, int batch, int cus)
+{
+    size_t need = 0;
+    for (int i = first; i <= last; ++i) {
+        if (is_stem(t->conv[i].d)) continue;
+        sgprs_conv_desc_t d = t->conv[i].d;
+        d.n = batch;
+        need = std::max(need, conv_workspace_bytes(d, plan_conv(d, cus)));
+    }
+    return need;
+}
+
+// Grows the split-K scratch if this (batch, partition size) needs more than
+// any earlier run.  Growing waits for the stream and reallocates, so it only
+// happens on the first run of a new shape.
+int ensure_splitk(sgprs_task* t, size_t need, hipStream_t stream)
+{
+    if (need <= t->splitk_bytes) return SGPRS_OK;
+    SGPRS_HIP(hipStreamSynchronize(stream));
+    if (t->splitk) SGPRS_HIP(hipFree(t->splitk));
+    t->splitk = nullptr;
+    t->splitk_bytes = 0;
+    hipError_t e = hipMalloc(&t->splitk, need);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(SGPRS_ERR_OOM, "hipMalloc(%zu) for split-K scratch: %s", need, hipGetErrorString(e));
+    }
+    t->splitk_bytes = need;
+    return SGPRS_OK;
+}
+
+int run_conv(sgprs_task* t, int i, int batch, const void* x, const void* res, void* y, int relu, hipStream_t s,
+             int cus, Profiler* prof)
+{
+    sgprs_conv_desc_t d = t->conv[i].d;
+    d.n = batch;
+    d.relu = relu;
+    if (is_stem(d)) return launch_stem(d, x, t->conv[i].w, t->conv[i].scale, t->conv[i].shift, y, s, cus, prof);
+    return launch_conv(d, x, t->conv[i].w, t->conv[i].scale, t->conv[i].shift, res, y, t->splitk, t->splitk_bytes, s,
+                       cus, prof);
+}
+
+// BasicBlock: out = ReLU(BN2(conv2(ReLU(BN1(conv1(x))))) + shortcut(x)); the
+// shortcut is x or BN(conv1x1/2(x)).  BN, the add and both ReLUs are fused
+// into the convolutions' epilogues.
+int run_block(sgprs_task* t, int c1, int c2, int down, int batch, const void* x, void* out, hipStream_t s, int cus,
+              Profiler* prof)
+{
+    int rc;
+    if ((rc = run_conv(t, c1, batch, x, nullptr, t->tmp[0], 1, s, cus, prof))) return rc;
+    const void* shortcut = x;
+    if (down >= 0) {
+        if ((rc = run_conv(t, down, batch, x, nullptr, t->tmp[1], 0, s, cus, prof))) return rc;
+        shortcut = t->tmp[1];
+    }
+    return run_conv(t, c2, batch, t->tmp[0], shortcut, out, 1, s, cus, prof);
+}
+
+int run_stage(sgprs_task* t, int j, int batch, const void* in, void* out, hipStream_t s, int cus)
+{
+    Profiler* prof = &t->prof[j];
+    prof->on = t->profiling;
+    prof->reset();
+    int rc;
+    if (j == 0) {
+        if ((rc = run_conv(t, 0, batch, in, nullptr, t->stem_out, 1, s, cus, prof))) return rc;
+        return launch_maxpool(t->dtype, batch, 112, 112, 64, t->stem_out, out, s, cus, prof);
+    }
+    if (j == 5)
+        return launch_avgpool_fc(t->dtype, batch, 49, kFcIn, kFcOut, in, t->fc_w, t->fc_b, (float*)out, t->pooled, s,
+                                 cus, prof);
+    const int first = j == 1 ? 1 : 5 + 5 * (j - 2);
+    const int last = j == 1 ? 4 : first + 4;
+    if ((rc = ensure_splitk(t, splitk_need(t, first, last, batch, cus), s))) return rc;
+    if (j == 1) {
+        if ((rc = run_block(t, 1, 2, -1, batch, in, t->tmp[2], s, cus, prof))) return rc;
+        return run_block(t, 3, 4, -1, batch, t->tmp[2], out, s, cus, prof);
+    }
+    if ((rc = run_block(t, first, first + 1, first + 2, batch, in, t->tmp[2], s, cus, prof))) return rc;
+    return run_block(t, first + 3, first + 4, -1, batch, t->tmp[2], out, s, cus, prof);
+}
+
+size_t stage_bytes(const sgprs_task* t, int boundary, int batch)
+{
+    const int* d = kStageDims[boundary];
+    const size_t el = (size_t)batch * d[0] * d[1] * d[2];
+    return el * (boundary == 6 ? sizeof(float) : dtype_size(t->dtype));
+}
+
+int check_task_call(const sgprs_task* t, int stage, int batch)
+{
+    if (!t) return fail(SGPRS_ERR_INVALID_ARG, "task is NULL");
+    if (stage < 0 || stage >= SGPRS_RESNET18_STAGES)
+        return fail(SGPRS_ERR_INVALID_ARG, "stage %d outside [0,%d)", stage, SGPRS_RESNET18_STAGES);
+    if (batch <= 0 || batch > t->max_batch)
+        return fail(SGPRS_ERR_INVALID_ARG, "batch %d outside [1,%d]", batch, t->max_batch);
+    return SGPRS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sgprs_task_create_resnet18(int device, int dtype, int max_batch, const sgprs_resnet18_params_t* hp,
+                               sgprs_task_t** out)
+{
+    if (!out) return fail(SGPRS_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (!hp) return fail(SGPRS_ERR_INVALID_ARG, "host_params is NULL");
+    if (!dtype_ok(dtype)) return fail(SGPRS_ERR_UNSUPPORTED, "dtype %d", dtype);
+    if (max_batch <= 0 || max_batch > 512) return fail(SGPRS_ERR_INVALID_ARG, "max_batch %d outside [1,512]", max_batch);
+    for (int i = 0; i < SGPRS_RESNET18_CONVS; ++i)
+        if (!hp->conv_w[i] || !hp->bn_gamma[i] || !hp->bn_beta[i] || !hp->bn_mean[i] || !hp->bn_var[i])
+            return fail(SGPRS_ERR_INVALID_ARG, "NULL parameter pointer for conv %d", i);
+    if (!hp->fc_w) return fail(SGPRS_ERR_INVALID_ARG, "fc_w is NULL");
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) {
+        (void)hipGetLastError();
+        return fail(SGPRS_ERR_NO_DEVICE, "no HIP device available");
+    }
+    if (device < 0 || device >= ndev) return fail(SGPRS_ERR_INVALID_ARG, "device %d outside [0,%d)", device, ndev);
+    SGPRS_HIP(hipSetDevice(device));
+
+    sgprs_task* t = new (std::nothrow) sgprs_task;
+    if (!t) return fail(SGPRS_ERR_OOM, "out of host memory");
+    t->device = device; t->dtype = dtype; t->max_batch = max_batch;
+    int rc = SGPRS_OK;
+    std::vector<unsigned char> packed;
+    std::vector<float> scale, shift;
+    for (int i = 0; i < SGPRS_RESNET18_CONVS && !rc; ++i) {
+        const ConvSpec& cs = kConvs[i];
+        sgprs_conv_desc_t& d = t->conv[i].d;
+        d.n = max_batch; d.h = cs.h; d.w = cs.h; d.cin = cs.cin; d.cout = cs.cout; d.r = cs.k; d.s = cs.k;
+        d.stride = cs.stride; d.pad = cs.pad; d.dtype = dtype; d.relu = 0;
+        size_t bytes = 0;
+        if ((rc = sgprs_conv_packed_weight_bytes(&d, &bytes))) break;
+        packed.resize(bytes);
+        if ((rc = sgprs_pack_conv_weights(&d, hp->conv_w[i], packed.data(), bytes))) break;
+        scale.resize(cs.cout); shift.resize(cs.cout);
+        if ((rc = sgprs_fold_bn(hp->bn_gamma[i], hp->bn_beta[i], hp->bn_mean[i], hp->bn_var[i], hp->bn_eps, cs.cout,
+                                scale.data(), shift.data())))
+            break;
+        if ((rc = upload(t, packed.data(), bytes, &t->conv[i].w))) break;
+        if ((rc = upload(t, scale.data(), cs.cout * sizeof(float), (void**)&t->conv[i].scale))) break;
+        rc = upload(t, shift.data(), cs.cout * sizeof(float), (void**)&t->conv[i].shift);
+    }
+    if (!rc) {
+        const size_t n = (size_t)kFcOut * kFcIn;
+        if (dtype == SGPRS_BF16) {
+            std::vector<uint16_t> w16(n);
+            for (size_t i = 0; i < n; ++i) w16[i] = f32_to_bf16_bits(hp->fc_w[i]);
+            rc = upload(t, w16.data(), n * 2, &t->fc_w);
+        } else {
+            rc = upload(t, hp->fc_w, n * 4, &t->fc_w);
+        }
+    }
+    if (!rc && hp->fc_b) rc = upload(t, hp->fc_b, kFcOut * sizeof(float), (void**)&t->fc_b);
+    const size_t es = dtype_size(dtype);
+    if (!rc) rc = dev_alloc(t, (size_t)max_batch * 112 * 112 * 64 * es, &t->stem_out);
+    for (int i = 0; i < 3 && !rc; ++i) rc = dev_alloc(t, (size_t)max_batch * 56 * 56 * 64 * es, &t->tmp[i]);
+    for (int j = 0; j < 5 && !rc; ++j) rc = dev_alloc(t, stage_bytes(t, j + 1, max_batch), &t->stage_out[j]);
+    if (!rc) rc = dev_alloc(t, (size_t)max_batch * kFcIn * sizeof(float), (void**)&t->pooled);
+    if (!rc) {
+        int total = 0;
+        if (hipDeviceGetAttribute(&total, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) total = 256;
+        size_t need = 0;
+        for (int cus = 8; cus <= total; cus += 8)
+            for (int b : {1, max_batch}) need = std::max(need, splitk_need(t, 1, SGPRS_RESNET18_CONVS - 1, b, cus));
+        if (need) rc = ensure_splitk(t, need, nullptr);
+    }
+    for (int j = 0; j < SGPRS_RESNET18_STAGES && !rc; ++j)
+        if (hipEventCreateWithFlags(&t->chain[j], hipEventDisableTiming) != hipSuccess)
+            rc = fail(SGPRS_ERR_HIP, "hipEventCreate failed");
+    if (rc) {
+        destroy_task(t);
+        return rc;
+    }
+    *out = t;
+    return SGPRS_OK;
+}
+
+int sgprs_task_destroy(sgprs_task_t* t)
+{
+    if (!t) return fail(SGPRS_ERR_INVALID_ARG, "task is NULL");
+    (void)hipDeviceSynchronize();
+    destroy_task(t);
+    return SGPRS_OK;
+}
+
+int sgprs_task_num_stages(const sgprs_task_t* t)
+{
+    if (!t) return fail(SGPRS_ERR_INVALID_ARG, "task is NULL");
+    return SGPRS_RESNET18_STAGES;
+}
+
+int sgprs_task_stage_io(const sgprs_task_t* t, int stage, int batch, size_t* in_bytes, size_t* out_bytes,
+                        int in_nchw[4], int out_nchw[4])
+{
+    int rc = check_task_call(t, stage, batch);
+    if (rc) return rc;
+    if (in_bytes) *in_bytes = stage_bytes(t, stage, batch);
+    if (out_bytes) *out_bytes = stage_bytes(t, stage + 1, batch);
+    if (in_nchw) { in_nchw[0] = batch; for (int i = 0; i < 3; ++i) in_nchw[1 + i] = kStageDims[stage][i]; }
+    if (out_nchw) { out_nchw[0] = batch; for (int i = 0; i < 3; ++i) out_nchw[1 + i] = kStageDims[stage + 1][i]; }
+    return SGPRS_OK;
+}
+
+int sgprs_stage_run(sgprs_task_t* t, int stage, int batch, const void* in, void* out, sgprs_pool_t* pool,
+                    int partition)
+{
+    int rc = check_task_call(t, stage, batch);
+    if (rc) return rc;
+    hipStream_t s;
+    int cus = 0;
+    if ((rc = resolve(pool, partition, &s, &cus))) return rc;
+    if (!in || !out || ((uintptr_t)in & 15) || ((uintptr_t)out & 15) || in == out)
+        return fail(SGPRS_ERR_INVALID_ARG, "in and out must be distinct, non-NULL and 16-byte aligned");
+    if (pool->device != t->device) return fail(SGPRS_ERR_INVALID_ARG, "pool and task live on different devices");
+    return run_stage(t, stage, batch, in, out, s, cus);
+}
+
+int sgprs_task_run(sgprs_task_t* t, int batch, const void* in, float* logits, sgprs_pool_t* pool, int partition,
+                   const int* pps)
+{
+    int rc = check_task_call(t, 0, batch);
+    if (rc) return rc;
+    if (!in || !logits || ((uintptr_t)in & 15) || ((uintptr_t)logits & 15))
+        return fail(SGPRS_ERR_INVALID_ARG, "in and logits must be non-NULL and 16-byte aligned");
+    hipStream_t s[SGPRS_RESNET18_STAGES];
+    int cus[SGPRS_RESNET18_STAGES];
+    for (int j = 0; j < SGPRS_RESNET18_STAGES; ++j)
+        if ((rc = resolve(pool, pps ? pps[j] : partition, &s[j], &cus[j]))) return rc;
+    if (pool->device != t->device) return fail(SGPRS_ERR_INVALID_ARG, "pool and task live on different devices");
+    for (int j = 0; j < SGPRS_RESNET18_STAGES; ++j) {
+        if (j > 0 && s[j] != s[j - 1]) {
+            SGPRS_HIP(hipEventRecord(t->chain[j], s[j - 1]));
+            SGPRS_HIP(hipStreamWaitEvent(s[j], t->chain[j], 0));
+        }
+        const void* src = j == 0 ? in : t->stage_out[j - 1];
+        void* dst = j == 5 ? (void*)logits : t->stage_out[j];
+        if ((rc = run_stage(t, j, batch, src, dst, s[j], cus[j]))) return rc;
+    }
+    return SGPRS_OK;
+}
+
+const void* sgprs_task_stage_output(const sgprs_task_t* t, int stage)
+{
+    if (!t || stage < 0 || stage > 4) {
+        fail(SGPRS_ERR_INVALID_ARG, "stage %d outside [0,4] or task NULL", stage);
+        return nullptr;
+    }
+    return t->stage_out[stage];
+}
+
+int sgprs_task_set_profiling(sgprs_task_t* t, int on)
+{
+    if (!t) return fail(SGPRS_ERR_INVALID_ARG, "task is NULL");
+    t->profiling = on != 0;
+    return SGPRS_OK;
+}
+
+int sgprs_task_kernel_times(sgprs_task_t* t, int stage, int* count, int* kind, int* variant, float* ms,
+                            double* flops, double* bytes)
+{
+    int rc = check_task_call(t, stage, 1);
+    if (rc) return rc;
+    if (!count) return fail(SGPRS_ERR_INVALID_ARG, "count is NULL");
+    const auto& recs = t->prof[stage].recs;
+    const int cap = *count;
+    *count = (int)recs.size();
+    if (cap < (int)recs.size()) return fail(SGPRS_ERR_INVALID_ARG, "room for %d records, %d needed", cap, *count);
+    for (size_t i = 0; i < recs.size(); ++i) {
+        float t_ms = 0.f;
+        SGPRS_HIP(hipEventElapsedTime(&t_ms, recs[i].start, recs[i].stop));
+        if (kind) kind[i] = recs[i].kind;
+        if (variant) variant[i] = recs[i].variant;
+        if (ms) ms[i] = t_ms;
+        if (flops) flops[i] = recs[i].flops;
+        if (bytes) bytes[i] = recs[i].bytes;
+    }
+    return SGPRS_OK;
+}
+
+const char* sgprs_kernel_name(int kind, int variant)
+{
+    switch (kind) {
+        case kKindIgemm: return igemm_variant_name(variant / 4, variant % 4);
+        case kKindStem: return "conv_stem_kernel";
+        case kKindReduce: return "splitk_reduce_kernel";
+        case kKindMaxpool: return "maxpool3x3s2_kernel";
+        case kKindAvgpool: return "avgpool_kernel";
+        case kKindFc: return "fc_kernel";
+        case kKindBnRelu: return "bn_relu_kernel";
+        case kKindAdd: return "add_relu_kernel";
+        default: return "?";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,135 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every
+declared symbol, and its host-side logic (masks, BN folding, packing,
+planning, validation) behaves.  No compute call is made."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2406_09425_amd as S
+from workloads import BN_EPS, make_bn, make_conv_weight
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    src = open(os.path.join(ROOT, "include", "sgprs.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(sgprs_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = S.lib()
+    names = declared_symbols()
+    assert len(names) >= 30
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in sgprs.h but not exported"
+
+
+def test_status_strings_and_version():
+    assert S.sgprs_version() >= 100
+    assert S.sgprs_status_string(0) == "ok"
+    assert "device" in S.sgprs_status_string(-2)
+
+
+def test_cu_mask_builder_interleaved_and_blocked():
+    for cus in (8, 16, 32, 64, 128, 256):
+        n_p = 256 // cus
+        acc = np.zeros(8, dtype=np.uint32)
+        for p in range(n_p):
+            m = S.sgprs_build_cu_mask(256, 8, cus, p)
+            assert sum(bin(int(w)).count("1") for w in m) == cus
+            assert not np.any(acc & m)
+            acc |= m
+            # equal share of every die: die x owns bits x, x+8, x+16, ...
+            bits = [i for i in range(256) if (int(m[i // 32]) >> (i % 32)) & 1]
+            per_die = np.bincount([b % 8 for b in bits], minlength=8)
+            assert np.all(per_die == cus // 8)
+            mb = S.sgprs_build_cu_mask(256, 8, cus, p, blocked_layout=True)
+            bits_b = [i for i in range(256) if (int(mb[i // 32]) >> (i % 32)) & 1]
+            assert np.all(np.bincount([b // 32 for b in bits_b], minlength=8) == cus // 8)
+        assert np.all(acc == 0xFFFFFFFF)
+    # partition index wraps (over-subscription)
+    assert np.array_equal(S.sgprs_build_cu_mask(256, 8, 128, 2), S.sgprs_build_cu_mask(256, 8, 128, 0))
+    for bad in [(256, 8, 12, 0), (256, 8, 0, 0), (256, 8, 512, 0), (250, 8, 8, 0), (256, 8, 8, -1)]:
+        with pytest.raises(S.SgprsError):
+            S.sgprs_build_cu_mask(*bad)
+
+
+def test_fold_bn_matches_closed_form():
+    g, b, m, v = make_bn(95, 0, 1, 64)
+    sc, sh = S.sgprs_fold_bn(g, b, m, v, BN_EPS)
+    ref_sc = g.astype(np.float64) / np.sqrt(v.astype(np.float64) + np.float32(BN_EPS).astype(np.float64))
+    assert np.allclose(sc, ref_sc, rtol=2e-7)
+    assert np.allclose(sh, b - m * ref_sc, rtol=1e-6, atol=1e-7)
+    with pytest.raises(S.SgprsError):
+        S.sgprs_fold_bn(g, b, m, -np.ones_like(v), BN_EPS)
+
+
+@pytest.mark.parametrize("dtype", [S.SGPRS_F32, S.SGPRS_BF16])
+@pytest.mark.parametrize("shape", [(64, 64, 3, 1, 1), (64, 128, 1, 2, 0), (3, 64, 7, 2, 3)])
+def test_pack_unpack_roundtrip(dtype, shape):
+    cin, cout, k, stride, pad = shape
+    d = S.ConvDesc(1, 32, 32, cin, cout, k, k, stride, pad, dtype, 0)
+    w = make_conv_weight(95, 1, 2, cout, cin, k, bf16=dtype == S.SGPRS_BF16)
+    packed = S.sgprs_pack_conv_weights(d, w)
+    assert np.array_equal(S.sgprs_unpack_conv_weights(d, packed), w)
+    es = 2 if dtype == S.SGPRS_BF16 else 4
+    if cin == 3:
+        assert packed.size == cout * 224 * es
+        # unused slots of the stem layout are zero
+        words = packed.view(np.uint16 if es == 2 else np.uint32).reshape(cout, 7, 32)
+        assert not np.any(words[:, :, 28:]) and not np.any(words[:, :, 3:28:4])
+    else:
+        assert packed.size == cout * cin * k * k * es
+        # (r, s, c) order with c fastest
+        vals = packed.view(np.uint16 if es == 2 else np.float32).reshape(cout, k, k, cin)
+        if es == 4:
+            assert np.array_equal(vals, np.transpose(w, (0, 2, 3, 1)))
+
+
+def test_bf16_pack_rounds_to_nearest_even():
+    d = S.ConvDesc(1, 8, 8, 64, 64, 1, 1, 1, 0, S.SGPRS_BF16, 0)
+    w = np.zeros((64, 64, 1, 1), dtype=np.float32)
+    # 1 + 2^-8 is a tie between 1.0 and 1 + 2^-7: goes to even (1.0); 1 + 3*2^-8 ties up to 1 + 2^-6
+    w[0, 0], w[0, 1], w[0, 2] = 1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, 1 + 2.0 ** -8 + 2.0 ** -20
+    back = S.sgprs_unpack_conv_weights(d, S.sgprs_pack_conv_weights(d, w))
+    assert back[0, 0, 0, 0] == 1.0 and back[0, 1, 0, 0] == 1 + 2.0 ** -6 and back[0, 2, 0, 0] == 1 + 2.0 ** -7
+
+
+def test_workspace_planning_is_deterministic_and_bounded():
+    for n, h, c in [(1, 56, 64), (1, 14, 256), (1, 7, 512), (64, 7, 512), (64, 56, 64)]:
+        d = S.ConvDesc(n, h, h, c, c, 3, 3, 1, 1, S.SGPRS_BF16, 1)
+        for cus in (8, 16, 32, 64, 128, 256):
+            a, b = S.sgprs_conv2d_workspace(d, cus), S.sgprs_conv2d_workspace(d, cus)
+            assert a == b
+            assert a % (n * h * h * c * 4) == 0 and a // (n * h * h * c * 4) <= 32
+    with pytest.raises(S.SgprsError):
+        S.sgprs_conv2d_workspace(S.ConvDesc(1, 8, 8, 64, 64, 5, 5, 1, 2, 0, 0), 8)
+    with pytest.raises(S.SgprsError):
+        S.sgprs_conv2d_workspace(S.ConvDesc(1, 8, 8, 64, 64, 3, 3, 1, 1, 0, 0), 0)
+
+
+def test_no_device_is_an_error_not_a_crash():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is visible")
+    with pytest.raises(S.SgprsError) as e:
+        S.Pool(1, 8)
+    assert e.value.status == -2
+    from workloads import make_resnet18_params
+    with pytest.raises(S.SgprsError) as e:
+        S.Task(make_resnet18_params(1, 0), S.SGPRS_F32, 1, BN_EPS)
+    assert e.value.status == -2
+
+
+def test_null_handles_rejected():
+    L = S.lib()
+    assert L.sgprs_pool_sync(None) == -1
+    assert L.sgprs_pool_destroy(None) == -1
+    assert L.sgprs_task_num_stages(None) == -1
+    assert L.sgprs_pool_stream(None, 0) is None
+    assert L.sgprs_stage_run(None, 0, 1, None, None, None, 0) == -1
+    assert "NULL" in S.sgprs_last_error()

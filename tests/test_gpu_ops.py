@@ -1,0 +1,210 @@
+"""GPU parity of the per-operator entry points against the fp64 oracle.
+
+Every case calls libsgprs through its C ABI (via the ctypes binding) on seeded
+inputs and compares element by element with the oracle:
+max|gpu - ref| <= 1e-4 * max|ref| for fp32 and <= 2e-2 * max|ref| for
+bf16-storage / fp32-accumulate (the oracle is fed the bf16-rounded values).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2406_09425_amd as S
+from workloads import BN_EPS, make_bn, make_conv_weight, make_input, round_to_bf16
+
+from gpu_util import (DevConv, assert_close, dev_empty, dev_f32, dev_nhwc, host_nchw, rel_err)
+
+pytestmark = pytest.mark.gpu
+DTYPES = [S.SGPRS_F32, S.SGPRS_BF16]
+DT_ID = {S.SGPRS_F32: "f32", S.SGPRS_BF16: "bf16"}
+
+
+@pytest.fixture(scope="module")
+def pools():
+    info = S.Pool(1, 8)
+    total = info.info()["total_cus"]
+    info.destroy()
+    ps = {c: S.Pool(1, c) for c in (8, 64, total)}
+    ps["full"] = ps[total]
+    yield ps
+    for p in set(ps.values()):
+        p.destroy()
+
+
+def conv_case(dtype, n, h, w, cin, cout, k, stride, pad, relu, with_res, seed, pool, cus, absx=False):
+    bf = dtype == S.SGPRS_BF16
+    x = make_input(90, seed, (n, cin, h, w), "absnormal" if absx else "normal", bf16=bf)
+    wt = make_conv_weight(90, seed, 1, cout, cin, k, bf16=bf)
+    g, b, m, v = make_bn(90, seed, 2, cout)
+    ref = oracle.bn(oracle.conv2d(x, wt, stride, pad), g, b, m, v, BN_EPS)
+    res = None
+    if with_res:
+        res = make_input(90, seed, ref.shape, bf16=bf, tensor_id=7)
+        ref = oracle.add(ref, res)
+    if relu:
+        ref = oracle.relu(ref)
+    d = S.ConvDesc(n, h, w, cin, cout, k, k, stride, pad, dtype, int(relu))
+    dc = DevConv(d, wt, g, b, m, v, BN_EPS)
+    xd = dev_nhwc(x, dtype)
+    rd = dev_nhwc(res, dtype) if with_res else None
+    yd = dev_empty((n, ref.shape[2], ref.shape[3], cout), dtype)
+    keep = dc.run(xd, yd, rd, pool, 0, cus)
+    pool.sync()
+    del keep
+    return host_nchw(yd), ref
+
+
+IGEMM_SHAPES = [
+    # n, h, w, cin, cout, k, stride, pad   (ResNet18 shapes at batch 1 + ragged ones)
+    (1, 56, 56, 64, 64, 3, 1, 1),
+    (1, 56, 56, 64, 128, 3, 2, 1),
+    (1, 56, 56, 64, 128, 1, 2, 0),
+    (1, 28, 28, 128, 128, 3, 1, 1),
+    (1, 14, 14, 256, 256, 3, 1, 1),
+    (1, 14, 14, 256, 512, 3, 2, 1),
+    (1, 7, 7, 512, 512, 3, 1, 1),
+    (1, 14, 14, 256, 512, 1, 2, 0),
+    (3, 9, 13, 64, 64, 3, 1, 1),     # ragged M = 351
+    (2, 11, 7, 128, 192, 3, 2, 1),   # odd sizes, cout 192 = 3 x 64
+    (5, 5, 5, 64, 64, 1, 1, 0),      # 1x1 stride 1
+]
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=DT_ID.get)
+@pytest.mark.parametrize("shape", IGEMM_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_conv_igemm_parity(pools, dtype, shape):
+    for i, cus in enumerate((8, "full")):
+        pool = pools[cus]
+        ncus = pool.partition_cus(0)
+        got, ref = conv_case(dtype, *shape, relu=True, with_res=True, seed=11 + i, pool=pool, cus=ncus)
+        e = assert_close(got, ref, dtype, f"conv {shape} on {ncus} CUs")
+        if dtype == S.SGPRS_F32:
+            assert e < 2e-5, e  # fp32 accumulation error should sit far inside the tolerance
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=DT_ID.get)
+def test_conv_flags_no_relu_no_residual(pools, dtype):
+    pool = pools["full"]
+    got, ref = conv_case(dtype, 2, 14, 14, 128, 128, 3, 1, 1, relu=False, with_res=False, seed=21, pool=pool,
+                         cus=pool.partition_cus(0))
+    assert_close(got, ref, dtype, "conv without relu/residual")
+    assert np.min(ref) < 0 and np.min(got) < 0
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=DT_ID.get)
+@pytest.mark.parametrize("shape", [(1, 224, 224), (2, 50, 70), (1, 30, 33)], ids=str)
+def test_conv_stem_parity(pools, dtype, shape):
+    n, h, w = shape
+    for cus in (8, "full"):
+        pool = pools[cus]
+        got, ref = conv_case(dtype, n, h, w, 3, 64, 7, 2, 3, relu=True, with_res=False, seed=31, pool=pool,
+                             cus=pool.partition_cus(0))
+        assert_close(got, ref, dtype, f"stem {shape}")
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=DT_ID.get)
+def test_conv_is_deterministic_and_mask_independent(pools, dtype):
+    shape = (1, 14, 14, 256, 256, 3, 1, 1)
+    outs = {}
+    for cus in (8, 64, "full"):
+        pool = pools[cus]
+        a, ref = conv_case(dtype, *shape, relu=True, with_res=True, seed=41, pool=pool, cus=pool.partition_cus(0))
+        b, _ = conv_case(dtype, *shape, relu=True, with_res=True, seed=41, pool=pool, cus=pool.partition_cus(0))
+        assert np.array_equal(a, b), "two runs of the same launch differ"
+        assert_close(a, ref, dtype)
+        outs[cus] = a
+    # masks change the split-K factor at most: results agree to rounding
+    assert rel_err(outs[8], outs["full"]) <= (1e-5 if dtype == S.SGPRS_F32 else 1e-2)
+
+
+def test_pack_unpack_roundtrip_on_device_copy():
+    d = S.ConvDesc(1, 8, 8, 64, 64, 3, 3, 1, 1, S.SGPRS_BF16, 0)
+    w = make_conv_weight(90, 0, 3, 64, 64, 3, bf16=True)
+    assert np.array_equal(S.sgprs_unpack_conv_weights(d, S.sgprs_pack_conv_weights(d, w)), w)
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=DT_ID.get)
+@pytest.mark.parametrize("shape", [(1, 64, 112, 112), (2, 16, 9, 11), (3, 64, 7, 8)], ids=str)
+def test_maxpool_parity_exact(pools, dtype, shape):
+    n, c, h, w = shape
+    x = make_input(91, 0, shape, bf16=dtype == S.SGPRS_BF16)  # has negatives: padding must not win
+    ref = oracle.maxpool2d(x)
+    xd = dev_nhwc(x, dtype)
+    yd = dev_empty((n, ref.shape[2], ref.shape[3], c), dtype)
+    S.sgprs_maxpool2d(dtype, n, h, w, c, xd.data_ptr(), yd.data_ptr(), pools["full"], 0)
+    pools["full"].sync()
+    assert np.array_equal(host_nchw(yd), ref)  # selection only: bit exact
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=DT_ID.get)
+def test_bn_relu_parity(pools, dtype):
+    shape = (1, 128, 28, 28)
+    x = make_input(92, 0, shape, bf16=dtype == S.SGPRS_BF16)
+    g, b, m, v = make_bn(92, 0, 1, 128)
+    ref = oracle.relu(oracle.bn(x, g, b, m, v, BN_EPS))
+    sc, sh = S.sgprs_fold_bn(g, b, m, v, BN_EPS)
+    xd, scd, shd = dev_nhwc(x, dtype), dev_f32(sc), dev_f32(sh)
+    yd = dev_empty((1, 28, 28, 128), dtype)
+    S.sgprs_bn_relu(dtype, 28 * 28, 128, xd.data_ptr(), scd.data_ptr(), shd.data_ptr(), yd.data_ptr(),
+                    pools["full"], 0)
+    pools["full"].sync()
+    assert_close(host_nchw(yd), ref, dtype, "bn_relu")
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=DT_ID.get)
+@pytest.mark.parametrize("relu", [False, True])
+def test_add_parity(pools, dtype, relu):
+    shape = (1, 512, 7, 7)
+    bf = dtype == S.SGPRS_BF16
+    a, b = make_input(93, 0, shape, bf16=bf), make_input(93, 1, shape, bf16=bf)
+    ref = oracle.add(a, b)
+    if relu:
+        ref = oracle.relu(ref)
+    ad, bd = dev_nhwc(a, dtype), dev_nhwc(b, dtype)
+    yd = dev_empty((1, 7, 7, 512), dtype)
+    S.sgprs_add_relu(dtype, a.size, ad.data_ptr(), bd.data_ptr(), yd.data_ptr(), relu, pools["full"], 0)
+    pools["full"].sync()
+    assert_close(host_nchw(yd), ref, dtype, "add")
+    if not relu:
+        assert np.min(host_nchw(yd)) < 0
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=DT_ID.get)
+@pytest.mark.parametrize("n", [1, 5, 33])
+def test_avgpool_fc_parity(pools, dtype, n):
+    bf = dtype == S.SGPRS_BF16
+    x = make_input(94, n, (n, 512, 7, 7), bf16=bf)
+    w = make_conv_weight(94, n, 1, 1000, 512, 1, bf16=bf)[:, :, 0, 0]
+    bias = (make_input(94, n, (1000,), tensor_id=2) * 0.1).astype(np.float32)
+    ref = oracle.fc(oracle.global_avgpool(x), w, bias)
+    xd = dev_nhwc(x, dtype)
+    wd = torch.from_numpy(np.ascontiguousarray(w)).to(xd.dtype).cuda()
+    bd = dev_f32(bias)
+    ws = torch.empty(n * 512, dtype=torch.float32, device="cuda")
+    yd = torch.full((n, 1000), float("nan"), dtype=torch.float32, device="cuda")
+    S.sgprs_avgpool_fc(dtype, n, 49, 512, 1000, xd.data_ptr(), wd.data_ptr(), bd.data_ptr(), yd.data_ptr(),
+                       ws.data_ptr(), pools["full"], 0)
+    pools["full"].sync()
+    got = yd.cpu().numpy().astype(np.float64)
+    assert_close(got, ref, dtype, "avgpool_fc")
+    # without bias
+    S.sgprs_avgpool_fc(dtype, n, 49, 512, 1000, xd.data_ptr(), wd.data_ptr(), None, yd.data_ptr(),
+                       ws.data_ptr(), pools["full"], 0)
+    pools["full"].sync()
+    assert_close(yd.cpu().numpy().astype(np.float64), ref - bias, dtype, "avgpool_fc no bias")
+
+
+def test_error_paths_enqueue_nothing(pools):
+    pool = pools["full"]
+    x = torch.zeros(64, device="cuda")
+    with pytest.raises(S.SgprsError) as e:
+        S.sgprs_maxpool2d(S.SGPRS_F32, 1, 4, 4, 4, x.data_ptr(), x.data_ptr(), pool, 0)  # aliasing
+    assert e.value.status == -1
+    with pytest.raises(S.SgprsError):
+        S.sgprs_maxpool2d(S.SGPRS_F32, 1, 4, 4, 4, x.data_ptr(), x.data_ptr() + 256, pool, 3)  # bad partition
+    with pytest.raises(S.SgprsError) as e:
+        S.sgprs_conv2d_workspace(S.ConvDesc(1, 8, 8, 48, 64, 3, 3, 1, 1, 0, 0), 256)  # cin % 32
+    assert e.value.status == -5
+    with pytest.raises(S.SgprsError):
+        S.sgprs_add_relu(S.SGPRS_F32, 12, x.data_ptr(), x.data_ptr(), x.data_ptr(), False, pool, 0)
