@@ -163,6 +163,12 @@ static int launch_stem_variant(const StemArgs& a, int grid, hipStream_t stream)
     constexpr int ES = DT == SGPRS_BF16 ? 2 : 4;
     constexpr int PATCH_BYTES = (((2 * TP + 5) * kPatchW * 4 * ES + 15) / 16) * 16;
     const size_t lds = 64 * (kStemK * ES + 16) + PATCH_BYTES;
+    static bool raised = false;  // more than 64 KB of dynamic LDS needs an explicit opt-in
+    if (lds > 65536 && !raised) {
+        SGPRS_HIP(hipFuncSetAttribute((const void*)conv_stem_kernel<DT, TP>,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        raised = true;
+    }
     hipLaunchKernelGGL((conv_stem_kernel<DT, TP>), dim3(grid), dim3(256), lds, stream, a);
     SGPRS_HIP(hipGetLastError());
     return SGPRS_OK;
