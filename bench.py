@@ -1,0 +1,410 @@
+#!/usr/bin/env python3
+"""Benchmark of the SGPRS stage computation on one MI355X.
+
+A "step" is one pass of the whole hot path -- all six ResNet18 stages -- over
+one batch of synthetic input already resident in HBM.  The headline workload
+is the batch-64 bf16 (fp32 accumulate) forward on one partition of all CUs;
+`value` is images/s.  The same run also reports, in the one JSON line:
+
+  roofline      the dominant kernel (the implicit-GEMM conv instantiation with
+                the largest total time): algorithmic FLOP / measured duration
+                against the dense bf16 MFMA peak
+  cpu_baseline  the fp64 oracle timed on the host cores on a bounded sample
+  stages        per-stage time, FLOP/s, GB/s and fraction of the per-kernel
+                roofline max(FLOP/peak, bytes/HBM peak)
+  batch1_fp32   six-stage latency of the fp32 batch-1 network (median / max)
+  cu_sweep      time and speed-up of six isolated operators on CU masks
+                8..256 (fp32 and bf16), with the oracle's host time beside it
+  multi_tenant  eight bf16 instances on an 8 x 32-CU pool, issued concurrently
+
+Only one GPU is used; --gpus above 1 is refused.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import statistics
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16 = 2500.0e12   # dense bf16 MFMA, FLOP/s
+PEAK_F32 = 157.3e12     # fp32 MFMA
+PEAK_HBM = 8.0e12       # bytes/s
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class Hip:
+    """Just enough of the HIP runtime for event timing on a given stream."""
+
+    def __init__(self):
+        self.l = ctypes.CDLL("libamdhip64.so")
+
+    def event(self):
+        e = ctypes.c_void_p()
+        assert self.l.hipEventCreate(ctypes.byref(e)) == 0
+        return e
+
+    def record(self, e, stream):
+        assert self.l.hipEventRecord(e, ctypes.c_void_p(stream)) == 0
+
+    def elapsed_ms(self, a, b):
+        assert self.l.hipEventSynchronize(b) == 0
+        ms = ctypes.c_float()
+        assert self.l.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+        return ms.value
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--batch", type=int, default=64)
+    ap.add_argument("--no-extras", action="store_true", help="skip batch-1, CU sweep and multi-tenant legs")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle CPU baseline")
+    ap.add_argument("--cpu-sample", type=int, default=24, help="images of the batch the oracle is timed on")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (the stage computation has no multi-GPU "
+                 "part); run with --gpus 1")
+
+    import torch
+
+    import paper_2406_09425_amd as S
+    from workloads import BN_EPS, SWEEP_OPS, make_bn, make_conv_weight, make_input, make_resnet18_params
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    hip = Hip()
+    total_cus = S.Pool(1, 8).info()["total_cus"]
+    pool = S.Pool(1, total_cus)
+    stream = pool.stream(0)
+
+    def nhwc(x, tdt):
+        return torch.from_numpy(np.ascontiguousarray(x.transpose(0, 2, 3, 1))).to(tdt).cuda().contiguous()
+
+    # ------------------------------------------------------------ headline
+    n = args.batch
+    params = make_resnet18_params(4, 0, bf16=True)
+    x_host = make_input(4, 0, (n, 3, 224, 224), bf16=True)
+    task = S.Task(params, S.SGPRS_BF16, n, BN_EPS)
+    xd = nhwc(x_host, torch.bfloat16)
+    logits = torch.empty((n, 1000), dtype=torch.float32, device="cuda")
+
+    def step():
+        task.run(n, xd.data_ptr(), logits.data_ptr(), pool, 0)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize(); pool.sync()
+    e0, e1 = hip.event(), hip.event()
+    t0 = time.perf_counter()
+    hip.record(e0, stream)
+    for _ in range(args.steps):
+        step()
+    hip.record(e1, stream)
+    pool.sync(); torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ev_ms = hip.elapsed_ms(e0, e1)
+    ms_per_step = wall * 1e3 / args.steps
+    value = n * args.steps / wall
+    log(f"headline: {value:.0f} img/s, {ms_per_step:.3f} ms/step (events: {ev_ms / args.steps:.3f} ms/step)")
+
+    # ------------------------------------------------------------ per-kernel profile
+    task.set_profiling(True)
+    agg = {}      # kernel name -> [time_s, flops, bytes, launches]
+    stages = []
+    prof_steps = min(args.steps, 20)
+    per_stage = [dict(ms=0.0, flops=0.0, bytes=0.0, roof_s=0.0) for _ in range(6)]
+    for _ in range(prof_steps):
+        step()
+        pool.sync()
+        for j in range(6):
+            for r in task.kernel_times(j):
+                a = agg.setdefault((r["name"], r["kind"]), [0.0, 0.0, 0.0, 0])
+                a[0] += r["ms"] * 1e-3; a[1] += r["flops"]; a[2] += r["bytes"]; a[3] += 1
+                ps = per_stage[j]
+                ps["ms"] += r["ms"]; ps["flops"] += r["flops"]; ps["bytes"] += r["bytes"]
+                ps["roof_s"] += max(r["flops"] / PEAK_BF16, r["bytes"] / PEAK_HBM)
+    task.set_profiling(False)
+    for j, ps in enumerate(per_stage):
+        t_s = ps["ms"] * 1e-3 / prof_steps
+        stages.append(dict(stage=j, ms=round(ps["ms"] / prof_steps, 4),
+                           images_per_s=round(n / t_s, 1),
+                           tflops=round(ps["flops"] / prof_steps / t_s / 1e12, 2),
+                           mfma_frac=round(ps["flops"] / prof_steps / t_s / PEAK_BF16, 4),
+                           gb_per_s=round(ps["bytes"] / prof_steps / t_s / 1e9, 1),
+                           roofline_frac=round(ps["roof_s"] / prof_steps / t_s, 4)))
+    kernels = []
+    for (name, kind), (t_s, fl, by, cnt) in sorted(agg.items(), key=lambda kv: -kv[1][0]):
+        kernels.append(dict(kernel=name, launches_per_step=cnt // prof_steps, avg_us=round(t_s / cnt * 1e6, 2),
+                            tflops=round(fl / t_s / 1e12, 2), gb_per_s=round(by / t_s / 1e9, 1)))
+    dom_key = max((k for k in agg if k[1] == 0), key=lambda k: agg[k][0])
+    dt_s, dfl, dby, dcnt = agg[dom_key]
+    roofline = dict(bound="mfma", kernel=dom_key[0], achieved=round(dfl / dt_s / 1e12, 2), peak=PEAK_BF16 / 1e12,
+                    unit="TFLOP/s", frac=round(dfl / dt_s / PEAK_BF16, 4), traffic=None,
+                    avg_launch_us=round(dt_s / dcnt * 1e6, 2), launches_per_step=dcnt // prof_steps,
+                    flop_per_launch=round(dfl / dcnt, 1))
+    conv_t = sum(v[0] for k, v in agg.items() if k[1] in (0, 1, 2))
+    conv_fl = sum(v[1] for k, v in agg.items() if k[1] in (0, 1))
+    conv_all = dict(tflops=round(conv_fl / conv_t / 1e12, 2), mfma_frac=round(conv_fl / conv_t / PEAK_BF16, 4),
+                    us_per_step=round(conv_t / prof_steps * 1e6, 1))
+    log("roofline:", json.dumps(roofline))
+    log("conv total:", json.dumps(conv_all))
+    for s in stages:
+        log("stage", json.dumps(s))
+    for k in kernels:
+        log("kernel", json.dumps(k))
+
+    # ------------------------------------------------------------ CPU baseline (oracle)
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        ns = max(1, min(args.cpu_sample, n))
+        t1 = time.perf_counter()
+        ref = oracle.resnet18(params, BN_EPS, x_host[:ns])
+        dt = time.perf_counter() - t1
+        got = logits[:ns].cpu().numpy().astype(np.float64)
+        err = float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
+        cpu = dict(value=round(ns / dt, 3), unit="images/s", cores=oracle.max_threads(), kind="oracle",
+                   sample=f"first {ns} images of the batch-{n} workload, fp64 direct loops, {dt:.1f} s",
+                   gpu_vs_oracle_max_rel_err=err,
+                   argmax_equal=bool(np.array_equal(np.argmax(got, 1), np.argmax(ref, 1))))
+        log("cpu_baseline:", json.dumps(cpu))
+    task.destroy()
+
+    out = {
+        "metric": "resnet18_images_per_s", "value": round(value, 1), "unit": "images/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"ResNet18 forward, batch {n}, bf16 storage / fp32 accumulate, 3x224x224 ~N(0,1), "
+                               f"six stages on one partition of all {total_cus} CUs",
+                   "batch": n, "partition_cus": total_cus},
+        "roofline": roofline, "cpu_baseline": cpu, "conv_all": conv_all, "stages": stages, "kernels": kernels,
+    }
+
+    if not args.no_extras:
+        out["batch1_fp32"] = leg_batch1(S, hip, pool, stream, nhwc, torch, total_cus)
+        out["cu_sweep"] = leg_sweep(S, hip, torch, total_cus, nhwc, with_cpu=not args.no_cpu)
+        out["multi_tenant"] = leg_multi_tenant(S, hip, torch, total_cus, nhwc)
+    pool.destroy()
+    print(json.dumps(out), flush=True)
+
+
+def leg_batch1(S, hip, pool, stream, nhwc, torch, total_cus, runs=100):
+    """Six-stage latency of the fp32 batch-1 network; max over runs = WCET."""
+    from workloads import BN_EPS, STAGE_IO, make_input, make_resnet18_params
+    params = make_resnet18_params(1, 0)
+    x = make_input(1, 0, (1, 3, 224, 224))
+    res = {}
+    for dtype, tdt, name in ((S.SGPRS_F32, torch.float32, "fp32"), (S.SGPRS_BF16, torch.bfloat16, "bf16")):
+        task = S.Task(params, dtype, 1, BN_EPS)
+        xd = nhwc(x, tdt)
+        lg = torch.empty((1, 1000), dtype=torch.float32, device="cuda")
+        ev = [hip.event() for _ in range(7)]
+        per = [[] for _ in range(6)]
+        whole = []
+        for it in range(runs + 10):
+            for j in range(6):
+                hip.record(ev[j], stream)
+                src = xd.data_ptr() if j == 0 else task.stage_output(j - 1)
+                dst = lg.data_ptr() if j == 5 else task.stage_output(j)
+                task.stage_run(j, 1, src, dst, pool, 0)
+            hip.record(ev[6], stream)
+            pool.sync()
+            if it >= 10:
+                for j in range(6):
+                    per[j].append(hip.elapsed_ms(ev[j], ev[j + 1]))
+                whole.append(hip.elapsed_ms(ev[0], ev[6]))
+        # back-to-back whole-network throughput (no per-stage events)
+        e0, e1 = hip.event(), hip.event()
+        hip.record(e0, stream)
+        for _ in range(runs):
+            task.run(1, xd.data_ptr(), lg.data_ptr(), pool, 0)
+        hip.record(e1, stream)
+        pool.sync()
+        thr_ms = hip.elapsed_ms(e0, e1) / runs
+        res[name] = dict(stage_ms_median=[round(statistics.median(p), 4) for p in per],
+                         stage_ms_max=[round(max(p), 4) for p in per],
+                         net_ms_median=round(statistics.median(whole), 4), net_ms_max=round(max(whole), 4),
+                         back_to_back_ms=round(thr_ms, 4), images_per_s=round(1e3 / thr_ms, 1))
+        log("batch1", name, json.dumps(res[name]))
+        task.destroy()
+    return res
+
+
+def leg_sweep(S, hip, torch, total_cus, nhwc, with_cpu=True, reps=200):
+    """Six isolated operators on CU masks 8..total; speed-up relative to 8 CUs."""
+    from workloads import BN_EPS, make_bn, make_conv_weight, make_input
+    cu_list = [c for c in (8, 16, 32, 64, 128, 256) if c <= total_cus]
+    res = {}
+    oracle_ms = {}
+    if with_cpu:
+        import oracle
+        x = make_input(2, 0, (1, 256, 14, 14)); w = make_conv_weight(2, 0, 1, 256, 256, 3)
+        xs = make_input(2, 1, (1, 3, 224, 224)); wsx = make_conv_weight(2, 1, 1, 64, 3, 7)
+        xm = make_input(2, 2, (1, 64, 112, 112)); xb = make_input(2, 3, (1, 128, 28, 28))
+        g, b, m, v = make_bn(2, 3, 1, 128)
+        xa = make_input(2, 4, (1, 512, 7, 7)); xf = make_input(2, 5, (1, 512, 7, 7))
+        wf = make_conv_weight(2, 5, 1, 1000, 512, 1)[:, :, 0, 0]
+
+        def tm(f):
+            ts = []
+            for _ in range(5):
+                t = time.perf_counter(); f(); ts.append(time.perf_counter() - t)
+            return round(statistics.median(ts) * 1e3, 4)
+        oracle_ms = {
+            "conv3x3_256": tm(lambda: oracle.conv2d(x, w, 1, 1)),
+            "conv7x7_stem": tm(lambda: oracle.conv2d(xs, wsx, 2, 3)),
+            "maxpool": tm(lambda: oracle.maxpool2d(xm)),
+            "bn_relu": tm(lambda: oracle.relu(oracle.bn(xb, g, b, m, v, BN_EPS))),
+            "add": tm(lambda: oracle.add(xa, xa)),
+            "avgpool_fc": tm(lambda: oracle.fc(oracle.global_avgpool(xf), wf, None)),
+        }
+    for dtype, tdt, dname in ((S.SGPRS_F32, torch.float32, "fp32"), (S.SGPRS_BF16, torch.bfloat16, "bf16")):
+        bf = dtype == S.SGPRS_BF16
+        es = 2 if bf else 4
+        # operands, built once
+        x = nhwc(make_input(2, 0, (1, 256, 14, 14), bf16=bf), tdt)
+        d3 = S.ConvDesc(1, 14, 14, 256, 256, 3, 3, 1, 1, dtype, 1)
+        w3 = torch.from_numpy(S.sgprs_pack_conv_weights(d3, make_conv_weight(2, 0, 1, 256, 256, 3, bf16=bf))).cuda()
+        xs = nhwc(make_input(2, 1, (1, 3, 224, 224), bf16=bf), tdt)
+        d7 = S.ConvDesc(1, 224, 224, 3, 64, 7, 7, 2, 3, dtype, 1)
+        w7 = torch.from_numpy(S.sgprs_pack_conv_weights(d7, make_conv_weight(2, 1, 1, 64, 3, 7, bf16=bf))).cuda()
+        ones = torch.ones(1024, dtype=torch.float32, device="cuda")
+        zeros = torch.zeros(1024, dtype=torch.float32, device="cuda")
+        y3 = torch.empty((1, 14, 14, 256), dtype=tdt, device="cuda")
+        y7 = torch.empty((1, 112, 112, 64), dtype=tdt, device="cuda")
+        xm = nhwc(make_input(2, 2, (1, 64, 112, 112), bf16=bf), tdt)
+        ym = torch.empty((1, 56, 56, 64), dtype=tdt, device="cuda")
+        xb = nhwc(make_input(2, 3, (1, 128, 28, 28), bf16=bf), tdt)
+        yb = torch.empty_like(xb)
+        xa = nhwc(make_input(2, 4, (1, 512, 7, 7), bf16=bf), tdt)
+        ya = torch.empty_like(xa)
+        wf = torch.from_numpy(make_conv_weight(2, 5, 1, 1000, 512, 1, bf16=bf)[:, :, 0, 0].copy()).to(tdt).cuda()
+        yf = torch.empty((1, 1000), dtype=torch.float32, device="cuda")
+        wsf = torch.empty(512, dtype=torch.float32, device="cuda")
+        work = {  # algorithmic FLOP, bytes
+            "conv3x3_256": (2.0 * 196 * 256 * 2304, (196 * 256 * 2 + 256 * 2304) * es),
+            "conv7x7_stem": (2.0 * 12544 * 64 * 147, (3 * 224 * 224 + 64 * 147 + 12544 * 64) * es),
+            "maxpool": (0.0, (64 * 112 * 112 + 64 * 56 * 56) * es),
+            "bn_relu": (2.0 * 100352, 2 * 100352 * es),
+            "add": (25088.0, 3 * 25088 * es),
+            "avgpool_fc": (2.0 * 512 * 1000, (25088 + 512000) * es + 4000),
+        }
+        res[dname] = {k: {"cus": cu_list, "us": [], "speedup_vs_8": [], "tflops": [], "gb_per_s": [],
+                          "flop": work[k][0], "bytes": work[k][1], "oracle_host_ms": oracle_ms.get(k)}
+                      for k in work}
+        for cus in cu_list:
+            pool = S.Pool(1, cus)
+            st = pool.stream(0)
+            wsb = max(S.sgprs_conv2d_workspace(d3, cus), 16)
+            ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+            ops = {
+                "conv3x3_256": lambda: S.sgprs_conv2d(d3, x.data_ptr(), w3.data_ptr(), ones.data_ptr(),
+                                                      zeros.data_ptr(), None, y3.data_ptr(), ws.data_ptr(), wsb,
+                                                      pool, 0),
+                "conv7x7_stem": lambda: S.sgprs_conv2d(d7, xs.data_ptr(), w7.data_ptr(), ones.data_ptr(),
+                                                       zeros.data_ptr(), None, y7.data_ptr(), None, 0, pool, 0),
+                "maxpool": lambda: S.sgprs_maxpool2d(dtype, 1, 112, 112, 64, xm.data_ptr(), ym.data_ptr(), pool, 0),
+                "bn_relu": lambda: S.sgprs_bn_relu(dtype, 784, 128, xb.data_ptr(), ones.data_ptr(),
+                                                   zeros.data_ptr(), yb.data_ptr(), pool, 0),
+                "add": lambda: S.sgprs_add_relu(dtype, 25088, xa.data_ptr(), xa.data_ptr(), ya.data_ptr(), False,
+                                                pool, 0),
+                "avgpool_fc": lambda: S.sgprs_avgpool_fc(dtype, 1, 49, 512, 1000, xa.data_ptr(), wf.data_ptr(), None,
+                                                         yf.data_ptr(), wsf.data_ptr(), pool, 0),
+            }
+            for name, f in ops.items():
+                for _ in range(10):
+                    f()
+                pool.sync()
+                e0, e1 = hip.event(), hip.event()
+                hip.record(e0, st)
+                for _ in range(reps):
+                    f()
+                hip.record(e1, st)
+                pool.sync()
+                us = hip.elapsed_ms(e0, e1) * 1e3 / reps
+                r = res[dname][name]
+                r["us"].append(round(us, 3))
+                r["tflops"].append(round(work[name][0] / us / 1e6, 3))
+                r["gb_per_s"].append(round(work[name][1] / us / 1e3, 2))
+            pool.destroy()
+        for name, r in res[dname].items():
+            r["speedup_vs_8"] = [round(r["us"][0] / u, 2) for u in r["us"]]
+            log("sweep", dname, name, "us", r["us"], "speedup", r["speedup_vs_8"])
+    return res
+
+
+def leg_multi_tenant(S, hip, torch, total_cus, nhwc, n_p=8, rounds=30):
+    """Eight bf16 instances, each pinned to its own 32-CU partition (a static
+    instance->partition assignment, i.e. pure spatial partitioning), stages of
+    all instances issued round-robin from one host thread."""
+    from workloads import BN_EPS, make_input, make_resnet18_params
+    pool = S.Pool(n_p, total_cus // n_p)
+    tasks, xs, lgs = [], [], []
+    for i in range(n_p):
+        tasks.append(S.Task(make_resnet18_params(3, i, bf16=True), S.SGPRS_BF16, 1, BN_EPS))
+        xs.append(nhwc(make_input(3, i, (1, 3, 224, 224), bf16=True), torch.bfloat16))
+        lgs.append(torch.empty((1, 1000), dtype=torch.float32, device="cuda"))
+
+    def issue_all(ev=None):
+        for j in range(6):
+            for i in range(n_p):
+                if ev is not None:
+                    hip.record(ev[i][j], pool.stream(i))
+                src = xs[i].data_ptr() if j == 0 else tasks[i].stage_output(j - 1)
+                dst = lgs[i].data_ptr() if j == 5 else tasks[i].stage_output(j)
+                tasks[i].stage_run(j, 1, src, dst, pool, i)
+        if ev is not None:
+            for i in range(n_p):
+                hip.record(ev[i][6], pool.stream(i))
+
+    for _ in range(5):
+        issue_all()
+    pool.sync()
+    ev = [[hip.event() for _ in range(7)] for _ in range(n_p)]
+    lat = [[[] for _ in range(6)] for _ in range(n_p)]
+    for _ in range(10):
+        issue_all(ev)
+        pool.sync()
+        for i in range(n_p):
+            for j in range(6):
+                lat[i][j].append(hip.elapsed_ms(ev[i][j], ev[i][j + 1]))
+    t0 = time.perf_counter()
+    for _ in range(rounds):
+        issue_all()
+    pool.sync()
+    dt = time.perf_counter() - t0
+    conc = n_p * rounds / dt
+    # context: the same eight images back to back on one full-GPU partition
+    full = S.Pool(1, total_cus)
+    t0 = time.perf_counter()
+    for _ in range(rounds):
+        for i in range(n_p):
+            tasks[i].run(1, xs[i].data_ptr(), lgs[i].data_ptr(), full, 0)
+    full.sync()
+    serial = n_p * rounds / (time.perf_counter() - t0)
+    out = dict(instances=n_p, partition_cus=total_cus // n_p, aggregate_images_per_s=round(conc, 1),
+               serial_full_gpu_images_per_s=round(serial, 1), issue="one host thread, round-robin over instances",
+               stage_latency_ms_median=[[round(statistics.median(l), 4) for l in inst] for inst in lat])
+    log("multi_tenant", json.dumps({k: v for k, v in out.items() if k != "stage_latency_ms_median"}))
+    for t in tasks:
+        t.destroy()
+    full.destroy(); pool.destroy()
+    return out
+
+
+if __name__ == "__main__":
+    main()
