@@ -150,14 +150,14 @@ def main():
     for (name, kind), (t_s, fl, by, cnt) in sorted(agg.items(), key=lambda kv: -kv[1][0]):
         kernels.append(dict(kernel=name, launches_per_step=cnt // prof_steps, avg_us=round(t_s / cnt * 1e6, 2),
                             tflops=round(fl / t_s / 1e12, 2), gb_per_s=round(by / t_s / 1e9, 1)))
-    dom_key = max((k for k in agg if k[1] == 0), key=lambda k: agg[k][0])
+    dom_key = max((k for k in agg if k[1] in (0, 8)), key=lambda k: agg[k][0])
     dt_s, dfl, dby, dcnt = agg[dom_key]
     roofline = dict(bound="mfma", kernel=dom_key[0], achieved=round(dfl / dt_s / 1e12, 2), peak=PEAK_BF16 / 1e12,
                     unit="TFLOP/s", frac=round(dfl / dt_s / PEAK_BF16, 4), traffic=None,
                     avg_launch_us=round(dt_s / dcnt * 1e6, 2), launches_per_step=dcnt // prof_steps,
                     flop_per_launch=round(dfl / dcnt, 1))
-    conv_t = sum(v[0] for k, v in agg.items() if k[1] in (0, 1, 2))
-    conv_fl = sum(v[1] for k, v in agg.items() if k[1] in (0, 1))
+    conv_t = sum(v[0] for k, v in agg.items() if k[1] in (0, 1, 2, 8))
+    conv_fl = sum(v[1] for k, v in agg.items() if k[1] in (0, 1, 8))
     conv_all = dict(tflops=round(conv_fl / conv_t / 1e12, 2), mfma_frac=round(conv_fl / conv_t / PEAK_BF16, 4),
                     us_per_step=round(conv_t / prof_steps * 1e6, 1))
     log("roofline:", json.dumps(roofline))

@@ -155,6 +155,11 @@ int sgprs_conv2d_workspace(const sgprs_conv_desc_t *d, int partition_cus, size_t
 int sgprs_conv2d(const sgprs_conv_desc_t *d, const void *x, const void *w_packed,
                  const float *scale, const float *shift, const void *residual, void *y,
                  void *workspace, size_t workspace_bytes, sgprs_pool_t *pool, int partition);
+/* Measurement hook, process-wide, not thread-safe: which convolution kernel
+ * sgprs_conv2d and the stages pick for 3x3 stride-1 bf16 layers.  kind -1:
+ * automatic (default); 0: implicit GEMM only; 1: the LDS-patch kernel with the
+ * given tile variant (0..3) and split factor where the shape allows it. */
+int sgprs_conv_tuning_override(int kind, int variant, int splits);
 /* Max pooling 3x3, stride 2, pad 1 (padding never wins): [n][h][w][c] ->
  * [n][(h-1)/2+1][(w-1)/2+1][c].  c % 8 == 0 (bf16) or c % 4 == 0 (fp32). */
 int sgprs_maxpool2d(int dtype, int n, int h, int w, int c, const void *x, void *y,
@@ -167,7 +172,7 @@ int sgprs_add_relu(int dtype, size_t count, const void *a, const void *b, void *
                    sgprs_pool_t *pool, int partition);
 /* Global average pool over hw positions, then FC: x [n][hw][cin] (dtype),
  * w [cout][cin] (dtype, DEVICE), bias NULL or fp32[cout], logits fp32 [n][cout].
- * workspace: DEVICE fp32[n*cin] for the pooled vectors.  cin % 64 == 0, cin <= 1024. */
+ * workspace: DEVICE fp32[n*cin] for the pooled vectors.  cin is 512, 1024 or 2048. */
 int sgprs_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void *x, const void *w,
                      const float *bias, float *logits, float *workspace, sgprs_pool_t *pool,
                      int partition);
@@ -222,7 +227,8 @@ const void *sgprs_task_stage_output(const sgprs_task_t *task, int stage);
  * latency; keep it off when timing throughput).  After synchronising,
  * sgprs_task_kernel_times returns, for the last run of each stage, one record
  * per launch: HOST arrays of length *count (in: capacity).  kind: 0 conv
- * implicit GEMM, 1 stem conv, 2 split-K reduce, 3 max-pool, 4 avg-pool, 5 FC.
+ * implicit GEMM, 1 stem conv, 2 split-K reduce, 3 max-pool, 4 avg-pool, 5 FC,
+ * 8 LDS-patch 3x3 conv.
  * flops/bytes are the algorithmic work of the launch. */
 int sgprs_task_set_profiling(sgprs_task_t *task, int on);
 int sgprs_task_kernel_times(sgprs_task_t *task, int stage, int *count, int *kind, int *variant,

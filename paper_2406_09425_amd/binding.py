@@ -19,7 +19,7 @@ __all__ = [
     "sgprs_version", "sgprs_status_string", "sgprs_last_error", "sgprs_build_cu_mask",
     "sgprs_fold_bn", "sgprs_conv_packed_weight_bytes", "sgprs_pack_conv_weights",
     "sgprs_unpack_conv_weights", "sgprs_conv2d_workspace", "sgprs_conv2d", "sgprs_maxpool2d",
-    "sgprs_bn_relu", "sgprs_add_relu", "sgprs_avgpool_fc", "sgprs_kernel_name",
+    "sgprs_conv_tuning_override", "sgprs_bn_relu", "sgprs_add_relu", "sgprs_avgpool_fc", "sgprs_kernel_name",
 ]
 
 SGPRS_F32, SGPRS_BF16 = 0, 1
@@ -85,6 +85,7 @@ def lib():
         "sgprs_unpack_conv_weights": (c_int, [POINTER(ConvDesc), vp, c_size_t, fp]),
         "sgprs_conv2d_workspace": (c_int, [POINTER(ConvDesc), c_int, POINTER(c_size_t)]),
         "sgprs_conv2d": (c_int, [POINTER(ConvDesc), vp, vp, vp, vp, vp, vp, vp, c_size_t, vp, c_int]),
+        "sgprs_conv_tuning_override": (c_int, [c_int, c_int, c_int]),
         "sgprs_maxpool2d": (c_int, [c_int, c_int, c_int, c_int, c_int, vp, vp, vp, c_int]),
         "sgprs_bn_relu": (c_int, [c_int, c_size_t, c_int, vp, vp, vp, vp, vp, c_int]),
         "sgprs_add_relu": (c_int, [c_int, c_size_t, vp, vp, vp, c_int, vp, c_int]),
@@ -244,6 +245,10 @@ def sgprs_conv2d(desc: ConvDesc, x: int, w_packed: int, scale: int, shift: int, 
                  workspace: int | None, workspace_bytes: int, pool, partition: int) -> None:
     _check(lib().sgprs_conv2d(ctypes.byref(desc), x, w_packed, scale, shift, residual, y, workspace,
                               workspace_bytes, _h(pool), partition))
+
+
+def sgprs_conv_tuning_override(kind: int, variant: int = 0, splits: int = 1) -> None:
+    _check(lib().sgprs_conv_tuning_override(kind, variant, splits))
 
 
 def sgprs_maxpool2d(dtype: int, n: int, h: int, w: int, c: int, x: int, y: int, pool, partition: int) -> None:

@@ -1,0 +1,485 @@
+// 3x3 stride-1 pad-1 convolution, bf16, with the input patch staged in LDS.
+//
+// A plain implicit GEMM re-reads every input pixel once per filter tap; at
+// ResNet18's shapes that makes the kernel bound by L2->CU traffic long before
+// the matrix cores are busy.  Here a workgroup owns TR whole output rows
+// (TR*W <= BM pixels, rows counted across the batch) and BN output channels.
+// For each chunk of KC input channels it stages in LDS
+//   * the input patch: the TR+2 (plus image-boundary padding) input rows of
+//     width W+2, zero filled outside the image, read once and reused by all
+//     nine taps, and
+//   * the weights of that chunk for its BN channels and all nine taps,
+// and then runs 9 * KC/16 MFMA k-steps straight out of LDS with no predicates.
+// The next chunk's patch and weights are fetched into registers while the
+// MFMAs of the current chunk run.  Workgroups are persistent over their work
+// items; when a layer has a single chunk and a single channel block (64->64)
+// the weights stay resident in LDS for the whole launch.
+//
+// Rows are addressed in an "extended" row space in which every image has one
+// zero row above and below it: output row g = n*H + p maps to extended row
+// e(g) = g + 2*(g/H) + 1 and needs extended rows e-1, e, e+1; a run of output
+// rows therefore needs a contiguous run of extended rows, even across images.
+#include "internal.h"
+
+namespace sgprs {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+struct PatchArgs {
+    const unsigned char* x;
+    const unsigned char* w;
+    unsigned char* y;
+    const float* scale;
+    const float* shift;
+    const unsigned char* res;
+    float* partial;
+    int H, W, Cin, Cout, NH;  // NH = N*H output rows in total
+    int PW, HE;               // W+2, H+2
+    unsigned mW, mPW, mHE, mH;  // ceil(2^32/d) multipliers for exact division
+    int TR;                   // output rows per tile
+    int n_mtiles, n_ntiles, n_chunks, chunks_per_split, splits;
+    int relu;
+};
+
+__device__ __forceinline__ unsigned fdiv(unsigned x, unsigned magic) { return __umulhi(x, magic); }
+
+template <int BM, int BN, int KC, int NW = 4> struct PatchCfg {
+    static constexpr int NT = NW * 64;                  // threads per workgroup
+    static constexpr int CPP = KC / 8;                  // 16-byte chunks per pixel
+    static constexpr int PS = KC * 2;                   // bytes per pixel of one chunk
+    static constexpr int PSP = PS + 16;                 // padded LDS pixel stride: 16 consecutive pixels hit 16 distinct bank groups
+    static constexpr int PCAP_PIX = BM == 256 ? 512 : 256;  // patch capacity in pixels
+    static constexpr int PCAP_IDS = PCAP_PIX * CPP;
+    static constexpr int P_IT = PCAP_IDS / NT;
+    static constexpr int PATCH_BYTES = PCAP_PIX * PSP;
+    static constexpr int WROWB = 9 * KC * 2 + 16;       // padded weight row
+    static constexpr int W_IDS = BN * 9 * CPP;
+    static constexpr int W_IT = W_IDS / NT;
+    static constexpr int LDS_BYTES = PATCH_BYTES + BN * WROWB;
+    static constexpr int WM = NW == 8 ? 4 : (BM == 256 && BN == 64) ? 4 : 2;
+    static constexpr int WN = NW / WM;
+    static constexpr int OCC = LDS_BYTES <= 80 * 1024 ? 2 : 1;  // workgroups per CU
+    static constexpr int WAVES_PER_SIMD = OCC * NW / 4;
+    static_assert(PCAP_IDS % NT == 0 && W_IDS % NT == 0 && PATCH_BYTES % 16 == 0, "loader shape");
+};
+
+template <int BM, int BN, int KC, bool STAT, bool SPLIT, int NW>
+__global__ __launch_bounds__((NW * 64), (PatchCfg<BM, BN, KC, NW>::WAVES_PER_SIMD)) void conv3x3_patch_kernel(const PatchArgs a)
+{
+    using C = PatchCfg<BM, BN, KC, NW>;
+    constexpr int NT = C::NT;
+    constexpr int CPP = C::CPP, PS = C::PS, PSP = C::PSP, P_IT = C::P_IT, W_IT = C::W_IT, WROWB = C::WROWB;
+    constexpr int WM = C::WM, WN = C::WN;
+    constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
+    constexpr int KS = KC / 16;
+    constexpr bool PRE_RES = C::WAVES_PER_SIMD == 1 && TM * TN <= 4;  // room in the register file: fetch the residual during the last chunk
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char* Ps = smem;
+    unsigned char* Ws = smem + C::PATCH_BYTES;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int frow = lane & 31, fhalf = lane >> 5;
+
+    u32x4_t preg[P_IT];
+    u32x4_t wreg[STAT ? 1 : W_IT];
+
+    const int n_items = a.n_mtiles * a.n_ntiles * a.splits;
+
+    // (item, chunk) -> registers.  Offsets are 32-bit byte offsets from the
+    // tensor base (tensors are below 2^31 elements).
+    auto fetch = [&](int item, int chunk) {
+        const int split = item % a.splits;
+        const int t2 = item / a.splits;
+        const int ntile = t2 % a.n_ntiles, mtile = t2 / a.n_ntiles;
+        const int c0 = (split * a.chunks_per_split + chunk) * KC;
+        const int g0 = mtile * a.TR;
+        const int g1 = min(g0 + a.TR, a.NH) - 1;
+        const int E0 = g0 + 2 * (int)fdiv(g0, a.mH);                 // e(g0) - 1
+        const int R = (g1 + 2 * (int)fdiv(g1, a.mH) + 2) - E0 + 1;   // e(g1) + 1 - E0 + 1
+        const unsigned char* xc = a.x + (size_t)c0 * 2;
+#pragma unroll
+        for (int it = 0; it < P_IT; ++it) {
+            const int id = it * NT + tid;
+            const int pix = id / CPP, ch = id % CPP;
+            const int prow = fdiv(pix, a.mPW), pcol = pix - prow * a.PW;
+            const int E = E0 + prow;
+            const int n = fdiv(E, a.mHE);
+            const int hh = E - n * a.HE - 1, ww = pcol - 1;
+            const bool ok = prow < R && (unsigned)hh < (unsigned)a.H && (unsigned)ww < (unsigned)a.W;
+            u32x4_t v = {0u, 0u, 0u, 0u};
+            if (ok) {
+                const unsigned off = ((unsigned)((n * a.H + hh) * a.W + ww) * (unsigned)a.Cin + ch * 8) * 2u;
+                v = *(const u32x4_t*)(xc + off);
+            }
+            preg[it] = v;
+        }
+        if constexpr (!STAT) {
+            const unsigned char* wc = a.w + ((size_t)ntile * BN * 9 * a.Cin + c0) * 2;
+#pragma unroll
+            for (int it = 0; it < W_IT; ++it) {
+                const int id = it * NT + tid;
+                const int row = id / (9 * CPP), rem = id % (9 * CPP);
+                const int tap = rem / CPP, ch = rem % CPP;
+                const unsigned off = ((unsigned)(row * 9 + tap) * (unsigned)a.Cin + ch * 8) * 2u;
+                wreg[it] = *(const u32x4_t*)(wc + off);
+            }
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int it = 0; it < P_IT; ++it) {
+            const int id = it * NT + tid;
+            *(u32x4_t*)(Ps + (id / CPP) * PSP + (id % CPP) * 16) = preg[it];
+        }
+        if constexpr (!STAT) {
+#pragma unroll
+            for (int it = 0; it < W_IT; ++it) {
+                const int id = it * NT + tid;
+                *(u32x4_t*)(Ws + (id / (9 * CPP)) * WROWB + (id % (9 * CPP)) * 16) = wreg[it];
+            }
+        }
+    };
+
+    if constexpr (STAT) {  // single chunk, single channel block: weights loaded once
+#pragma unroll
+        for (int it = 0; it < W_IT; ++it) {
+            const int id = it * NT + tid;
+            const int row = id / (9 * CPP), rem = id % (9 * CPP);
+            const int tap = rem / CPP, ch = rem % CPP;
+            *(u32x4_t*)(Ws + row * WROWB + rem * 16) =
+                *(const u32x4_t*)(a.w + ((size_t)(row * 9 + tap) * a.Cin + ch * 8) * 2);
+        }
+    }
+
+    int item = blockIdx.x;
+    if (item >= n_items) return;
+    fetch(item, 0);
+
+    // epilogue geometry: after the LDS transpose every lane owns 8 consecutive
+    // channels (c8) of row rsub + pass*RPP of each 32-row piece
+    constexpr int SROW = WTN + 4;   // padded scratch row (floats)
+    constexpr int LPR = WTN / 8;    // lanes per row in the read-back
+    constexpr int RPP = 64 / LPR;   // rows per pass
+    constexpr int NPASS = 32 / RPP;
+    const int c8 = (lane % LPR) * 8, rsub = lane / LPR;
+
+    while (item < n_items) {
+        const int split = item % a.splits;
+        const int t2 = item / a.splits;
+        const int ntile = t2 % a.n_ntiles, mtile = t2 / a.n_ntiles;
+        const int nch = min(a.chunks_per_split, a.n_chunks - split * a.chunks_per_split);
+        const int g0 = mtile * a.TR;
+        const int E0 = g0 + 2 * (int)fdiv(g0, a.mH);
+        const int rows_here = min(a.TR, a.NH - g0);
+        const int m_lim = rows_here * a.W;
+        const int nbase = ntile * BN + wn * WTN + c8;
+
+        // this lane's output pixels (A-fragment rows) -> byte address of their
+        // top-left patch pixel; a tile is TR whole rows, so its output pixels
+        // are contiguous from g0*W
+        int pbase[TM];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int t = wm * WTM + i * 32 + frow;
+            const int pr = fdiv(t, a.mW), q = t - pr * a.W;
+            const bool ok = pr < rows_here;
+            const int g = g0 + (ok ? pr : 0);
+            const int e1 = g + 2 * (int)fdiv(g, a.mH);  // e(g) - 1
+            pbase[i] = ((e1 - E0) * a.PW + (ok ? q : 0)) * PSP + fhalf * 16;
+        }
+
+        f32x4_t sc0 = {1.f, 1.f, 1.f, 1.f}, sc1 = sc0, sh0 = {0.f, 0.f, 0.f, 0.f}, sh1 = sh0;
+        u32x4_t rres[TM][NPASS];
+        auto load_residual = [&]() {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int pass = 0; pass < NPASS; ++pass) {
+                    const int t = wm * WTM + i * 32 + pass * RPP + rsub;
+                    u32x4_t rv = {0u, 0u, 0u, 0u};
+                    if (a.res && t < m_lim)
+                        rv = *(const u32x4_t*)(a.res + (((size_t)g0 * a.W + t) * a.Cout + nbase) * 2);
+                    rres[i][pass] = rv;
+                }
+        };
+
+        f32x16_t acc[TM][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+        const int wbase = C::PATCH_BYTES + (wn * WTN + frow) * WROWB + fhalf * 16;
+        u32x4_t fa[2][TM], fb[2][TN];
+        // fragments of k-step (tap, ks): tap offsets are added to the lane's
+        // base addresses, the k-step is an immediate offset
+        auto load_frags = [&](int set, int pa_off, int wb_off, int ks) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[set][i] = *(const u32x4_t*)(smem + pbase[i] + pa_off + ks * 32);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[set][j] = *(const u32x4_t*)(smem + wbase + wb_off + j * 32 * WROWB + ks * 32);
+        };
+
+        for (int chunk = 0; chunk < nch; ++chunk) {
+            __syncthreads();  // the previous chunk's fragment reads (or epilogue scratch) are done
+            stage();
+            __syncthreads();
+            // prefetch what comes next while this chunk computes
+            if (chunk + 1 < nch) fetch(item, chunk + 1);
+            else if (item + (int)gridDim.x < n_items) fetch(item + gridDim.x, 0);
+            if constexpr (!SPLIT) {
+                // epilogue operands: requested during the last chunk so that they
+                // arrive while its MFMAs run
+                if (chunk + 1 == nch) {
+                    sc0 = *(const f32x4_t*)(a.scale + nbase); sc1 = *(const f32x4_t*)(a.scale + nbase + 4);
+                    sh0 = *(const f32x4_t*)(a.shift + nbase); sh1 = *(const f32x4_t*)(a.shift + nbase + 4);
+                    if constexpr (PRE_RES) load_residual();
+                }
+            }
+            load_frags(0, 0, 0, 0);
+            int r = 0, s = 0;
+#pragma unroll 1
+            for (int tap = 0; tap < 9; ++tap) {
+                int s2 = s + 1, r2 = r;
+                if (s2 == 3) { s2 = 0; r2 = r + 1; }
+                const int pa_cur = (r * a.PW + s) * PSP, pa_next = (r2 * a.PW + s2) * PSP;
+                const int wb_cur = tap * PS, wb_next = wb_cur + PS;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const int cur = ks & 1;
+                    if (ks + 1 < KS) load_frags(cur ^ 1, pa_cur, wb_cur, ks + 1);
+                    else if (tap + 1 < 9) load_frags(cur ^ 1, pa_next, wb_next, 0);
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                __builtin_bit_cast(bf16x8_t, fa[cur][i]), __builtin_bit_cast(bf16x8_t, fb[cur][j]),
+                                acc[i][j], 0, 0, 0);
+                }
+                r = r2; s = s2;
+            }
+        }
+
+        // ---- epilogue.  Accumulator register e of a 32x32 tile holds column
+        // lane%32, row 8*(e/4) + 4*(lane/32) + e%4.  Each wavefront transposes one
+        // 32-row x WTN-column piece at a time through its own LDS scratch so that
+        // every lane then owns 8 consecutive channels of one pixel: 16-byte
+        // residual loads and output stores, scale/shift/residual/ReLU in fp32.
+        if constexpr (!SPLIT && !PRE_RES) load_residual();
+        __syncthreads();  // all fragment reads of the last chunk are done: LDS is free
+        {
+            float* scr = (float*)smem + wave * 32 * SROW;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        scr[(8 * (e >> 2) + 4 * fhalf + (e & 3)) * SROW + j * 32 + frow] = acc[i][j][e];
+                // same wavefront wrote and reads: LDS ops of a wave complete in order
+#pragma unroll
+                for (int pass = 0; pass < NPASS; ++pass) {
+                    const int rr = pass * RPP + rsub;
+                    const int t = wm * WTM + i * 32 + rr;
+                    f32x4_t v0 = *(const f32x4_t*)(scr + rr * SROW + c8);
+                    f32x4_t v1 = *(const f32x4_t*)(scr + rr * SROW + c8 + 4);
+                    if (t < m_lim) {
+                        const size_t m = (size_t)g0 * a.W + t;
+                        if constexpr (SPLIT) {
+                            float* dst = a.partial + ((size_t)split * a.NH * a.W + m) * a.Cout + nbase;
+                            *(f32x4_t*)dst = v0;
+                            *(f32x4_t*)(dst + 4) = v1;
+                        } else {
+                            const u32x4_t rv = rres[i][pass];
+                            v0 = v0 * sc0 + sh0;
+                            v1 = v1 * sc1 + sh1;
+                            float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+                            u32x4_t ov;
+#pragma unroll
+                            for (int u = 0; u < 4; ++u) {
+                                float lo = v[2 * u] + __uint_as_float(rv[u] << 16);
+                                float hi = v[2 * u + 1] + __uint_as_float(rv[u] & 0xffff0000u);
+                                if (a.relu) { lo = fmaxf(lo, 0.f); hi = fmaxf(hi, 0.f); }
+                                const __bf16 l16 = (__bf16)lo, h16 = (__bf16)hi;
+                                ov[u] = (unsigned)__builtin_bit_cast(unsigned short, l16) |
+                                        ((unsigned)__builtin_bit_cast(unsigned short, h16) << 16);
+                            }
+                            *(u32x4_t*)(a.y + (m * a.Cout + nbase) * 2) = ov;
+                        }
+                    }
+                }
+            }
+        }
+        item += gridDim.x;
+    }
+}
+
+// ---- host side ---------------------------------------------------------------
+static unsigned magic_for(unsigned d) { return (unsigned)((0x100000000ull + d - 1) / d); }
+
+struct PatchVariant { int bm, bn, kc; };
+static const PatchVariant kPatchVariants[] = {{256, 64, 64}, {256, 128, 32}, {128, 64, 64}, {128, 128, 32}, {256, 64, 32}, {256, 64, 64}, {256, 128, 32}};
+constexpr int kNumPatchVariants = 7;
+int patch_num_variants() { return kNumPatchVariants; }
+
+const char* patch_variant_name(int v)
+{
+    static const char* names[] = {"conv3x3_patch_kernel<256, 64, 64", "conv3x3_patch_kernel<256, 128, 32",
+                                  "conv3x3_patch_kernel<128, 64, 64", "conv3x3_patch_kernel<128, 128, 32",
+                                  "conv3x3_patch_kernel<256, 64, 32", "conv3x3_patch_kernel<256, 64, 64, *, *, 8",
+                                  "conv3x3_patch_kernel<256, 128, 32, *, *, 8"};
+    return v >= 0 && v < kNumPatchVariants ? names[v] : "?";
+}
+
+bool patch_eligible(const sgprs_conv_desc_t& d)
+{
+    return d.dtype == SGPRS_BF16 && d.r == 3 && d.s == 3 && d.stride == 1 && d.pad == 1 && d.cin % 64 == 0 &&
+           d.cout % 64 == 0 && d.w <= 128 && d.w >= 2 && d.h >= 2 && (long long)d.n * d.h * (d.w + 2) * 8 < (1ll << 24);
+}
+
+// Fills the tile geometry of variant v for this shape; false if it does not fit.
+static bool patch_geometry(const sgprs_conv_desc_t& d, int v, int splits, PatchArgs* a)
+{
+    const PatchVariant& pv = kPatchVariants[v];
+    if (d.cout % pv.bn || d.cin % pv.kc || d.w > pv.bm) return false;
+    const int TR = pv.bm / d.w, NH = d.n * d.h;
+    const int cap = pv.bm == 256 ? 512 : 256;  // patch capacity in pixels
+    const int n_mtiles = (NH + TR - 1) / TR;
+    int rmax = 0;
+    for (int t = 0; t < n_mtiles; ++t) {
+        const int g0 = t * TR, g1 = std::min(g0 + TR, NH) - 1;
+        rmax = std::max(rmax, (g1 + 2 * (g1 / d.h) + 2) - (g0 + 2 * (g0 / d.h)) + 1);
+    }
+    if (rmax * (d.w + 2) > cap) return false;
+    const int n_chunks = d.cin / pv.kc;
+    if (splits < 1 || splits > n_chunks) return false;
+    const int cps = (n_chunks + splits - 1) / splits;
+    if ((splits - 1) * cps >= n_chunks) return false;
+    // exactness of the multiply-high divisions: dividend * divisor < 2^32
+    const unsigned long long lim = 1ull << 32;
+    if ((unsigned long long)(NH + 2 * d.n + 4) * (d.h + 2) >= lim || (unsigned long long)(cap + 256) * (d.w + 2) >= lim) return false;
+    a->H = d.h; a->W = d.w; a->Cin = d.cin; a->Cout = d.cout; a->NH = NH;
+    a->PW = d.w + 2; a->HE = d.h + 2;
+    a->mW = magic_for(d.w); a->mPW = magic_for(d.w + 2); a->mHE = magic_for(d.h + 2); a->mH = magic_for(d.h);
+    a->TR = TR; a->n_mtiles = n_mtiles; a->n_ntiles = d.cout / pv.bn; a->n_chunks = n_chunks;
+    a->chunks_per_split = cps; a->splits = splits; a->relu = d.relu;
+    return true;
+}
+
+static int g_force_variant = -1, g_force_splits = 0;
+void patch_force(int variant, int splits) { g_force_variant = variant; g_force_splits = splits; }
+
+// Picks the tile variant: the candidate with the smallest estimated time
+// rounds(items / CUs) * chunks * cost-per-chunk, the per-chunk costs (in
+// microseconds, whole-GPU measurements at batch 64) only rank candidates.
+// Split-K is left to the implicit-GEMM path: when a shape offers too few work
+// items to fill the partition this kernel declines.
+bool plan_patch(const sgprs_conv_desc_t& d, int cus, int* variant, int* splits)
+{
+    if (!patch_eligible(d)) return false;
+    PatchArgs a;
+    if (g_force_variant >= 0) {
+        if (g_force_variant >= kNumPatchVariants || !patch_geometry(d, g_force_variant, std::max(1, g_force_splits), &a))
+            return false;
+        *variant = g_force_variant; *splits = std::max(1, g_force_splits);
+        return true;
+    }
+    static const struct { int v; double cost; } cand[] = {{5, 7.0}, {6, 7.0}, {3, 4.1}, {2, 4.4}};
+    double best = 1e30;
+    bool found = false;
+    for (const auto& c : cand) {
+        if (!patch_geometry(d, c.v, 1, &a)) continue;
+        const long long items = (long long)a.n_mtiles * a.n_ntiles;
+        if (items * 2 < cus) continue;
+        const long long rounds = (items + cus - 1) / cus;
+        const double cost = rounds * a.n_chunks * c.cost;
+        if (cost < best) { best = cost; *variant = c.v; *splits = 1; found = true; }
+    }
+    return found;
+}
+
+size_t patch_workspace_bytes(const sgprs_conv_desc_t& d, int splits)
+{
+    return splits > 1 ? (size_t)splits * d.n * d.h * d.w * d.cout * sizeof(float) : 0;
+}
+
+template <int BM, int BN, int KC, bool STAT, bool SPLIT, int NW>
+static int launch_patch_inst(const PatchArgs& a, int grid, hipStream_t stream)
+{
+    using C = PatchCfg<BM, BN, KC, NW>;
+    static bool raised = false;
+    if (!raised) {
+        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_kernel<BM, BN, KC, STAT, SPLIT, NW>,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
+        raised = true;
+    }
+    hipLaunchKernelGGL((conv3x3_patch_kernel<BM, BN, KC, STAT, SPLIT, NW>), dim3(grid), dim3(C::NT), C::LDS_BYTES, stream, a);
+    SGPRS_HIP(hipGetLastError());
+    return SGPRS_OK;
+}
+
+template <int BM, int BN, int KC, int NW = 4>
+static int launch_patch_variant(const PatchArgs& a, int grid, bool stat, hipStream_t stream)
+{
+    if (a.splits > 1) return launch_patch_inst<BM, BN, KC, false, true, NW>(a, grid, stream);
+    if constexpr (BM == 256 && BN == 64 && KC == 64)
+        if (stat) return launch_patch_inst<BM, BN, KC, true, false, NW>(a, grid, stream);
+    return launch_patch_inst<BM, BN, KC, false, false, NW>(a, grid, stream);
+}
+
+int launch_splitk_reduce(int dtype, const float* partial, int splits, size_t total, int cout, const float* scale,
+                         const float* shift, const void* res, void* y, int relu, hipStream_t stream);
+
+int launch_conv3x3_patch(const sgprs_conv_desc_t& d, int variant, int splits, const void* x, const void* w,
+                         const float* scale, const float* shift, const void* residual, void* y, void* ws,
+                         size_t ws_bytes, hipStream_t stream, int cus, Profiler* prof)
+{
+    PatchArgs a;
+    if (variant < 0 || variant >= kNumPatchVariants || !patch_eligible(d) || !patch_geometry(d, variant, splits, &a))
+        return fail(SGPRS_ERR_INVALID_ARG, "internal: patch plan does not match the shape");
+    const size_t need = patch_workspace_bytes(d, splits);
+    if (need > ws_bytes || (need && !ws))
+        return fail(SGPRS_ERR_INVALID_ARG, "split-K workspace %zu bytes needed, %zu given", need, ws_bytes);
+    a.x = (const unsigned char*)x; a.w = (const unsigned char*)w; a.y = (unsigned char*)y;
+    a.scale = scale; a.shift = shift; a.res = (const unsigned char*)residual; a.partial = (float*)ws;
+    const long long items = (long long)a.n_mtiles * a.n_ntiles * a.splits;
+    const int occ = variant == 4 ? 2 : 1;
+    const int grid = (int)std::min<long long>(items, (long long)cus * occ);
+    const bool stat = a.n_chunks == 1 && a.n_ntiles == 1 && a.splits == 1;
+    const double M = (double)d.n * d.h * d.w;
+    const double flops = 2.0 * M * d.cout * 9.0 * d.cin;
+    const double bytes = (M * d.cin + (double)d.cout * 9 * d.cin + M * d.cout * (residual ? 2 : 1)) * 2.0;
+    int rc;
+    if (prof && prof->on && (rc = prof->begin(stream, kKindPatch, variant, flops, bytes))) return rc;
+    switch (variant) {
+        case 0: rc = launch_patch_variant<256, 64, 64>(a, grid, stat, stream); break;
+        case 1: rc = launch_patch_variant<256, 128, 32>(a, grid, stat, stream); break;
+        case 2: rc = launch_patch_variant<128, 64, 64>(a, grid, stat, stream); break;
+        case 4: rc = launch_patch_variant<256, 64, 32>(a, grid, stat, stream); break;
+        case 5: rc = launch_patch_variant<256, 64, 64, 8>(a, grid, stat, stream); break;
+        case 6: rc = launch_patch_variant<256, 128, 32, 8>(a, grid, stat, stream); break;
+        default: rc = launch_patch_variant<128, 128, 32>(a, grid, stat, stream); break;
+    }
+    if (rc) return rc;
+    if (prof && prof->on && (rc = prof->end(stream))) return rc;
+    if (splits > 1) {
+        const size_t total = (size_t)M * d.cout;
+        if (prof && prof->on &&
+            (rc = prof->begin(stream, kKindReduce, d.dtype, 0.0, (double)total * 4.0 * splits + total * 2.0)))
+            return rc;
+        if ((rc = launch_splitk_reduce(d.dtype, a.partial, splits, total, d.cout, scale, shift, residual, y, d.relu, stream)))
+            return rc;
+        if (prof && prof->on && (rc = prof->end(stream))) return rc;
+    }
+    return SGPRS_OK;
+}
+
+}  // namespace sgprs

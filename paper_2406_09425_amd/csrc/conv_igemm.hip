@@ -277,12 +277,29 @@ const char* igemm_variant_name(int dtype, int variant)
     return names[dtype][variant];
 }
 
+int launch_splitk_reduce(int dtype, const float* partial, int splits, size_t total, int cout, const float* scale,
+                         const float* shift, const void* res, void* y, int relu, hipStream_t stream)
+{
+    const unsigned blocks = (unsigned)((total / 4 + 255) / 256);
+    if (dtype == SGPRS_BF16)
+        hipLaunchKernelGGL(splitk_reduce_kernel<SGPRS_BF16>, dim3(blocks), dim3(256), 0, stream, partial, splits, total,
+                           cout, scale, shift, (const unsigned char*)res, (unsigned char*)y, relu);
+    else
+        hipLaunchKernelGGL(splitk_reduce_kernel<SGPRS_F32>, dim3(blocks), dim3(256), 0, stream, partial, splits, total,
+                           cout, scale, shift, (const unsigned char*)res, (unsigned char*)y, relu);
+    SGPRS_HIP(hipGetLastError());
+    return SGPRS_OK;
+}
+
 int launch_conv(const sgprs_conv_desc_t& d, const void* x, const void* w, const float* scale,
                 const float* shift, const void* residual, void* y, void* ws, size_t ws_bytes,
                 hipStream_t stream, int cus, Profiler* prof)
 {
     const ConvPlan p = plan_conv(d, cus);
     if (p.bm == 0) return fail(SGPRS_ERR_UNSUPPORTED, "no tile shape fits cout %d", d.cout);
+    if (p.kind == 1)
+        return launch_conv3x3_patch(d, p.variant, p.splits, x, w, scale, shift, residual, y, ws, ws_bytes, stream, cus,
+                                    prof);
     const size_t need = conv_workspace_bytes(d, p);
     if (need > ws_bytes || (need && !ws))
         return fail(SGPRS_ERR_INVALID_ARG, "split-K workspace %zu bytes needed, %zu given", need, ws_bytes);
@@ -310,17 +327,12 @@ int launch_conv(const sgprs_conv_desc_t& d, const void* x, const void* w, const 
     if (prof && prof->on && (rc = prof->end(stream))) return rc;
     if (p.splits > 1) {
         const size_t total = (size_t)a.M * d.cout;
-        const unsigned blocks = (unsigned)((total / 4 + 255) / 256);
         if (prof && prof->on &&
             (rc = prof->begin(stream, kKindReduce, d.dtype, 0.0, (double)total * 4.0 * p.splits + total * es)))
             return rc;
-        if (d.dtype == SGPRS_BF16)
-            hipLaunchKernelGGL(splitk_reduce_kernel<SGPRS_BF16>, dim3(blocks), dim3(256), 0, stream, a.partial,
-                               p.splits, total, d.cout, scale, shift, a.res, a.y, d.relu);
-        else
-            hipLaunchKernelGGL(splitk_reduce_kernel<SGPRS_F32>, dim3(blocks), dim3(256), 0, stream, a.partial,
-                               p.splits, total, d.cout, scale, shift, a.res, a.y, d.relu);
-        SGPRS_HIP(hipGetLastError());
+        if ((rc = launch_splitk_reduce(d.dtype, a.partial, p.splits, total, d.cout, scale, shift, a.res, a.y, d.relu,
+                                       stream)))
+            return rc;
         if (prof && prof->on && (rc = prof->end(stream))) return rc;
     }
     return SGPRS_OK;

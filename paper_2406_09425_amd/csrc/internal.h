@@ -86,7 +86,8 @@ inline int out_dim(int in, int k, int stride, int pad) { return (in + 2 * pad - 
 
 // Tile configuration of one implicit-GEMM launch.
 struct ConvPlan {
-    int variant = 0;   // index into the tile table
+    int kind = 0;      // 0: implicit GEMM, 1: LDS-patch 3x3 kernel
+    int variant = 0;   // index into the kernel's tile table
     int bm = 0, bn = 0;
     int splits = 1;    // split-K factor (grid.z)
     int ktiles = 0;    // total k-tiles of 128 bytes
@@ -116,7 +117,7 @@ struct Profiler {
 };
 
 enum KernelKind { kKindIgemm = 0, kKindStem = 1, kKindReduce = 2, kKindMaxpool = 3, kKindAvgpool = 4,
-                  kKindFc = 5, kKindBnRelu = 6, kKindAdd = 7 };
+                  kKindFc = 5, kKindBnRelu = 6, kKindAdd = 7, kKindPatch = 8 };
 
 // launchers (device pointers; validated by callers)
 int launch_conv(const sgprs_conv_desc_t& d, const void* x, const void* w, const float* scale,
@@ -134,6 +135,18 @@ int launch_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void* x
                       const float* bias, float* logits, float* ws, hipStream_t stream, int cus,
                       Profiler* prof);
 int launch_probe(int n_blocks, int spin_cycles, uint32_t* out, hipStream_t stream);
+
+// LDS-patch 3x3 kernel (bf16, stride 1)
+bool plan_patch(const sgprs_conv_desc_t& d, int cus, int* variant, int* splits);
+void patch_force(int variant, int splits);
+const char* patch_variant_name(int variant);
+int launch_conv3x3_patch(const sgprs_conv_desc_t& d, int variant, int splits, const void* x, const void* w,
+                         const float* scale, const float* shift, const void* residual, void* y, void* ws,
+                         size_t ws_bytes, hipStream_t stream, int cus, Profiler* prof);
+int launch_splitk_reduce(int dtype, const float* partial, int splits, size_t total, int cout, const float* scale,
+                         const float* shift, const void* res, void* y, int relu, hipStream_t stream);
+// tuning override: kind -1 automatic, 0 implicit GEMM only, 1 force patch (variant, splits)
+extern int g_conv_force_kind;
 
 const char* igemm_variant_name(int dtype, int variant);
 int igemm_num_variants();

@@ -60,6 +60,14 @@ int sgprs_conv2d(const sgprs_conv_desc_t* d, const void* x, const void* w_packed
     return launch_conv(*d, x, w_packed, scale, shift, residual, y, workspace, workspace_bytes, stream, cus, nullptr);
 }
 
+int sgprs_conv_tuning_override(int kind, int variant, int splits)
+{
+    if (kind < -1 || kind > 1) return fail(SGPRS_ERR_INVALID_ARG, "kind %d outside [-1,1]", kind);
+    g_conv_force_kind = kind;
+    patch_force(kind == 1 ? variant : -1, splits);
+    return SGPRS_OK;
+}
+
 int sgprs_maxpool2d(int dtype, int n, int h, int w, int c, const void* x, void* y, sgprs_pool_t* pool,
                     int partition)
 {

@@ -52,8 +52,19 @@ static const Tile kTiles[] = {{128, 128, 1.0}, {128, 64, 0.85}, {64, 64, 0.6}, {
 
 int igemm_num_variants() { return (int)(sizeof(kTiles) / sizeof(kTiles[0])); }
 
+int g_conv_force_kind = -1;
+
 ConvPlan plan_conv(const sgprs_conv_desc_t& d, int cus)
 {
+    if (g_conv_force_kind != 0) {
+        int v = 0, s = 1;
+        if (plan_patch(d, cus < 1 ? 1 : cus, &v, &s)) {
+            ConvPlan p;
+            p.kind = 1; p.variant = v; p.splits = s;
+            p.bm = 1;  // marks a valid plan
+            return p;
+        }
+    }
     const int P = out_dim(d.h, d.r, d.stride, d.pad), Q = out_dim(d.w, d.s, d.stride, d.pad);
     const long long M = (long long)d.n * P * Q;
     const int kt_el = d.dtype == SGPRS_BF16 ? 64 : 32;

@@ -373,6 +373,7 @@ const char* sgprs_kernel_name(int kind, int variant)
 {
     switch (kind) {
         case kKindIgemm: return igemm_variant_name(variant / 4, variant % 4);
+        case kKindPatch: return patch_variant_name(variant);
         case kKindStem: return "conv_stem_kernel";
         case kKindReduce: return "splitk_reduce_kernel";
         case kKindMaxpool: return "maxpool3x3s2_kernel";

@@ -208,3 +208,49 @@ def test_error_paths_enqueue_nothing(pools):
     assert e.value.status == -5
     with pytest.raises(S.SgprsError):
         S.sgprs_add_relu(S.SGPRS_F32, 12, x.data_ptr(), x.data_ptr(), x.data_ptr(), False, pool, 0)
+
+
+# ---- the LDS-patch 3x3 kernel, every tile variant forced in turn ----------------
+PATCH_SHAPES = [
+    # n, h, w, cin, cout: tiles straddle image boundaries, ragged last tile, several channel blocks/chunks
+    (5, 14, 14, 64, 64),
+    (3, 28, 28, 64, 128),
+    (9, 7, 7, 128, 64),
+    (2, 56, 56, 64, 64),
+    (7, 9, 11, 128, 128),
+]
+
+
+@pytest.mark.parametrize("variant", range(7))
+@pytest.mark.parametrize("shape", PATCH_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_conv3x3_patch_variants_parity(pools, variant, shape):
+    n, h, w, cin, cout = shape
+    pool = pools["full"]
+    dtype = S.SGPRS_BF16
+    try:
+        for splits in (1, 2):
+            S.sgprs_conv_tuning_override(1, variant, splits)
+            for with_res in (True, False):
+                got, ref = conv_case(dtype, n, h, w, cin, cout, 3, 1, 1, relu=with_res, with_res=with_res,
+                                     seed=50 + variant, pool=pool, cus=pool.partition_cus(0))
+                assert_close(got, ref, dtype, f"patch variant {variant} splits {splits} {shape}")
+    finally:
+        S.sgprs_conv_tuning_override(-1, 0, 1)
+
+
+def test_conv_planner_choices_agree(pools):
+    """Automatic choice, implicit GEMM only and a forced patch variant give the
+    same result to bf16 rounding on a batch large enough for the patch kernel."""
+    pool = pools["full"]
+    shape = (64, 14, 14, 64, 64, 3, 1, 1)
+    outs = []
+    try:
+        for kind in (-1, 0, 1):
+            S.sgprs_conv_tuning_override(kind, 5, 1)
+            got, ref = conv_case(S.SGPRS_BF16, *shape, relu=True, with_res=True, seed=61, pool=pool,
+                                 cus=pool.partition_cus(0))
+            assert_close(got, ref, S.SGPRS_BF16, f"kind {kind}")
+            outs.append(got)
+    finally:
+        S.sgprs_conv_tuning_override(-1, 0, 1)
+    assert rel_err(outs[0], outs[1]) < 1e-2 and rel_err(outs[2], outs[1]) < 1e-2
