@@ -156,8 +156,8 @@ def main():
                     unit="TFLOP/s", frac=round(dfl / dt_s / PEAK_BF16, 4), traffic=None,
                     avg_launch_us=round(dt_s / dcnt * 1e6, 2), launches_per_step=dcnt // prof_steps,
                     flop_per_launch=round(dfl / dcnt, 1))
-    conv_t = sum(v[0] for k, v in agg.items() if k[1] in (0, 1, 2, 8))
-    conv_fl = sum(v[1] for k, v in agg.items() if k[1] in (0, 1, 8))
+    conv_t = sum(v[0] for k, v in agg.items() if k[1] in (0, 1, 2, 8, 9))
+    conv_fl = sum(v[1] for k, v in agg.items() if k[1] in (0, 1, 8, 9))
     conv_all = dict(tflops=round(conv_fl / conv_t / 1e12, 2), mfma_frac=round(conv_fl / conv_t / PEAK_BF16, 4),
                     us_per_step=round(conv_t / prof_steps * 1e6, 1))
     log("roofline:", json.dumps(roofline))

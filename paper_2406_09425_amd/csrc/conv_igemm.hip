@@ -188,27 +188,72 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const IgemmArgs a)
 
     // ---- epilogue.  32x32 accumulator layout: column = lane % 32,
     // row = 8*(e/4) + 4*(lane/32) + e%4 for register e.
+    // Each wavefront transposes one 32-row x WTN-column piece at a time through
+    // its own LDS scratch (the k-loop ended with a barrier, so the staging
+    // buffers are free); afterwards a lane owns 8 consecutive channels of one
+    // output pixel and moves 16 (bf16) or 32 (fp32) contiguous bytes.
+    constexpr int SROW = WTN + 4;  // padded scratch row, floats
+    constexpr int LPR = WTN / 8;   // lanes per row in the read-back
+    constexpr int RPP = 64 / LPR;  // rows per pass
+    constexpr int NPASS = 32 / RPP;
+    static_assert(4 * 32 * SROW * 4 <= 2 * STAGE, "epilogue scratch fits the staging buffers");
+    float* scr = (float*)smem + wave * 32 * SROW;
+    const int c8 = (lane % LPR) * 8, rsub = lane / LPR;
+    const int nb = n0 + wn * WTN + c8;
+    f32x4_t sc0 = {1.f, 1.f, 1.f, 1.f}, sc1 = sc0, sh0 = {0.f, 0.f, 0.f, 0.f}, sh1 = sh0;
+    if constexpr (!SPLIT) {
+        sc0 = *(const f32x4_t*)(a.scale + nb); sc1 = *(const f32x4_t*)(a.scale + nb + 4);
+        sh0 = *(const f32x4_t*)(a.shift + nb); sh1 = *(const f32x4_t*)(a.shift + nb + 4);
+    }
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int n = n0 + wn * WTN + j * 32 + frow;
-        float sc = 1.f, sh = 0.f;
-        if constexpr (!SPLIT) { sc = a.scale[n]; sh = a.shift[n]; }
+    for (int i = 0; i < TM; ++i) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int m = m0 + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * fhalf + (e & 3);
-                if (m >= a.M) continue;
-                if constexpr (SPLIT) {
-                    a.partial[((size_t)blockIdx.z * a.M + m) * a.Cout + n] = acc[i][j][e];
+            for (int e = 0; e < 16; ++e)
+                scr[(8 * (e >> 2) + 4 * fhalf + (e & 3)) * SROW + j * 32 + frow] = acc[i][j][e];
+#pragma unroll
+        for (int pass = 0; pass < NPASS; ++pass) {
+            const int rr = pass * RPP + rsub;
+            const int m = m0 + wm * WTM + i * 32 + rr;
+            f32x4_t v0 = *(const f32x4_t*)(scr + rr * SROW + c8);
+            f32x4_t v1 = *(const f32x4_t*)(scr + rr * SROW + c8 + 4);
+            if (m >= a.M) continue;
+            if constexpr (SPLIT) {
+                float* dst = a.partial + ((size_t)blockIdx.z * a.M + m) * a.Cout + nb;
+                *(f32x4_t*)dst = v0;
+                *(f32x4_t*)(dst + 4) = v1;
+            } else {
+                const size_t o = (size_t)m * a.Cout + nb;
+                v0 = v0 * sc0 + sh0;
+                v1 = v1 * sc1 + sh1;
+                if constexpr (DT == SGPRS_F32) {
+                    if (a.res) {
+                        v0 += *(const f32x4_t*)(a.res + o * 4);
+                        v1 += *(const f32x4_t*)(a.res + o * 4 + 16);
+                    }
+                    if (a.relu) {
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) { v0[u] = fmaxf(v0[u], 0.f); v1[u] = fmaxf(v1[u], 0.f); }
+                    }
+                    *(f32x4_t*)(a.y + o * 4) = v0;
+                    *(f32x4_t*)(a.y + o * 4 + 16) = v1;
                 } else {
-                    const size_t o = (size_t)m * a.Cout + n;
-                    float v = acc[i][j][e] * sc + sh;
-                    if (a.res) v += Store<DT>::load(a.res, o);
-                    if (a.relu) v = fmaxf(v, 0.f);
-                    Store<DT>::store(a.y, o, v);
+                    float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+                    u32x4_t rv = {0u, 0u, 0u, 0u};
+                    if (a.res) rv = *(const u32x4_t*)(a.res + o * 2);
+                    u32x4_t ov;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        float lo = v[2 * u] + __uint_as_float(rv[u] << 16);
+                        float hi = v[2 * u + 1] + __uint_as_float(rv[u] & 0xffff0000u);
+                        if (a.relu) { lo = fmaxf(lo, 0.f); hi = fmaxf(hi, 0.f); }
+                        ov[u] = (unsigned)f32_to_bf16(lo) | ((unsigned)f32_to_bf16(hi) << 16);
+                    }
+                    *(u32x4_t*)(a.y + o * 2) = ov;
                 }
             }
+        }
     }
 }
 

@@ -117,7 +117,7 @@ struct Profiler {
 };
 
 enum KernelKind { kKindIgemm = 0, kKindStem = 1, kKindReduce = 2, kKindMaxpool = 3, kKindAvgpool = 4,
-                  kKindFc = 5, kKindBnRelu = 6, kKindAdd = 7, kKindPatch = 8 };
+                  kKindFc = 5, kKindBnRelu = 6, kKindAdd = 7, kKindPatch = 8, kKindStemPool = 9 };
 
 // launchers (device pointers; validated by callers)
 int launch_conv(const sgprs_conv_desc_t& d, const void* x, const void* w, const float* scale,
@@ -135,6 +135,10 @@ int launch_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void* x
                       const float* bias, float* logits, float* ws, hipStream_t stream, int cus,
                       Profiler* prof);
 int launch_probe(int n_blocks, int spin_cycles, uint32_t* out, hipStream_t stream);
+// stage 0 fused: conv7x7/2 + BN + ReLU + max-pool 3x3/2
+bool stem_pool_applicable(int dtype, int n, int h, int w, int cus);
+int launch_stem_pool(int dtype, int n, int h, int w, const void* x, const void* wts, const float* scale,
+                     const float* shift, void* y, hipStream_t stream, int cus, Profiler* prof);
 
 // LDS-patch 3x3 kernel (bf16, stride 1)
 bool plan_patch(const sgprs_conv_desc_t& d, int cus, int* variant, int* splits);

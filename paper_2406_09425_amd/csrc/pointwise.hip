@@ -124,28 +124,38 @@ __global__ __launch_bounds__(256) void add_relu_kernel(const void* __restrict__ 
 }
 
 // ---- global average pool: x [n][hw][c] -> v [n][c] fp32 ---------------------
+// One workgroup per (image, 64 channel vectors): the four wavefronts take
+// every fourth position, partial sums meet in LDS and are added in wavefront
+// order, so the result does not depend on timing.
 template <int DT>
 __global__ __launch_bounds__(256) void avgpool_kernel(const void* __restrict__ x, float* __restrict__ v, int HW,
-                                                      int C, size_t total_vec)
+                                                      int C)
 {
     constexpr int N = Vec<DT>::N;
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total_vec) return;
+    __shared__ float part[4][64][N];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int cv = C / N;
-    const int c = (int)(idx % cv);
-    const size_t n = idx / cv;
+    const int c = blockIdx.x * 64 + lane;
+    const size_t n = blockIdx.y;
     float s[N];
 #pragma unroll
     for (int i = 0; i < N; ++i) s[i] = 0.f;
-    for (int j = 0; j < HW; ++j) {
-        Vec<DT> t;
-        t.load(x, (n * HW + j) * cv + c);
+    if (c < cv)
+        for (int j = wave; j < HW; j += 4) {
+            Vec<DT> t;
+            t.load(x, (n * HW + j) * cv + c);
 #pragma unroll
-        for (int i = 0; i < N; ++i) s[i] += t.v[i];
+            for (int i = 0; i < N; ++i) s[i] += t.v[i];
+        }
+#pragma unroll
+    for (int i = 0; i < N; ++i) part[wave][lane][i] = s[i];
+    __syncthreads();
+    if (wave == 0 && c < cv) {
+        const float hw = (float)HW;
+#pragma unroll
+        for (int i = 0; i < N; ++i)
+            v[(n * cv + c) * N + i] = (((part[0][lane][i] + part[1][lane][i]) + part[2][lane][i]) + part[3][lane][i]) / hw;
     }
-    const float hw = (float)HW;
-#pragma unroll
-    for (int i = 0; i < N; ++i) v[(n * cv + c) * N + i] = s[i] / hw;
 }
 
 // ---- FC: logits[n][o] = sum_c w[o][c] v[n][c] + b[o] ------------------------
@@ -280,14 +290,12 @@ int launch_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void* x
 {
     const int vec = dtype == SGPRS_BF16 ? 8 : 4;
     const size_t es = dtype_size(dtype);
-    const size_t total = (size_t)n * (cin / vec);
     PROF_BEGIN(kKindAvgpool, dtype, (double)n * hw * cin, (double)n * hw * cin * es + (double)n * cin * 4);
+    const dim3 pgrid((cin / vec + 63) / 64, n);
     if (dtype == SGPRS_BF16)
-        hipLaunchKernelGGL(avgpool_kernel<SGPRS_BF16>, dim3(blocks_for(total)), dim3(256), 0, stream, x, ws, hw, cin,
-                           total);
+        hipLaunchKernelGGL(avgpool_kernel<SGPRS_BF16>, pgrid, dim3(256), 0, stream, x, ws, hw, cin);
     else
-        hipLaunchKernelGGL(avgpool_kernel<SGPRS_F32>, dim3(blocks_for(total)), dim3(256), 0, stream, x, ws, hw, cin,
-                           total);
+        hipLaunchKernelGGL(avgpool_kernel<SGPRS_F32>, pgrid, dim3(256), 0, stream, x, ws, hw, cin);
     SGPRS_HIP(hipGetLastError());
     PROF_END();
 

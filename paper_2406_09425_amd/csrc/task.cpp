@@ -151,6 +151,9 @@ int run_stage(sgprs_task* t, int j, int batch, const void* in, void* out, hipStr
     prof->reset();
     int rc;
     if (j == 0) {
+        if (stem_pool_applicable(t->dtype, batch, 224, 224, cus))
+            return launch_stem_pool(t->dtype, batch, 224, 224, in, t->conv[0].w, t->conv[0].scale, t->conv[0].shift, out, s,
+                                    cus, prof);
         if ((rc = run_conv(t, 0, batch, in, nullptr, t->stem_out, 1, s, cus, prof))) return rc;
         return launch_maxpool(t->dtype, batch, 112, 112, 64, t->stem_out, out, s, cus, prof);
     }
@@ -375,6 +378,7 @@ const char* sgprs_kernel_name(int kind, int variant)
         case kKindIgemm: return igemm_variant_name(variant / 4, variant % 4);
         case kKindPatch: return patch_variant_name(variant);
         case kKindStem: return "conv_stem_kernel";
+        case kKindStemPool: return "stem_pool_kernel";
         case kKindReduce: return "splitk_reduce_kernel";
         case kKindMaxpool: return "maxpool3x3s2_kernel";
         case kKindAvgpool: return "avgpool_kernel";

@@ -233,6 +233,6 @@ def test_kernel_times_records(full_pool, cfg1):
     for j in range(6):
         recs = task.kernel_times(j)
         assert recs and all(r["ms"] >= 0 for r in recs)
-        flops += sum(r["flops"] for r in recs if r["kind"] in (0, 1, 5, 8))
+        flops += sum(r["flops"] for r in recs if r["kind"] in (0, 1, 5, 8, 9))
     assert abs(flops - 2 * 1814073344) / (2 * 1814073344) < 1e-9
     task.destroy()
