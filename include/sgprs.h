@@ -234,7 +234,8 @@ int sgprs_task_set_profiling(sgprs_task_t *task, int on);
 int sgprs_task_kernel_times(sgprs_task_t *task, int stage, int *count, int *kind, int *variant,
                             float *ms, double *flops, double *bytes);
 /* Name of the kernel instantiation behind (kind, variant), for matching
- * profiler rows; static storage. */
+ * profiler rows; points into a small ring of static buffers (copy it before
+ * asking for more than eight names). */
 const char *sgprs_kernel_name(int kind, int variant);
 
 #ifdef __cplusplus

@@ -330,13 +330,18 @@ static const PatchVariant kPatchVariants[] = {{256, 64, 64}, {256, 128, 32}, {12
 constexpr int kNumPatchVariants = 7;
 int patch_num_variants() { return kNumPatchVariants; }
 
+// Name as a profiler prints it: v = tile variant + 16 * stationary + 32 * split.
 const char* patch_variant_name(int v)
 {
-    static const char* names[] = {"conv3x3_patch_kernel<256, 64, 64", "conv3x3_patch_kernel<256, 128, 32",
-                                  "conv3x3_patch_kernel<128, 64, 64", "conv3x3_patch_kernel<128, 128, 32",
-                                  "conv3x3_patch_kernel<256, 64, 32", "conv3x3_patch_kernel<256, 64, 64, *, *, 8",
-                                  "conv3x3_patch_kernel<256, 128, 32, *, *, 8"};
-    return v >= 0 && v < kNumPatchVariants ? names[v] : "?";
+    static char buf[8][96];
+    static int next = 0;
+    const int tv = v & 15;
+    if (tv >= kNumPatchVariants) return "?";
+    const PatchVariant& pv = kPatchVariants[tv];
+    char* out = buf[next++ & 7];
+    snprintf(out, 96, "conv3x3_patch_kernel<%d, %d, %d, %s, %s, %d>", pv.bm, pv.bn, pv.kc, (v & 16) ? "true" : "false",
+             (v & 32) ? "true" : "false", tv >= 5 ? 8 : 4);
+    return out;
 }
 
 bool patch_eligible(const sgprs_conv_desc_t& d)
@@ -421,7 +426,7 @@ static int launch_patch_inst(const PatchArgs& a, int grid, hipStream_t stream)
                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
         raised = true;
     }
-    hipLaunchKernelGGL((conv3x3_patch_kernel<BM, BN, KC, STAT, SPLIT, NW>), dim3(grid), dim3(C::NT), C::LDS_BYTES, stream, a);
+    SGPRS_LAUNCH((conv3x3_patch_kernel<BM, BN, KC, STAT, SPLIT, NW>), dim3(grid), dim3(C::NT), C::LDS_BYTES, stream, a);
     SGPRS_HIP(hipGetLastError());
     return SGPRS_OK;
 }
@@ -458,7 +463,7 @@ int launch_conv3x3_patch(const sgprs_conv_desc_t& d, int variant, int splits, co
     const double flops = 2.0 * M * d.cout * 9.0 * d.cin;
     const double bytes = (M * d.cin + (double)d.cout * 9 * d.cin + M * d.cout * (residual ? 2 : 1)) * 2.0;
     int rc;
-    if (prof && prof->on && (rc = prof->begin(stream, kKindPatch, variant, flops, bytes))) return rc;
+    if (prof && prof->on && (rc = prof->begin(stream, kKindPatch, variant + (stat && variant % 5 == 0 ? 16 : 0) + (splits > 1 ? 32 : 0), flops, bytes))) return rc;
     switch (variant) {
         case 0: rc = launch_patch_variant<256, 64, 64>(a, grid, stat, stream); break;
         case 1: rc = launch_patch_variant<256, 128, 32>(a, grid, stat, stream); break;

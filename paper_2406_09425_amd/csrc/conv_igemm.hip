@@ -292,9 +292,9 @@ static int launch_variant(const IgemmArgs& a, const ConvPlan& p, hipStream_t str
     const dim3 grid(p.grid_m, p.grid_n, p.splits), block(256);
     const size_t lds = 2 * (BM + BN) * 128;
     if (p.splits > 1)
-        hipLaunchKernelGGL((conv_igemm_kernel<DT, BM, BN, WM, WN, true>), grid, block, lds, stream, a);
+        SGPRS_LAUNCH((conv_igemm_kernel<DT, BM, BN, WM, WN, true>), grid, block, lds, stream, a);
     else
-        hipLaunchKernelGGL((conv_igemm_kernel<DT, BM, BN, WM, WN, false>), grid, block, lds, stream, a);
+        SGPRS_LAUNCH((conv_igemm_kernel<DT, BM, BN, WM, WN, false>), grid, block, lds, stream, a);
     SGPRS_HIP(hipGetLastError());
     return SGPRS_OK;
 }
@@ -311,15 +311,18 @@ static int launch_dtype(const IgemmArgs& a, const ConvPlan& p, hipStream_t strea
     }
 }
 
-const char* igemm_variant_name(int dtype, int variant)
+// Name as a profiler prints it: v = tile variant + 4 * dtype + 8 * split.
+const char* igemm_variant_name(int v)
 {
-    static const char* names[2][4] = {
-        {"conv_igemm_kernel<0, 128, 128, 2, 2", "conv_igemm_kernel<0, 128, 64, 2, 2",
-         "conv_igemm_kernel<0, 64, 64, 2, 2", "conv_igemm_kernel<0, 32, 128, 1, 4"},
-        {"conv_igemm_kernel<1, 128, 128, 2, 2", "conv_igemm_kernel<1, 128, 64, 2, 2",
-         "conv_igemm_kernel<1, 64, 64, 2, 2", "conv_igemm_kernel<1, 32, 128, 1, 4"}};
-    if (!dtype_ok(dtype) || variant < 0 || variant >= 4) return "?";
-    return names[dtype][variant];
+    static const int shape[4][4] = {{128, 128, 2, 2}, {128, 64, 2, 2}, {64, 64, 2, 2}, {32, 128, 1, 4}};
+    static char buf[8][96];
+    static int next = 0;
+    if (v < 0 || v >= 16) return "?";
+    const int* t = shape[v & 3];
+    char* out = buf[next++ & 7];
+    snprintf(out, 96, "conv_igemm_kernel<%d, %d, %d, %d, %d, %s>", (v >> 2) & 1, t[0], t[1], t[2], t[3],
+             (v & 8) ? "true" : "false");
+    return out;
 }
 
 int launch_splitk_reduce(int dtype, const float* partial, int splits, size_t total, int cout, const float* scale,
@@ -327,10 +330,10 @@ int launch_splitk_reduce(int dtype, const float* partial, int splits, size_t tot
 {
     const unsigned blocks = (unsigned)((total / 4 + 255) / 256);
     if (dtype == SGPRS_BF16)
-        hipLaunchKernelGGL(splitk_reduce_kernel<SGPRS_BF16>, dim3(blocks), dim3(256), 0, stream, partial, splits, total,
+        SGPRS_LAUNCH(splitk_reduce_kernel<SGPRS_BF16>, dim3(blocks), dim3(256), 0, stream, partial, splits, total,
                            cout, scale, shift, (const unsigned char*)res, (unsigned char*)y, relu);
     else
-        hipLaunchKernelGGL(splitk_reduce_kernel<SGPRS_F32>, dim3(blocks), dim3(256), 0, stream, partial, splits, total,
+        SGPRS_LAUNCH(splitk_reduce_kernel<SGPRS_F32>, dim3(blocks), dim3(256), 0, stream, partial, splits, total,
                            cout, scale, shift, (const unsigned char*)res, (unsigned char*)y, relu);
     SGPRS_HIP(hipGetLastError());
     return SGPRS_OK;
@@ -366,7 +369,7 @@ int launch_conv(const sgprs_conv_desc_t& d, const void* x, const void* w, const 
     const double bytes = ((double)d.n * d.h * d.w * d.cin + (double)d.cout * d.r * d.s * d.cin +
                           (double)a.M * d.cout * (residual ? 2 : 1)) * es;
     int rc;
-    if (prof && prof->on && (rc = prof->begin(stream, kKindIgemm, d.dtype * 4 + p.variant, flops, bytes))) return rc;
+    if (prof && prof->on && (rc = prof->begin(stream, kKindIgemm, d.dtype * 4 + p.variant + (p.splits > 1 ? 8 : 0), flops, bytes))) return rc;
     rc = d.dtype == SGPRS_BF16 ? launch_dtype<SGPRS_BF16>(a, p, stream) : launch_dtype<SGPRS_F32>(a, p, stream);
     if (rc) return rc;
     if (prof && prof->on && (rc = prof->end(stream))) return rc;

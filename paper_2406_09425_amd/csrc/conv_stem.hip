@@ -169,7 +169,7 @@ static int launch_stem_variant(const StemArgs& a, int grid, hipStream_t stream)
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         raised = true;
     }
-    hipLaunchKernelGGL((conv_stem_kernel<DT, TP>), dim3(grid), dim3(256), lds, stream, a);
+    SGPRS_LAUNCH((conv_stem_kernel<DT, TP>), dim3(grid), dim3(256), lds, stream, a);
     SGPRS_HIP(hipGetLastError());
     return SGPRS_OK;
 }

@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cstdarg>
 #include <cstdint>
@@ -103,16 +104,25 @@ struct KernelRecord {
     double flops = 0, bytes = 0;
     hipEvent_t start = nullptr, stop = nullptr;
 };
-// Optional per-launch timing hook: when non-null, launchers bracket each
-// kernel with events and append a record.
+// Optional per-launch timing hook.  begin() appends a record and publishes its
+// stop event in tl_stop; the next kernel launch (SGPRS_LAUNCH) attaches it to
+// its own dispatch, so it carries the kernel's completion time.  A record's
+// start is the stop event of the kernel queued just before it on the same
+// stream (kernels of a run are queued back to back), or a plain event when
+// there is none: separately recorded event packets would add microseconds of
+// their own latency to every interval.
+extern thread_local hipEvent_t tl_start, tl_stop;
+#define SGPRS_LAUNCH(kernel, grid, block, lds, stream, ...) \
+    hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, ::sgprs::tl_start, ::sgprs::tl_stop, 0, __VA_ARGS__)
 struct Profiler {
     bool on = false;
     std::vector<KernelRecord> recs;      // records of the stage being run
     std::vector<hipEvent_t> event_pool;  // reused events
     size_t next_event = 0;
+    hipEvent_t prev = nullptr;           // completion event of the previous kernel on this stream
     int begin(hipStream_t s, int kind, int variant, double flops, double bytes);
     int end(hipStream_t s);
-    void reset() { recs.clear(); next_event = 0; }
+    void reset(hipEvent_t prev_stop = nullptr) { recs.clear(); next_event = 0; prev = prev_stop; }
     ~Profiler();
 };
 
@@ -152,7 +162,7 @@ int launch_splitk_reduce(int dtype, const float* partial, int splits, size_t tot
 // tuning override: kind -1 automatic, 0 implicit GEMM only, 1 force patch (variant, splits)
 extern int g_conv_force_kind;
 
-const char* igemm_variant_name(int dtype, int variant);
+const char* igemm_variant_name(int v);
 int igemm_num_variants();
 
 }  // namespace sgprs

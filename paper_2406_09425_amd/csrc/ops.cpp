@@ -4,6 +4,8 @@
 
 namespace sgprs {
 
+thread_local hipEvent_t tl_start = nullptr, tl_stop = nullptr;
+
 Profiler::~Profiler()
 {
     for (hipEvent_t e : event_pool) (void)hipEventDestroy(e);
@@ -18,16 +20,24 @@ int Profiler::begin(hipStream_t s, int kind, int variant, double flops, double b
     }
     KernelRecord r;
     r.kind = kind; r.variant = variant; r.flops = flops; r.bytes = bytes;
-    r.start = event_pool[next_event++];
     r.stop = event_pool[next_event++];
-    SGPRS_HIP(hipEventRecord(r.start, s));
+    if (prev) {
+        r.start = prev;
+    } else {
+        r.start = event_pool[next_event++];
+        SGPRS_HIP(hipEventRecord(r.start, s));
+    }
     recs.push_back(r);
+    tl_start = nullptr;
+    tl_stop = r.stop;
+    prev = r.stop;
     return SGPRS_OK;
 }
 
-int Profiler::end(hipStream_t s)
+int Profiler::end(hipStream_t)
 {
-    SGPRS_HIP(hipEventRecord(recs.back().stop, s));
+    tl_start = nullptr;
+    tl_stop = nullptr;
     return SGPRS_OK;
 }
 

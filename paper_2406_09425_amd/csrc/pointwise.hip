@@ -241,10 +241,10 @@ int launch_maxpool(int dtype, int n, int h, int w, int c, const void* x, void* y
     const double bytes = ((double)n * h * w * c + (double)n * P * Q * c) * dtype_size(dtype);
     PROF_BEGIN(kKindMaxpool, dtype, 0.0, bytes);
     if (dtype == SGPRS_BF16)
-        hipLaunchKernelGGL(maxpool3x3s2_kernel<SGPRS_BF16>, dim3(blocks_for(total)), dim3(256), 0, stream, x, y, h, w,
+        SGPRS_LAUNCH(maxpool3x3s2_kernel<SGPRS_BF16>, dim3(blocks_for(total)), dim3(256), 0, stream, x, y, h, w,
                            c, P, Q, total);
     else
-        hipLaunchKernelGGL(maxpool3x3s2_kernel<SGPRS_F32>, dim3(blocks_for(total)), dim3(256), 0, stream, x, y, h, w,
+        SGPRS_LAUNCH(maxpool3x3s2_kernel<SGPRS_F32>, dim3(blocks_for(total)), dim3(256), 0, stream, x, y, h, w,
                            c, P, Q, total);
     SGPRS_HIP(hipGetLastError());
     PROF_END();
@@ -258,10 +258,10 @@ int launch_bn_relu(int dtype, size_t pixels, int c, const void* x, const float* 
     const size_t total = pixels * (c / vec);
     PROF_BEGIN(kKindBnRelu, dtype, 2.0 * pixels * c, 2.0 * pixels * c * dtype_size(dtype));
     if (dtype == SGPRS_BF16)
-        hipLaunchKernelGGL(bn_relu_kernel<SGPRS_BF16>, dim3(blocks_for(total)), dim3(256), 0, stream, x, y, scale,
+        SGPRS_LAUNCH(bn_relu_kernel<SGPRS_BF16>, dim3(blocks_for(total)), dim3(256), 0, stream, x, y, scale,
                            shift, c, total);
     else
-        hipLaunchKernelGGL(bn_relu_kernel<SGPRS_F32>, dim3(blocks_for(total)), dim3(256), 0, stream, x, y, scale,
+        SGPRS_LAUNCH(bn_relu_kernel<SGPRS_F32>, dim3(blocks_for(total)), dim3(256), 0, stream, x, y, scale,
                            shift, c, total);
     SGPRS_HIP(hipGetLastError());
     PROF_END();
@@ -275,10 +275,10 @@ int launch_add_relu(int dtype, size_t count, const void* a, const void* b, void*
     const size_t total = count / vec;
     PROF_BEGIN(kKindAdd, dtype, (double)count, 3.0 * count * dtype_size(dtype));
     if (dtype == SGPRS_BF16)
-        hipLaunchKernelGGL(add_relu_kernel<SGPRS_BF16>, dim3(blocks_for(total)), dim3(256), 0, stream, a, b, y, relu,
+        SGPRS_LAUNCH(add_relu_kernel<SGPRS_BF16>, dim3(blocks_for(total)), dim3(256), 0, stream, a, b, y, relu,
                            total);
     else
-        hipLaunchKernelGGL(add_relu_kernel<SGPRS_F32>, dim3(blocks_for(total)), dim3(256), 0, stream, a, b, y, relu,
+        SGPRS_LAUNCH(add_relu_kernel<SGPRS_F32>, dim3(blocks_for(total)), dim3(256), 0, stream, a, b, y, relu,
                            total);
     SGPRS_HIP(hipGetLastError());
     PROF_END();
@@ -293,9 +293,9 @@ int launch_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void* x
     PROF_BEGIN(kKindAvgpool, dtype, (double)n * hw * cin, (double)n * hw * cin * es + (double)n * cin * 4);
     const dim3 pgrid((cin / vec + 63) / 64, n);
     if (dtype == SGPRS_BF16)
-        hipLaunchKernelGGL(avgpool_kernel<SGPRS_BF16>, pgrid, dim3(256), 0, stream, x, ws, hw, cin);
+        SGPRS_LAUNCH(avgpool_kernel<SGPRS_BF16>, pgrid, dim3(256), 0, stream, x, ws, hw, cin);
     else
-        hipLaunchKernelGGL(avgpool_kernel<SGPRS_F32>, pgrid, dim3(256), 0, stream, x, ws, hw, cin);
+        SGPRS_LAUNCH(avgpool_kernel<SGPRS_F32>, pgrid, dim3(256), 0, stream, x, ws, hw, cin);
     SGPRS_HIP(hipGetLastError());
     PROF_END();
 
@@ -304,7 +304,7 @@ int launch_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void* x
     const int cpl = cin / 512;
     PROF_BEGIN(kKindFc, dtype, 2.0 * n * cin * cout, (double)cin * cout * es + (double)n * (cin + cout) * 4);
 #define FC_LAUNCH(DT, CPL)                                                                                  \
-    hipLaunchKernelGGL((fc_kernel<DT, CPL>), grid, dim3(256), 0, stream, (const float*)ws, w, bias, logits, n, cin, \
+    SGPRS_LAUNCH((fc_kernel<DT, CPL>), grid, dim3(256), 0, stream, (const float*)ws, w, bias, logits, n, cin, \
                        cout, img_per_block)
     if (dtype == SGPRS_BF16) {
         if (cpl == 1) FC_LAUNCH(SGPRS_BF16, 1); else if (cpl == 2) FC_LAUNCH(SGPRS_BF16, 2); else FC_LAUNCH(SGPRS_BF16, 4);
@@ -319,7 +319,7 @@ int launch_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void* x
 
 int launch_probe(int n_blocks, int spin_cycles, uint32_t* out, hipStream_t stream)
 {
-    hipLaunchKernelGGL(probe_kernel, dim3(n_blocks), dim3(64), 0, stream, out, spin_cycles);
+    SGPRS_LAUNCH(probe_kernel, dim3(n_blocks), dim3(64), 0, stream, out, spin_cycles);
     SGPRS_HIP(hipGetLastError());
     return SGPRS_OK;
 }

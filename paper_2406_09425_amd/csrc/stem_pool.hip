@@ -245,14 +245,14 @@ int launch_stem_pool(int dtype, int n, int h, int w, const void* x, const void* 
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
             raised[1] = true;
         }
-        hipLaunchKernelGGL(stem_pool_kernel<SGPRS_BF16>, dim3(grid), dim3(256), lds, stream, a);
+        SGPRS_LAUNCH(stem_pool_kernel<SGPRS_BF16>, dim3(grid), dim3(256), lds, stream, a);
     } else {
         if (!raised[0]) {
             SGPRS_HIP(hipFuncSetAttribute((const void*)stem_pool_kernel<SGPRS_F32>,
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
             raised[0] = true;
         }
-        hipLaunchKernelGGL(stem_pool_kernel<SGPRS_F32>, dim3(grid), dim3(256), lds, stream, a);
+        SGPRS_LAUNCH(stem_pool_kernel<SGPRS_F32>, dim3(grid), dim3(256), lds, stream, a);
     }
     SGPRS_HIP(hipGetLastError());
     if (prof && prof->on && (rc = prof->end(stream))) return rc;

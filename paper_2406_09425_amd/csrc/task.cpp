@@ -144,11 +144,12 @@ int run_block(sgprs_task* t, int c1, int c2, int down, int batch, const void* x,
     return run_conv(t, c2, batch, t->tmp[0], shortcut, out, 1, s, cus, prof);
 }
 
-int run_stage(sgprs_task* t, int j, int batch, const void* in, void* out, hipStream_t s, int cus)
+int run_stage(sgprs_task* t, int j, int batch, const void* in, void* out, hipStream_t s, int cus,
+              hipEvent_t prev_stop = nullptr)
 {
     Profiler* prof = &t->prof[j];
     prof->on = t->profiling;
-    prof->reset();
+    prof->reset(prev_stop);
     int rc;
     if (j == 0) {
         if (stem_pool_applicable(t->dtype, batch, 224, 224, cus))
@@ -329,7 +330,11 @@ int sgprs_task_run(sgprs_task_t* t, int batch, const void* in, float* logits, sg
         }
         const void* src = j == 0 ? in : t->stage_out[j - 1];
         void* dst = j == 5 ? (void*)logits : t->stage_out[j];
-        if ((rc = run_stage(t, j, batch, src, dst, s[j], cus[j]))) return rc;
+        // profiling: a stage on the same stream as its predecessor times its first
+        // kernel from the predecessor's last completion event
+        hipEvent_t prev = nullptr;
+        if (t->profiling && j > 0 && s[j] == s[j - 1] && !t->prof[j - 1].recs.empty()) prev = t->prof[j - 1].recs.back().stop;
+        if ((rc = run_stage(t, j, batch, src, dst, s[j], cus[j], prev))) return rc;
     }
     return SGPRS_OK;
 }
@@ -375,10 +380,10 @@ int sgprs_task_kernel_times(sgprs_task_t* t, int stage, int* count, int* kind, i
 const char* sgprs_kernel_name(int kind, int variant)
 {
     switch (kind) {
-        case kKindIgemm: return igemm_variant_name(variant / 4, variant % 4);
+        case kKindIgemm: return igemm_variant_name(variant);
         case kKindPatch: return patch_variant_name(variant);
         case kKindStem: return "conv_stem_kernel";
-        case kKindStemPool: return "stem_pool_kernel";
+        case kKindStemPool: return variant == SGPRS_BF16 ? "stem_pool_kernel<1>" : "stem_pool_kernel<0>";
         case kKindReduce: return "splitk_reduce_kernel";
         case kKindMaxpool: return "maxpool3x3s2_kernel";
         case kKindAvgpool: return "avgpool_kernel";
