@@ -90,6 +90,30 @@ __global__ __launch_bounds__((NW * 64), (PatchCfg<BM, BN, KC, NW>::WAVES_PER_SIM
 
     const int n_items = a.n_mtiles * a.n_ntiles * a.splits;
 
+    // Loader tables, fixed for the whole launch: which patch row / byte offset
+    // inside an input row this thread's it-th 16-byte chunk comes from, and the
+    // byte offset of its it-th weight chunk inside a (channel block, chunk) slab.
+    int p_row[P_IT];
+    unsigned p_goff[P_IT];  // ~0u: the chunk lies in the zero halo column
+#pragma unroll
+    for (int it = 0; it < P_IT; ++it) {
+        const int id = it * NT + tid;
+        const int pix = id / CPP, ch = id % CPP;
+        const int prow = fdiv(pix, a.mPW), pcol = pix - prow * a.PW;
+        p_row[it] = prow;
+        p_goff[it] = (pcol >= 1 && pcol <= a.W) ? ((unsigned)(pcol - 1) * (unsigned)a.Cin + ch * 8) * 2u : ~0u;
+    }
+    unsigned w_goff[STAT ? 1 : W_IT];
+    if constexpr (!STAT) {
+#pragma unroll
+        for (int it = 0; it < W_IT; ++it) {
+            const int id = it * NT + tid;
+            const int row = id / (9 * CPP), rem = id % (9 * CPP);
+            w_goff[it] = ((unsigned)(row * 9 + rem / CPP) * (unsigned)a.Cin + (rem % CPP) * 8) * 2u;
+        }
+    }
+    const unsigned row_bytes = (unsigned)a.W * (unsigned)a.Cin * 2u;
+
     // (item, chunk) -> registers.  Offsets are 32-bit byte offsets from the
     // tensor base (tensors are below 2^31 elements).
     auto fetch = [&](int item, int chunk) {
@@ -104,30 +128,18 @@ __global__ __launch_bounds__((NW * 64), (PatchCfg<BM, BN, KC, NW>::WAVES_PER_SIM
         const unsigned char* xc = a.x + (size_t)c0 * 2;
 #pragma unroll
         for (int it = 0; it < P_IT; ++it) {
-            const int id = it * NT + tid;
-            const int pix = id / CPP, ch = id % CPP;
-            const int prow = fdiv(pix, a.mPW), pcol = pix - prow * a.PW;
-            const int E = E0 + prow;
+            const int E = E0 + p_row[it];
             const int n = fdiv(E, a.mHE);
-            const int hh = E - n * a.HE - 1, ww = pcol - 1;
-            const bool ok = prow < R && (unsigned)hh < (unsigned)a.H && (unsigned)ww < (unsigned)a.W;
+            const int hh = E - n * a.HE - 1;
+            const bool ok = p_row[it] < R && (unsigned)hh < (unsigned)a.H && p_goff[it] != ~0u;
             u32x4_t v = {0u, 0u, 0u, 0u};
-            if (ok) {
-                const unsigned off = ((unsigned)((n * a.H + hh) * a.W + ww) * (unsigned)a.Cin + ch * 8) * 2u;
-                v = *(const u32x4_t*)(xc + off);
-            }
+            if (ok) v = *(const u32x4_t*)(xc + ((unsigned)(n * a.H + hh) * row_bytes + p_goff[it]));
             preg[it] = v;
         }
         if constexpr (!STAT) {
             const unsigned char* wc = a.w + ((size_t)ntile * BN * 9 * a.Cin + c0) * 2;
 #pragma unroll
-            for (int it = 0; it < W_IT; ++it) {
-                const int id = it * NT + tid;
-                const int row = id / (9 * CPP), rem = id % (9 * CPP);
-                const int tap = rem / CPP, ch = rem % CPP;
-                const unsigned off = ((unsigned)(row * 9 + tap) * (unsigned)a.Cin + ch * 8) * 2u;
-                wreg[it] = *(const u32x4_t*)(wc + off);
-            }
+            for (int it = 0; it < W_IT; ++it) wreg[it] = *(const u32x4_t*)(wc + w_goff[it]);
         }
     };
     auto stage = [&]() {

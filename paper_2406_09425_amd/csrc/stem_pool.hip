@@ -69,32 +69,60 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemPoolArgs a)
     }
     if (tid < 64) { SCs[tid] = a.scale[tid]; SCs[64 + tid] = a.shift[tid]; }
 
-    for (int tile = blockIdx.x; tile < a.ntiles; tile += gridDim.x) {
+    // The next tile's input patch is fetched into registers while the current
+    // tile computes: PF_IT pixels per thread, 3 channels each.
+    constexpr int PF_IT = (kInR * kInC + 255) / 256;
+    unsigned pf_lo[PF_IT], pf_hi[PF_IT], pf_x[DT == SGPRS_BF16 ? 1 : PF_IT];
+    auto fetch_patch = [&](int tile) {
         const int n = tile / (a.tiles_p * a.tiles_q), t2 = tile - n * (a.tiles_p * a.tiles_q);
         const int pp0 = (t2 / a.tiles_q) * kPoolTP, pq0 = (t2 % a.tiles_q) * kPoolTQ;
-        const int cr0 = 2 * pp0 - 1, cc0 = 2 * pq0 - 1;   // first conv row / column of the tile
-        const int h_base = 2 * cr0 - 3, w_base = 2 * cc0 - 3;
-
-        __syncthreads();  // the previous tile's pooling reads are done
-        for (int i = tid; i < kInR * kInC; i += 256) {
+        const int h_base = 2 * (2 * pp0 - 1) - 3, w_base = 2 * (2 * pq0 - 1) - 3;
+#pragma unroll
+        for (int it = 0; it < PF_IT; ++it) {
+            const int i = it * 256 + tid;
             const int pr = i / kInC, pc = i - pr * kInC;
             const int ih = h_base + pr, iw = w_base + pc;
-            const bool ok = (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+            const bool ok = i < kInR * kInC && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
             const size_t g = ((size_t)(n * a.H + (ok ? ih : 0)) * a.W + (ok ? iw : 0)) * 3;
             if constexpr (DT == SGPRS_BF16) {
                 const unsigned short* xp = (const unsigned short*)a.x + g;
                 unsigned short v0 = 0, v1 = 0, v2 = 0;
                 if (ok) { v0 = xp[0]; v1 = xp[1]; v2 = xp[2]; }
-                u32x2_t o = {(unsigned)v0 | ((unsigned)v1 << 16), (unsigned)v2};
-                *(u32x2_t*)(Ps + i * PIX) = o;
+                pf_lo[it] = (unsigned)v0 | ((unsigned)v1 << 16);
+                pf_hi[it] = (unsigned)v2;
             } else {
-                const float* xp = (const float*)a.x + g;
-                f32x4_t o = {0.f, 0.f, 0.f, 0.f};
-                if (ok) { o[0] = xp[0]; o[1] = xp[1]; o[2] = xp[2]; }
-                *(f32x4_t*)(Ps + i * PIX) = o;
+                const unsigned* xp = (const unsigned*)a.x + g;
+                unsigned v0 = 0, v1 = 0, v2 = 0;
+                if (ok) { v0 = xp[0]; v1 = xp[1]; v2 = xp[2]; }
+                pf_lo[it] = v0; pf_hi[it] = v1; pf_x[it] = v2;
             }
         }
+    };
+    auto store_patch = [&]() {
+#pragma unroll
+        for (int it = 0; it < PF_IT; ++it) {
+            const int i = it * 256 + tid;
+            if (i >= kInR * kInC) continue;
+            if constexpr (DT == SGPRS_BF16) {
+                u32x2_t o = {pf_lo[it], pf_hi[it]};
+                *(u32x2_t*)(Ps + i * PIX) = o;
+            } else {
+                u32x4_t o = {pf_lo[it], pf_hi[it], pf_x[it], 0u};
+                *(u32x4_t*)(Ps + i * PIX) = o;
+            }
+        }
+    };
+
+    if ((int)blockIdx.x < a.ntiles) fetch_patch(blockIdx.x);
+    for (int tile = blockIdx.x; tile < a.ntiles; tile += gridDim.x) {
+        const int n = tile / (a.tiles_p * a.tiles_q), t2 = tile - n * (a.tiles_p * a.tiles_q);
+        const int pp0 = (t2 / a.tiles_q) * kPoolTP, pq0 = (t2 % a.tiles_q) * kPoolTQ;
+        const int cr0 = 2 * pp0 - 1, cc0 = 2 * pq0 - 1;   // first conv row / column of the tile
+
+        __syncthreads();  // the previous tile's pooling reads are done
+        store_patch();
         __syncthreads();
+        if (tile + (int)gridDim.x < a.ntiles) fetch_patch(tile + gridDim.x);
 
         // accumulators: [channel tile i][pixel tile j]; this wavefront owns conv
         // pixels 64*wave .. 64*wave+63 of the tile (pixel t = row*17 + column)
