@@ -236,6 +236,7 @@ def main():
         out["batch1_fp32"] = leg_batch1(S, hip, pool, stream, nhwc, torch, total_cus)
         out["cu_sweep"] = leg_sweep(S, hip, torch, total_cus, nhwc, with_cpu=not args.no_cpu)
         out["multi_tenant"] = leg_multi_tenant(S, hip, torch, total_cus, nhwc)
+        out["memory_bound_ops"] = leg_membound(S, hip, torch, pool, stream)
     pool.destroy()
     print(json.dumps(out), flush=True)
 
@@ -382,6 +383,45 @@ def leg_sweep(S, hip, torch, total_cus, nhwc, with_cpu=True, reps=200):
         for name, r in res[dname].items():
             r["speedup_vs_8"] = [round(r["us"][0] / u, 2) for u in r["us"]]
             log("sweep", dname, name, "us", r["us"], "speedup", r["speedup_vs_8"])
+    return res
+
+
+def leg_membound(S, hip, torch, pool, stream, reps=20):
+    """Bandwidth kernels at batch-64 sizes, bf16, on the full-GPU partition.  Each launch works on its
+    own buffers out of a rotating set larger than the 256 MB last-level cache, so the bytes really
+    come from and go to HBM.  GB/s = algorithmic bytes / time."""
+    dt, tdt, es = S.SGPRS_BF16, torch.bfloat16, 2
+    res = {}
+
+    def timed(name, nbytes, make, run):
+        sets = [make() for _ in range(max(2, int(700e6 // nbytes) + 1))]
+        for k in range(2):
+            run(sets[k % len(sets)])
+        pool.sync()
+        e0, e1 = hip.event(), hip.event()
+        hip.record(e0, stream)
+        for k in range(reps):
+            run(sets[k % len(sets)])
+        hip.record(e1, stream)
+        pool.sync()
+        us = hip.elapsed_ms(e0, e1) * 1e3 / reps
+        res[name] = dict(us=round(us, 2), mbytes=round(nbytes / 1e6, 1), gb_per_s=round(nbytes / us / 1e3, 1),
+                         hbm_frac=round(nbytes / us / 1e3 / (PEAK_HBM / 1e9), 3), buffer_sets=len(sets))
+        log("membound", name, json.dumps(res[name]))
+
+    n = 64
+    timed("maxpool3x3s2 64x(112x112x64)", (n * 112 * 112 * 64 + n * 56 * 56 * 64) * es,
+          lambda: (torch.randn((n, 112, 112, 64), device="cuda").to(tdt), torch.empty((n, 56, 56, 64), dtype=tdt, device="cuda")),
+          lambda b: S.sgprs_maxpool2d(dt, n, 112, 112, 64, b[0].data_ptr(), b[1].data_ptr(), pool, 0))
+    sc = torch.ones(128, dtype=torch.float32, device="cuda"); sh = torch.zeros(128, dtype=torch.float32, device="cuda")
+    npx = 1024 * 28 * 28
+    timed("bn_relu 1024x(28x28x128)", 2 * npx * 128 * es,
+          lambda: (torch.randn((npx, 128), device="cuda").to(tdt), torch.empty((npx, 128), dtype=tdt, device="cuda")),
+          lambda b: S.sgprs_bn_relu(dt, npx, 128, b[0].data_ptr(), sc.data_ptr(), sh.data_ptr(), b[1].data_ptr(), pool, 0))
+    cnt = 4096 * 512 * 7 * 7
+    timed("add_relu 4096x(7x7x512)", 3 * cnt * es,
+          lambda: (torch.randn(cnt, device="cuda").to(tdt), torch.randn(cnt, device="cuda").to(tdt), torch.empty(cnt, dtype=tdt, device="cuda")),
+          lambda b: S.sgprs_add_relu(dt, cnt, b[0].data_ptr(), b[1].data_ptr(), b[2].data_ptr(), True, pool, 0))
     return res
 
 

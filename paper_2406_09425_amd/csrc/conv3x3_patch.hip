@@ -41,10 +41,37 @@ struct PatchArgs {
     unsigned mW, mPW, mHE, mH;  // ceil(2^32/d) multipliers for exact division
     int TR;                   // output rows per tile
     int n_mtiles, n_ntiles, n_chunks, chunks_per_split, splits;
+    int xcd_groups;           // > 0: work items are laid out so that one die keeps one channel block
+    int n_slots;              // size of the (possibly padded) work-item index space
     int relu;
 };
 
 __device__ __forceinline__ unsigned fdiv(unsigned x, unsigned magic) { return __umulhi(x, magic); }
+
+// Work-item index -> (split, channel block, row tile).  Workgroup b of a launch
+// runs on die b % 8 and keeps that die for all its items (the grid is a
+// multiple of 8), so with xcd_groups = 8 / n_ntiles every die only ever touches
+// the weights of one channel block: they stay in that die's L2 while the input
+// patches stream through.
+struct PatchItem { int split, ntile, mtile; bool valid; };
+__device__ __forceinline__ PatchItem decode_item(const PatchArgs& a, int item)
+{
+    PatchItem r;
+    if (a.xcd_groups > 0) {
+        const int x = item & 7, s = item >> 3;
+        r.split = 0;
+        r.ntile = x % a.n_ntiles;
+        r.mtile = s * a.xcd_groups + x / a.n_ntiles;
+        r.valid = item < a.n_slots && r.mtile < a.n_mtiles;
+    } else {
+        r.split = item % a.splits;
+        const int t2 = item / a.splits;
+        r.ntile = t2 % a.n_ntiles;
+        r.mtile = t2 / a.n_ntiles;
+        r.valid = item < a.n_slots;
+    }
+    return r;
+}
 
 template <int BM, int BN, int KC, int NW = 4> struct PatchCfg {
     static constexpr int NT = NW * 64;                  // threads per workgroup
@@ -88,7 +115,7 @@ __global__ __launch_bounds__((NW * 64), (PatchCfg<BM, BN, KC, NW>::WAVES_PER_SIM
     u32x4_t preg[P_IT];
     u32x4_t wreg[STAT ? 1 : W_IT];
 
-    const int n_items = a.n_mtiles * a.n_ntiles * a.splits;
+    const int n_items = a.n_slots;
 
     // Loader tables, fixed for the whole launch: which patch row / byte offset
     // inside an input row this thread's it-th 16-byte chunk comes from, and the
@@ -117,10 +144,9 @@ __global__ __launch_bounds__((NW * 64), (PatchCfg<BM, BN, KC, NW>::WAVES_PER_SIM
     // (item, chunk) -> registers.  Offsets are 32-bit byte offsets from the
     // tensor base (tensors are below 2^31 elements).
     auto fetch = [&](int item, int chunk) {
-        const int split = item % a.splits;
-        const int t2 = item / a.splits;
-        const int ntile = t2 % a.n_ntiles, mtile = t2 / a.n_ntiles;
-        const int c0 = (split * a.chunks_per_split + chunk) * KC;
+        const PatchItem pi = decode_item(a, item);
+        const int ntile = pi.ntile, mtile = pi.mtile;
+        const int c0 = (pi.split * a.chunks_per_split + chunk) * KC;
         const int g0 = mtile * a.TR;
         const int g1 = min(g0 + a.TR, a.NH) - 1;
         const int E0 = g0 + 2 * (int)fdiv(g0, a.mH);                 // e(g0) - 1
@@ -169,7 +195,7 @@ __global__ __launch_bounds__((NW * 64), (PatchCfg<BM, BN, KC, NW>::WAVES_PER_SIM
     }
 
     int item = blockIdx.x;
-    if (item >= n_items) return;
+    if (!decode_item(a, item).valid) return;  // invalid slots only exist at the tail of a die's sequence
     fetch(item, 0);
 
     // epilogue geometry: after the LDS transpose every lane owns 8 consecutive
@@ -181,9 +207,9 @@ __global__ __launch_bounds__((NW * 64), (PatchCfg<BM, BN, KC, NW>::WAVES_PER_SIM
     const int c8 = (lane % LPR) * 8, rsub = lane / LPR;
 
     while (item < n_items) {
-        const int split = item % a.splits;
-        const int t2 = item / a.splits;
-        const int ntile = t2 % a.n_ntiles, mtile = t2 / a.n_ntiles;
+        const PatchItem pi = decode_item(a, item);
+        if (!pi.valid) break;
+        const int split = pi.split, ntile = pi.ntile, mtile = pi.mtile;
         const int nch = min(a.chunks_per_split, a.n_chunks - split * a.chunks_per_split);
         const int g0 = mtile * a.TR;
         const int E0 = g0 + 2 * (int)fdiv(g0, a.mH);
@@ -245,7 +271,7 @@ __global__ __launch_bounds__((NW * 64), (PatchCfg<BM, BN, KC, NW>::WAVES_PER_SIM
             __syncthreads();
             // prefetch what comes next while this chunk computes
             if (chunk + 1 < nch) fetch(item, chunk + 1);
-            else if (item + (int)gridDim.x < n_items) fetch(item + gridDim.x, 0);
+            else if (decode_item(a, item + gridDim.x).valid) fetch(item + gridDim.x, 0);
             if constexpr (!SPLIT) {
                 // epilogue operands: requested during the last chunk so that they
                 // arrive while its MFMAs run
@@ -338,8 +364,9 @@ __global__ __launch_bounds__((NW * 64), (PatchCfg<BM, BN, KC, NW>::WAVES_PER_SIM
 static unsigned magic_for(unsigned d) { return (unsigned)((0x100000000ull + d - 1) / d); }
 
 struct PatchVariant { int bm, bn, kc; };
-static const PatchVariant kPatchVariants[] = {{256, 64, 64}, {256, 128, 32}, {128, 64, 64}, {128, 128, 32}, {256, 64, 32}, {256, 64, 64}, {256, 128, 32}};
-constexpr int kNumPatchVariants = 7;
+// tile variants: 0-3 run 4 wavefronts per workgroup, 4-5 run 8 (two per SIMD)
+static const PatchVariant kPatchVariants[] = {{256, 64, 64}, {256, 128, 32}, {128, 64, 64}, {128, 128, 32}, {256, 64, 64}, {256, 128, 32}};
+constexpr int kNumPatchVariants = 6;
 int patch_num_variants() { return kNumPatchVariants; }
 
 // Name as a profiler prints it: v = tile variant + 16 * stationary + 32 * split.
@@ -352,7 +379,7 @@ const char* patch_variant_name(int v)
     const PatchVariant& pv = kPatchVariants[tv];
     char* out = buf[next++ & 7];
     snprintf(out, 96, "conv3x3_patch_kernel<%d, %d, %d, %s, %s, %d>", pv.bm, pv.bn, pv.kc, (v & 16) ? "true" : "false",
-             (v & 32) ? "true" : "false", tv >= 5 ? 8 : 4);
+             (v & 32) ? "true" : "false", tv >= 4 ? 8 : 4);
     return out;
 }
 
@@ -388,6 +415,8 @@ static bool patch_geometry(const sgprs_conv_desc_t& d, int v, int splits, PatchA
     a->mW = magic_for(d.w); a->mPW = magic_for(d.w + 2); a->mHE = magic_for(d.h + 2); a->mH = magic_for(d.h);
     a->TR = TR; a->n_mtiles = n_mtiles; a->n_ntiles = d.cout / pv.bn; a->n_chunks = n_chunks;
     a->chunks_per_split = cps; a->splits = splits; a->relu = d.relu;
+    a->xcd_groups = (splits == 1 && a->n_ntiles <= 8 && 8 % a->n_ntiles == 0) ? 8 / a->n_ntiles : 0;
+    a->n_slots = a->xcd_groups ? 8 * ((n_mtiles + a->xcd_groups - 1) / a->xcd_groups) : n_mtiles * a->n_ntiles * splits;
     return true;
 }
 
@@ -409,7 +438,7 @@ bool plan_patch(const sgprs_conv_desc_t& d, int cus, int* variant, int* splits)
         *variant = g_force_variant; *splits = std::max(1, g_force_splits);
         return true;
     }
-    static const struct { int v; double cost; } cand[] = {{5, 7.0}, {6, 7.0}, {3, 4.1}, {2, 4.4}};
+    static const struct { int v; double cost; } cand[] = {{4, 7.0}, {5, 7.0}, {3, 4.1}, {2, 4.4}};
     double best = 1e30;
     bool found = false;
     for (const auto& c : cand) {
@@ -468,21 +497,22 @@ int launch_conv3x3_patch(const sgprs_conv_desc_t& d, int variant, int splits, co
     a.x = (const unsigned char*)x; a.w = (const unsigned char*)w; a.y = (unsigned char*)y;
     a.scale = scale; a.shift = shift; a.res = (const unsigned char*)residual; a.partial = (float*)ws;
     const long long items = (long long)a.n_mtiles * a.n_ntiles * a.splits;
-    const int occ = variant == 4 ? 2 : 1;
-    const int grid = (int)std::min<long long>(items, (long long)cus * occ);
+    const int occ = 1;  // every variant fills a CU's LDS with one workgroup
+    // a multiple of 8 keeps every workgroup on one die across its items
+    int grid = (int)std::min<long long>(a.n_slots, (long long)cus * occ);
+    if (a.xcd_groups && grid >= 8) grid -= grid % 8;
     const bool stat = a.n_chunks == 1 && a.n_ntiles == 1 && a.splits == 1;
     const double M = (double)d.n * d.h * d.w;
     const double flops = 2.0 * M * d.cout * 9.0 * d.cin;
     const double bytes = (M * d.cin + (double)d.cout * 9 * d.cin + M * d.cout * (residual ? 2 : 1)) * 2.0;
     int rc;
-    if (prof && prof->on && (rc = prof->begin(stream, kKindPatch, variant + (stat && variant % 5 == 0 ? 16 : 0) + (splits > 1 ? 32 : 0), flops, bytes))) return rc;
+    if (prof && prof->on && (rc = prof->begin(stream, kKindPatch, variant + (stat && variant % 4 == 0 ? 16 : 0) + (splits > 1 ? 32 : 0), flops, bytes))) return rc;
     switch (variant) {
         case 0: rc = launch_patch_variant<256, 64, 64>(a, grid, stat, stream); break;
         case 1: rc = launch_patch_variant<256, 128, 32>(a, grid, stat, stream); break;
         case 2: rc = launch_patch_variant<128, 64, 64>(a, grid, stat, stream); break;
-        case 4: rc = launch_patch_variant<256, 64, 32>(a, grid, stat, stream); break;
-        case 5: rc = launch_patch_variant<256, 64, 64, 8>(a, grid, stat, stream); break;
-        case 6: rc = launch_patch_variant<256, 128, 32, 8>(a, grid, stat, stream); break;
+        case 4: rc = launch_patch_variant<256, 64, 64, 8>(a, grid, stat, stream); break;
+        case 5: rc = launch_patch_variant<256, 128, 32, 8>(a, grid, stat, stream); break;
         default: rc = launch_patch_variant<128, 128, 32>(a, grid, stat, stream); break;
     }
     if (rc) return rc;

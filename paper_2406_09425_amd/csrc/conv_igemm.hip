@@ -205,6 +205,23 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const IgemmArgs a)
         sc0 = *(const f32x4_t*)(a.scale + nb); sc1 = *(const f32x4_t*)(a.scale + nb + 4);
         sh0 = *(const f32x4_t*)(a.shift + nb); sh1 = *(const f32x4_t*)(a.shift + nb + 4);
     }
+    // The residual rows are requested up front, unconditionally and from clamped
+    // (always valid) rows, so that all of them are in flight together instead
+    // of one round trip per pass.
+    constexpr int RV = DT == SGPRS_F32 ? 2 : 1;
+    u32x4_t rres[TM][NPASS][RV];
+    const bool has_res = !SPLIT && a.res != nullptr;
+    if (has_res) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int pass = 0; pass < NPASS; ++pass) {
+                const int m = min(m0 + wm * WTM + i * 32 + pass * RPP + rsub, a.M - 1);
+                const unsigned char* rp = a.res + ((size_t)m * a.Cout + nb) * ES;
+#pragma unroll
+                for (int v = 0; v < RV; ++v) rres[i][pass][v] = *(const u32x4_t*)(rp + 16 * v);
+            }
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -228,9 +245,9 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const IgemmArgs a)
                 v0 = v0 * sc0 + sh0;
                 v1 = v1 * sc1 + sh1;
                 if constexpr (DT == SGPRS_F32) {
-                    if (a.res) {
-                        v0 += *(const f32x4_t*)(a.res + o * 4);
-                        v1 += *(const f32x4_t*)(a.res + o * 4 + 16);
+                    if (has_res) {
+                        v0 += __builtin_bit_cast(f32x4_t, rres[i][pass][0]);
+                        v1 += __builtin_bit_cast(f32x4_t, rres[i][pass][RV - 1]);
                     }
                     if (a.relu) {
 #pragma unroll
@@ -241,7 +258,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const IgemmArgs a)
                 } else {
                     float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
                     u32x4_t rv = {0u, 0u, 0u, 0u};
-                    if (a.res) rv = *(const u32x4_t*)(a.res + o * 2);
+                    if (has_res) rv = rres[i][pass][0];
                     u32x4_t ov;
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {

@@ -53,38 +53,62 @@ template <> struct Vec<SGPRS_BF16> {
 };
 
 // ---- max pool 3x3 stride 2 pad 1 -------------------------------------------
+// One thread = one 16-byte channel vector of two vertically adjacent output
+// pixels: the five input rows they need are read once (the middle row is
+// shared), 15 loads for 2 outputs.  All index arithmetic is 32-bit.
 template <int DT>
 __global__ __launch_bounds__(256) void maxpool3x3s2_kernel(const void* __restrict__ x, void* __restrict__ y,
-                                                           int H, int W, int C, int P, int Q, size_t total_vec)
+                                                           int H, int W, int C, int P, int Q, unsigned total_items)
 {
     constexpr int N = Vec<DT>::N;
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total_vec) return;
-    const int cv = C / N;
-    const int c = (int)(idx % cv);
-    size_t pix = idx / cv;
-    const int q = (int)(pix % Q);
-    pix /= Q;
-    const int p = (int)(pix % P);
-    const int n = (int)(pix / P);
-    Vec<DT> m;
+    // Workgroup b runs on die b % 8: give each die a contiguous band of the
+    // output so that input rows shared by neighbouring output rows hit in that
+    // die's L2 instead of being fetched once per die.
+    const unsigned per_die = (gridDim.x + 7) / 8;
+    const unsigned vb = (blockIdx.x % 8) * per_die + blockIdx.x / 8;
+    const unsigned idx = vb * 256 + threadIdx.x;
+    if (idx >= total_items) return;
+    const unsigned cv = C / N, P2 = (P + 1) / 2;
+    const unsigned c = idx % cv;
+    unsigned t = idx / cv;
+    const int q = (int)(t % Q);
+    t /= Q;
+    const int p0 = 2 * (int)(t % P2);
+    const int n = (int)(t / P2);
+    // All 15 loads are issued unconditionally from clamped (always valid)
+    // coordinates so that they are in flight together; taps outside the image
+    // are replaced by -inf afterwards (padding never wins).
+    Vec<DT> v[5][3];
+    bool rok[5], cok[3];
 #pragma unroll
-    for (int i = 0; i < N; ++i) m.v[i] = -INFINITY;
-#pragma unroll
-    for (int r = 0; r < 3; ++r) {
-        const int ih = 2 * p - 1 + r;
-        if ((unsigned)ih >= (unsigned)H) continue;
+    for (int r = 0; r < 5; ++r) {
+        const int ih = 2 * p0 - 1 + r;
+        rok[r] = (unsigned)ih < (unsigned)H;
+        const int ihc = min(max(ih, 0), H - 1);
 #pragma unroll
         for (int s = 0; s < 3; ++s) {
             const int iw = 2 * q - 1 + s;
-            if ((unsigned)iw >= (unsigned)W) continue;
-            Vec<DT> t;
-            t.load(x, ((size_t)(n * H + ih) * W + iw) * cv + c);
-#pragma unroll
-            for (int i = 0; i < N; ++i) m.v[i] = fmaxf(m.v[i], t.v[i]);
+            cok[s] = (unsigned)iw < (unsigned)W;
+            const int iwc = min(max(iw, 0), W - 1);
+            v[r][s].load(x, ((size_t)(n * H + ihc) * W + iwc) * cv + c);
         }
     }
-    m.store(y, idx);
+    Vec<DT> m0, m1;
+#pragma unroll
+    for (int i = 0; i < N; ++i) { m0.v[i] = -INFINITY; m1.v[i] = -INFINITY; }
+#pragma unroll
+    for (int r = 0; r < 5; ++r) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            float rm = -INFINITY;  // horizontal maximum of this input row's three taps
+#pragma unroll
+            for (int s = 0; s < 3; ++s) rm = fmaxf(rm, (rok[r] && cok[s]) ? v[r][s].v[i] : -INFINITY);
+            if (r <= 2) m0.v[i] = fmaxf(m0.v[i], rm);
+            if (r >= 2) m1.v[i] = fmaxf(m1.v[i], rm);
+        }
+    }
+    m0.store(y, ((size_t)(n * P + p0) * Q + q) * cv + c);
+    if (p0 + 1 < P) m1.store(y, ((size_t)(n * P + p0 + 1) * Q + q) * cv + c);
 }
 
 // ---- y = max(0, scale*x + shift) -------------------------------------------
@@ -96,7 +120,9 @@ __global__ __launch_bounds__(256) void bn_relu_kernel(const void* __restrict__ x
     constexpr int N = Vec<DT>::N;
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total_vec) return;
-    const int c0 = (int)(idx % (C / N)) * N;
+    // (block * 256 + thread) mod cv without a 64-bit division
+    const unsigned cv = C / N;
+    const int c0 = (int)((((unsigned)(blockIdx.x % cv) * (256u % cv)) + threadIdx.x) % cv) * N;
     Vec<DT> t;
     t.load(x, idx);
 #pragma unroll
@@ -237,14 +263,15 @@ int launch_maxpool(int dtype, int n, int h, int w, int c, const void* x, void* y
 {
     const int P = (h - 1) / 2 + 1, Q = (w - 1) / 2 + 1;
     const int vec = dtype == SGPRS_BF16 ? 8 : 4;
-    const size_t total = (size_t)n * P * Q * (c / vec);
+    const unsigned total = (unsigned)((size_t)n * ((P + 1) / 2) * Q * (c / vec));  // two output rows per thread
     const double bytes = ((double)n * h * w * c + (double)n * P * Q * c) * dtype_size(dtype);
     PROF_BEGIN(kKindMaxpool, dtype, 0.0, bytes);
+    const unsigned nblk = (blocks_for(total) + 7) / 8 * 8;  // whole multiple of the die count
     if (dtype == SGPRS_BF16)
-        SGPRS_LAUNCH(maxpool3x3s2_kernel<SGPRS_BF16>, dim3(blocks_for(total)), dim3(256), 0, stream, x, y, h, w,
+        SGPRS_LAUNCH(maxpool3x3s2_kernel<SGPRS_BF16>, dim3(nblk), dim3(256), 0, stream, x, y, h, w,
                            c, P, Q, total);
     else
-        SGPRS_LAUNCH(maxpool3x3s2_kernel<SGPRS_F32>, dim3(blocks_for(total)), dim3(256), 0, stream, x, y, h, w,
+        SGPRS_LAUNCH(maxpool3x3s2_kernel<SGPRS_F32>, dim3(nblk), dim3(256), 0, stream, x, y, h, w,
                            c, P, Q, total);
     SGPRS_HIP(hipGetLastError());
     PROF_END();
