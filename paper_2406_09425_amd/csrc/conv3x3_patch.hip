@@ -44,6 +44,7 @@ struct PatchArgs {
     int xcd_groups;           // > 0: work items are laid out so that one die keeps one channel block
     int n_slots;              // size of the (possibly padded) work-item index space
     int relu;
+    unsigned x_bytes, w_bytes;  // sizes of x and w (buffer-descriptor bounds of the direct-to-LDS kernel)
 };
 
 __device__ __forceinline__ unsigned fdiv(unsigned x, unsigned magic) { return __umulhi(x, magic); }
@@ -102,7 +103,11 @@ __global__ __launch_bounds__((NW * 64), (PatchCfg<BM, BN, KC, NW>::WAVES_PER_SIM
     constexpr int WM = C::WM, WN = C::WN;
     constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
     constexpr int KS = KC / 16;
-    constexpr bool PRE_RES = C::WAVES_PER_SIMD == 1 && TM * TN <= 4;  // room in the register file: fetch the residual during the last chunk
+    // With one wavefront per SIMD nothing else hides the residual's latency, so it
+    // is requested before the last chunk's MFMA loop (when the tile is small
+    // enough to afford the registers); with two wavefronts per SIMD requesting it
+    // at the start of the epilogue measured faster.
+    constexpr bool PRE_RES = C::WAVES_PER_SIMD == 1 && TM * TN <= 4;
 
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char* Ps = smem;
@@ -255,7 +260,8 @@ __global__ __launch_bounds__((NW * 64), (PatchCfg<BM, BN, KC, NW>::WAVES_PER_SIM
                 for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
         const int wbase = C::PATCH_BYTES + (wn * WTN + frow) * WROWB + fhalf * 16;
-        u32x4_t fa[2][TM], fb[2][TN];
+        constexpr bool DEEP = NW == 4;  // one wavefront per SIMD: fragments are fetched two k-steps ahead
+        u32x4_t fa[DEEP ? 3 : 2][TM], fb[DEEP ? 3 : 2][TN];
         // fragments of k-step (tap, ks): tap offsets are added to the lane's
         // base addresses, the k-step is an immediate offset
         auto load_frags = [&](int set, int pa_off, int wb_off, int ks) {
@@ -281,6 +287,33 @@ __global__ __launch_bounds__((NW * 64), (PatchCfg<BM, BN, KC, NW>::WAVES_PER_SIM
                     if constexpr (PRE_RES) load_residual();
                 }
             }
+            if constexpr (DEEP) {
+                // one filter row (3 taps) per loop trip; its 3*KS k-steps are unrolled with
+                // three rotating fragment sets, loads running two k-steps ahead of the MFMAs
+                constexpr int STEPS = 3 * KS;
+                static_assert(STEPS % 3 == 0, "set rotation must close over a filter row");
+                load_frags(0, 0, 0, 0);
+                load_frags(1, KS == 1 ? PSP : 0, KS == 1 ? PS : 0, KS == 1 ? 0 : 1);
+#pragma unroll 1
+                for (int g = 0; g < 3; ++g) {
+                    const int pa_row = g * a.PW * PSP, wb_row = g * 3 * PS;
+#pragma unroll
+                    for (int u = 0; u < STEPS; ++u) {
+                        const int u2 = u + 2;  // the k-step to fetch now
+                        if (u2 < STEPS) load_frags(u2 % 3, pa_row + (u2 / KS) * PSP, wb_row + (u2 / KS) * PS, u2 % KS);
+                        else if (g < 2)
+                            load_frags(u2 % 3, pa_row + a.PW * PSP + ((u2 - STEPS) / KS) * PSP,
+                                       wb_row + 3 * PS + ((u2 - STEPS) / KS) * PS, (u2 - STEPS) % KS);
+#pragma unroll
+                        for (int i = 0; i < TM; ++i)
+#pragma unroll
+                            for (int j = 0; j < TN; ++j)
+                                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                    __builtin_bit_cast(bf16x8_t, fa[u % 3][i]), __builtin_bit_cast(bf16x8_t, fb[u % 3][j]),
+                                    acc[i][j], 0, 0, 0);
+                    }
+                }
+            } else {
             load_frags(0, 0, 0, 0);
             int r = 0, s = 0;
 #pragma unroll 1
@@ -303,6 +336,7 @@ __global__ __launch_bounds__((NW * 64), (PatchCfg<BM, BN, KC, NW>::WAVES_PER_SIM
                                 acc[i][j], 0, 0, 0);
                 }
                 r = r2; s = s2;
+            }
             }
         }
 
@@ -360,13 +394,274 @@ __global__ __launch_bounds__((NW * 64), (PatchCfg<BM, BN, KC, NW>::WAVES_PER_SIM
     }
 }
 
+// ---- direct-to-LDS variant -------------------------------------------------------
+// Same decomposition with BM = 256, BN = 64 and chunks of 32 channels, but the
+// global loads write LDS directly (buffer loads with the LDS bit: 64 lanes x 16
+// bytes land in one contiguous KiB), so no registers, no LDS-store instructions
+// and no address arithmetic are spent on staging.  Two LDS buffers: while the
+// MFMAs of step t (one chunk of one work item) read buffer t % 2, the loads of
+// step t+1 are issued into the other one, one per MFMA k-step.  Out-of-image
+// pixels get a buffer offset beyond the descriptor's size, for which the
+// hardware returns zeros: the zero halo costs no branch and no select.
+//
+// LDS layout: pixel p of the patch occupies bytes [64p, 64p+64) as four 16-byte
+// slots; slot s holds channel group s ^ f(p), f(p) = bit-swap of (p >> 2) & 3,
+// so that 16 consecutive pixels of one group, or 8 consecutive pixels of two
+// adjacent groups, touch 16 distinct 16-byte bank groups without padding.  The
+// weights use the same rule with the output channel in the place of p.
+// With two chunks and one channel block (64 -> 64 layers) all weights stay
+// resident (STAT) and only the patch is double buffered.
+__device__ __forceinline__ unsigned dl_swz(unsigned p) { return ((p >> 3) & 1u) | ((p >> 1) & 2u); }
+
+template <bool STAT>
+__global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a)
+{
+    constexpr int BN = 64, KC = 32, NT = 256;
+    constexpr int PCAP_PIX = 512, P_IT = PCAP_PIX * 4 / NT, W_IT = BN * 9 * 4 / NT;
+    constexpr int P_BYTES = PCAP_PIX * 64, P_PITCH = P_BYTES + 4096, W_BYTES = BN * 9 * 64;
+    constexpr int W_BASE = 2 * P_PITCH;
+    constexpr int TM = 2, TN = 2, KS = KC / 16, NSTEP = 9 * KS;
+    constexpr int WTN = 64, SROW = WTN + 4, RPP = 8, NPASS = 4;
+    static_assert(P_IT == 8 && W_IT == 9 && NSTEP >= P_IT + W_IT, "loader slots");
+    static_assert(4 * 32 * SROW * 4 <= P_PITCH, "epilogue scratch fits the patch buffer and its pad");
+    typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int nch = a.n_chunks;
+
+    // weight loader: 16-byte unit u = it * 256 + tid is slot u % 4 of tap (u / 4) % 9 of row u / 36
+    unsigned w_voff[W_IT];
+#pragma unroll
+    for (int it = 0; it < W_IT; ++it) {
+        const unsigned u = it * NT + tid, row = u / 36, rem = u % 36;
+        w_voff[it] = ((row * 9 + rem / 4) * (unsigned)a.Cin + (((rem & 3) ^ dl_swz(row)) * 8)) * 2u;
+    }
+    // patch loader: unit u is slot u % 4 of patch pixel u / 4
+    int p_row[P_IT], p_col[P_IT];
+    unsigned p_grp[P_IT];
+#pragma unroll
+    for (int it = 0; it < P_IT; ++it) {
+        const unsigned u = it * NT + tid, pix = u >> 2;
+        p_row[it] = fdiv(pix, a.mPW);
+        p_col[it] = pix - p_row[it] * a.PW;
+        p_grp[it] = (((u & 3) ^ dl_swz(pix)) * 8) * 2u;
+    }
+    unsigned p_voff[P_IT];  // byte offset of each unit's source inside x for the item being loaded
+    auto patch_offsets = [&](int mtile) {
+        const int g0 = mtile * a.TR;
+        const int g1 = min(g0 + a.TR, a.NH) - 1;
+        const int E0 = g0 + 2 * (int)fdiv(g0, a.mH);
+        const int R = (g1 + 2 * (int)fdiv(g1, a.mH) + 2) - E0 + 1;
+#pragma unroll
+        for (int it = 0; it < P_IT; ++it) {
+            const int E = E0 + p_row[it];
+            const int n = fdiv(E, a.mHE);
+            const int hh = E - n * a.HE - 1;
+            const bool ok = p_row[it] < R && (unsigned)hh < (unsigned)a.H && p_col[it] >= 1 && p_col[it] <= a.W;
+            p_voff[it] = ok ? ((unsigned)((n * a.H + hh) * a.W + p_col[it] - 1) * (unsigned)a.Cin) * 2u + p_grp[it]
+                            : 0x80000000u;
+        }
+    };
+
+    // Work items blockIdx.x + k * gridDim.x; an item is n_chunks steps (n_chunks is
+    // even, so every item starts on buffer 0 and ends on buffer 1).
+    int item = blockIdx.x;
+    PatchItem cur = decode_item(a, item);
+    if (!cur.valid) return;
+
+    const __amdgpu_buffer_rsrc_t w_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, (int)a.w_bytes, 0x00020000);
+    if constexpr (STAT) {  // both weight chunks resident
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int it = 0; it < W_IT; ++it)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rs, (lds_ptr_t)(smem + W_BASE + c * W_BYTES + (it * NT + wave * 64) * 16),
+                                                         16, w_voff[it], c * KC * 2, 0, 0);
+    }
+    // loads of the first step
+    patch_offsets(cur.mtile);
+    {
+        const __amdgpu_buffer_rsrc_t x_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.x, 0, (int)a.x_bytes, 0x00020000);
+#pragma unroll
+        for (int it = 0; it < P_IT; ++it)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rs, (lds_ptr_t)(smem + (it * NT + wave * 64) * 16), 16, p_voff[it], 0, 0, 0);
+        if constexpr (!STAT) {
+            const int ws = cur.ntile * BN * 9 * a.Cin * 2;
+#pragma unroll
+            for (int it = 0; it < W_IT; ++it)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rs, (lds_ptr_t)(smem + W_BASE + (it * NT + wave * 64) * 16), 16, w_voff[it], ws, 0, 0);
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+
+    const int c8 = (lane % 8) * 8, rsub = lane / 8;
+    // this lane's weight rows: byte offset inside a weight buffer for k-step parity 0 / 1
+    unsigned wb[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) wb[ks] = frow * 576 + (((ks * 2 + fhalf) ^ dl_swz(frow)) << 4);
+
+    for (;;) {
+        // ---- this work item
+        const int g0 = cur.mtile * a.TR;
+        const int rows_here = min(a.TR, a.NH - g0);
+        const int m_lim = rows_here * a.W;
+        const int nbase = cur.ntile * BN + c8;
+        unsigned aoff[TM][9];  // this lane's patch fragment address for every tap (k-step parity 0)
+        {
+            const int E0 = g0 + 2 * (int)fdiv(g0, a.mH);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int tt = wave * 64 + i * 32 + frow;
+                const int pr = fdiv(tt, a.mW), q = tt - pr * a.W;
+                const bool ok = pr < rows_here;
+                const int g = g0 + (ok ? pr : 0);
+                const int e1 = g + 2 * (int)fdiv(g, a.mH);
+                const unsigned pp = (unsigned)((e1 - E0) * a.PW + (ok ? q : 0));
+#pragma unroll
+                for (int tap = 0; tap < 9; ++tap) {
+                    const unsigned p = pp + (tap / 3) * a.PW + (tap % 3);
+                    aoff[i][tap] = (p << 6) + ((fhalf ^ dl_swz(p)) << 4);
+                }
+            }
+        }
+        f32x16_t acc[TM][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+        // the item after this one (its first step is loaded during this item's last step)
+        const PatchItem nxt = decode_item(a, item + (int)gridDim.x);
+
+        f32x4_t sc0 = {1.f, 1.f, 1.f, 1.f}, sc1 = sc0, sh0 = {0.f, 0.f, 0.f, 0.f}, sh1 = sh0;
+        u32x4_t rres[TM][NPASS];
+
+        // One step: MFMAs of chunk `chunk` from buffer BUF; loads of the following step into the other buffer.
+        auto step = [&](auto BUFC, int chunk) {
+            constexpr int BUF = decltype(BUFC)::value;
+            const bool last = BUF == 1 && chunk == nch - 1;
+            const bool has1 = !last || nxt.valid;
+            if (last && nxt.valid) patch_offsets(nxt.mtile);
+            // without a following step the descriptors have size 0: the loads fetch nothing
+            const __amdgpu_buffer_rsrc_t x_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.x, 0, has1 ? (int)a.x_bytes : 0, 0x00020000);
+            const __amdgpu_buffer_rsrc_t wn_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, has1 ? (int)a.w_bytes : 0, 0x00020000);
+            const int chunk1 = last ? 0 : chunk + 1;
+            const int xs1 = chunk1 * KC * 2;
+            const int ws1 = ((last ? nxt.ntile : cur.ntile) * BN * 9 * a.Cin + chunk1 * KC) * 2;
+            auto issue_slot = [&](int k) {
+                if (k < P_IT)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rs, (lds_ptr_t)(smem + (BUF ^ 1) * P_PITCH + (k * NT + wave * 64) * 16),
+                                                             16, p_voff[k < P_IT ? k : 0], xs1, 0, 0);
+                else if (!STAT && k - P_IT < W_IT)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(wn_rs, (lds_ptr_t)(smem + W_BASE + (BUF ^ 1) * W_BYTES + ((k - P_IT) * NT + wave * 64) * 16),
+                                                             16, w_voff[k - P_IT < W_IT && k >= P_IT ? k - P_IT : 0], ws1, 0, 0);
+            };
+            if (BUF == 1 && last) {  // epilogue operands, requested now so that they arrive during the MFMAs
+                sc0 = *(const f32x4_t*)(a.scale + nbase); sc1 = *(const f32x4_t*)(a.scale + nbase + 4);
+                sh0 = *(const f32x4_t*)(a.shift + nbase); sh1 = *(const f32x4_t*)(a.shift + nbase + 4);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int pass = 0; pass < NPASS; ++pass) {
+                        const int tt = wave * 64 + i * 32 + pass * RPP + rsub;
+                        u32x4_t rv = {0u, 0u, 0u, 0u};
+                        if (a.res && tt < m_lim)
+                            rv = *(const u32x4_t*)(a.res + (((size_t)g0 * a.W + tt) * a.Cout + nbase) * 2);
+                        rres[i][pass] = rv;
+                    }
+            }
+            // MFMA loop: 18 k-steps, fragments fetched two k-steps ahead, one load slot per k-step
+            const unsigned char* pbuf = smem + BUF * P_PITCH;
+            const unsigned char* wbuf = smem + W_BASE + (STAT ? chunk : BUF) * W_BYTES;
+            u32x4_t fa[3][TM], fb[3][TN];
+            auto load_frags = [&](int set, int st) {
+                const int tap = st / KS, ks = st % KS;
+#pragma unroll
+                for (int i = 0; i < TM; ++i) fa[set][i] = *(const u32x4_t*)(pbuf + (aoff[i][tap] ^ (ks << 5)));
+#pragma unroll
+                for (int j = 0; j < TN; ++j) fb[set][j] = *(const u32x4_t*)(wbuf + wb[ks] + j * 32 * 576 + tap * 64);
+            };
+            load_frags(0, 0);
+            load_frags(1, 1);
+#pragma unroll
+            for (int st = 0; st < NSTEP; ++st) {
+                __builtin_amdgcn_sched_barrier(0);  // keep the two-k-steps-ahead order of the LDS reads
+                if (st + 2 < NSTEP) load_frags((st + 2) % 3, st + 2);
+                issue_slot(st);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8_t, fa[st % 3][i]), __builtin_bit_cast(bf16x8_t, fb[st % 3][j]),
+                            acc[i][j], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // the following step's data has landed, and nobody reads this buffer any more
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+        };
+        for (int chunk = 0; chunk < nch; chunk += 2) {
+            step(std::integral_constant<int, 0>{}, chunk);
+            step(std::integral_constant<int, 1>{}, chunk + 1);
+        }
+
+        {   // epilogue through the patch area of buffer 1 (the next item's first step sits in buffer 0)
+            float* scr = (float*)(smem + P_PITCH) + wave * 32 * SROW;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        scr[(8 * (e >> 2) + 4 * fhalf + (e & 3)) * SROW + j * 32 + frow] = acc[i][j][e];
+#pragma unroll
+                for (int pass = 0; pass < NPASS; ++pass) {
+                    const int rr = pass * RPP + rsub;
+                    const int tt = wave * 64 + i * 32 + rr;
+                    f32x4_t v0 = *(const f32x4_t*)(scr + rr * SROW + c8);
+                    f32x4_t v1 = *(const f32x4_t*)(scr + rr * SROW + c8 + 4);
+                    if (tt < m_lim) {
+                        const size_t m = (size_t)g0 * a.W + tt;
+                        const u32x4_t rv = rres[i][pass];
+                        v0 = v0 * sc0 + sh0;
+                        v1 = v1 * sc1 + sh1;
+                        float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+                        u32x4_t ov;
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            float lo = v[2 * u] + __uint_as_float(rv[u] << 16);
+                            float hi = v[2 * u + 1] + __uint_as_float(rv[u] & 0xffff0000u);
+                            if (a.relu) { lo = fmaxf(lo, 0.f); hi = fmaxf(hi, 0.f); }
+                            const __bf16 l16 = (__bf16)lo, h16 = (__bf16)hi;
+                            ov[u] = (unsigned)__builtin_bit_cast(unsigned short, l16) |
+                                    ((unsigned)__builtin_bit_cast(unsigned short, h16) << 16);
+                        }
+                        *(u32x4_t*)(a.y + (m * a.Cout + nbase) * 2) = ov;
+                    }
+                }
+            }
+        }
+        if (!nxt.valid) break;
+        __syncthreads();  // the scratch area is free again before the next item's loads target it
+        item += gridDim.x;
+        cur = nxt;
+    }
+}
+
 // ---- host side ---------------------------------------------------------------
 static unsigned magic_for(unsigned d) { return (unsigned)((0x100000000ull + d - 1) / d); }
 
 struct PatchVariant { int bm, bn, kc; };
 // tile variants: 0-3 run 4 wavefronts per workgroup, 4-5 run 8 (two per SIMD)
-static const PatchVariant kPatchVariants[] = {{256, 64, 64}, {256, 128, 32}, {128, 64, 64}, {128, 128, 32}, {256, 64, 64}, {256, 128, 32}};
-constexpr int kNumPatchVariants = 6;
+static const PatchVariant kPatchVariants[] = {{256, 64, 64}, {256, 128, 32}, {128, 64, 64}, {128, 128, 32}, {256, 64, 64}, {256, 128, 32}, {128, 64, 32}, {256, 64, 32}};
+constexpr int kNumPatchVariants = 8;
+constexpr int kPatchDlVariant = 7;  // the direct-to-LDS kernel
 int patch_num_variants() { return kNumPatchVariants; }
 
 // Name as a profiler prints it: v = tile variant + 16 * stationary + 32 * split.
@@ -378,8 +673,12 @@ const char* patch_variant_name(int v)
     if (tv >= kNumPatchVariants) return "?";
     const PatchVariant& pv = kPatchVariants[tv];
     char* out = buf[next++ & 7];
+    if (tv == kPatchDlVariant) {
+        snprintf(out, 96, "conv3x3_patch_dl_kernel<%s>", (v & 16) ? "true" : "false");
+        return out;
+    }
     snprintf(out, 96, "conv3x3_patch_kernel<%d, %d, %d, %s, %s, %d>", pv.bm, pv.bn, pv.kc, (v & 16) ? "true" : "false",
-             (v & 32) ? "true" : "false", tv >= 4 ? 8 : 4);
+             (v & 32) ? "true" : "false", (tv == 4 || tv == 5) ? 8 : 4);
     return out;
 }
 
@@ -394,6 +693,10 @@ static bool patch_geometry(const sgprs_conv_desc_t& d, int v, int splits, PatchA
 {
     const PatchVariant& pv = kPatchVariants[v];
     if (d.cout % pv.bn || d.cin % pv.kc || d.w > pv.bm) return false;
+    // the direct-to-LDS kernel addresses x and w through 31-bit buffer offsets
+    if (v == kPatchDlVariant && (splits != 1 || (long long)d.n * d.h * d.w * d.cin * 2 >= (1ll << 31) ||
+                                 (long long)d.cout * 9 * d.cin * 2 >= (1ll << 31)))
+        return false;
     const int TR = pv.bm / d.w, NH = d.n * d.h;
     const int cap = pv.bm == 256 ? 512 : 256;  // patch capacity in pixels
     const int n_mtiles = (NH + TR - 1) / TR;
@@ -481,6 +784,25 @@ static int launch_patch_variant(const PatchArgs& a, int grid, bool stat, hipStre
     return launch_patch_inst<BM, BN, KC, false, false, NW>(a, grid, stream);
 }
 
+static int launch_patch_dl(const PatchArgs& a, int grid, hipStream_t stream)
+{
+    constexpr int kLds = 2 * (512 * 64 + 4096) + 2 * 64 * 9 * 64;
+    static bool raised = false;
+    if (!raised) {
+        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<true>,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
+        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<false>,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
+        raised = true;
+    }
+    if (a.n_chunks == 2 && a.n_ntiles == 1)
+        SGPRS_LAUNCH(conv3x3_patch_dl_kernel<true>, dim3(grid), dim3(256), kLds, stream, a);
+    else
+        SGPRS_LAUNCH(conv3x3_patch_dl_kernel<false>, dim3(grid), dim3(256), kLds, stream, a);
+    SGPRS_HIP(hipGetLastError());
+    return SGPRS_OK;
+}
+
 int launch_splitk_reduce(int dtype, const float* partial, int splits, size_t total, int cout, const float* scale,
                          const float* shift, const void* res, void* y, int relu, hipStream_t stream);
 
@@ -496,8 +818,9 @@ int launch_conv3x3_patch(const sgprs_conv_desc_t& d, int variant, int splits, co
         return fail(SGPRS_ERR_INVALID_ARG, "split-K workspace %zu bytes needed, %zu given", need, ws_bytes);
     a.x = (const unsigned char*)x; a.w = (const unsigned char*)w; a.y = (unsigned char*)y;
     a.scale = scale; a.shift = shift; a.res = (const unsigned char*)residual; a.partial = (float*)ws;
+    a.x_bytes = (unsigned)((size_t)d.n * d.h * d.w * d.cin * 2); a.w_bytes = (unsigned)((size_t)d.cout * 9 * d.cin * 2);
     const long long items = (long long)a.n_mtiles * a.n_ntiles * a.splits;
-    const int occ = 1;  // every variant fills a CU's LDS with one workgroup
+    const int occ = variant == 6 ? 2 : 1;  // variant 6 is small enough for two workgroups per CU
     // a multiple of 8 keeps every workgroup on one die across its items
     int grid = (int)std::min<long long>(a.n_slots, (long long)cus * occ);
     if (a.xcd_groups && grid >= 8) grid -= grid % 8;
@@ -506,13 +829,15 @@ int launch_conv3x3_patch(const sgprs_conv_desc_t& d, int variant, int splits, co
     const double flops = 2.0 * M * d.cout * 9.0 * d.cin;
     const double bytes = (M * d.cin + (double)d.cout * 9 * d.cin + M * d.cout * (residual ? 2 : 1)) * 2.0;
     int rc;
-    if (prof && prof->on && (rc = prof->begin(stream, kKindPatch, variant + (stat && variant % 4 == 0 ? 16 : 0) + (splits > 1 ? 32 : 0), flops, bytes))) return rc;
+    if (prof && prof->on && (rc = prof->begin(stream, kKindPatch, variant + ((variant == kPatchDlVariant ? (a.n_chunks == 2 && a.n_ntiles == 1) : (stat && variant % 4 == 0)) ? 16 : 0) + (splits > 1 ? 32 : 0), flops, bytes))) return rc;
     switch (variant) {
         case 0: rc = launch_patch_variant<256, 64, 64>(a, grid, stat, stream); break;
         case 1: rc = launch_patch_variant<256, 128, 32>(a, grid, stat, stream); break;
         case 2: rc = launch_patch_variant<128, 64, 64>(a, grid, stat, stream); break;
         case 4: rc = launch_patch_variant<256, 64, 64, 8>(a, grid, stat, stream); break;
         case 5: rc = launch_patch_variant<256, 128, 32, 8>(a, grid, stat, stream); break;
+        case 6: rc = launch_patch_variant<128, 64, 32>(a, grid, stat, stream); break;
+        case kPatchDlVariant: rc = launch_patch_dl(a, grid, stream); break;
         default: rc = launch_patch_variant<128, 128, 32>(a, grid, stat, stream); break;
     }
     if (rc) return rc;
