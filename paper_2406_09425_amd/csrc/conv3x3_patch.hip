@@ -592,7 +592,7 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
             for (int st = 0; st < NSTEP; ++st) {
                 __builtin_amdgcn_sched_barrier(0);  // keep the two-k-steps-ahead order of the LDS reads
                 if (st + 2 < NSTEP) load_frags((st + 2) % 3, st + 2);
-                issue_slot(st);
+                issue_slot(st);  // one per k-step: issuing them faster only stalls on the address queue
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -727,7 +727,7 @@ static int g_force_variant = -1, g_force_splits = 0;
 void patch_force(int variant, int splits) { g_force_variant = variant; g_force_splits = splits; }
 
 // Picks the tile variant: the candidate with the smallest estimated time
-// rounds(items / CUs) * chunks * cost-per-chunk, the per-chunk costs (in
+// rounds(items / CUs) * (chunks * cost-per-chunk + cost-per-item); the costs (in
 // microseconds, whole-GPU measurements at batch 64) only rank candidates.
 // Split-K is left to the implicit-GEMM path: when a shape offers too few work
 // items to fill the partition this kernel declines.
@@ -741,15 +741,18 @@ bool plan_patch(const sgprs_conv_desc_t& d, int cus, int* variant, int* splits)
         *variant = g_force_variant; *splits = std::max(1, g_force_splits);
         return true;
     }
-    static const struct { int v; double cost; } cand[] = {{4, 7.0}, {5, 7.0}, {3, 4.1}, {2, 4.4}};
+    // {variant, microseconds per chunk, microseconds per work item}
+    static const struct { int v; double step, item; } cand[] = {
+        {7, 1.65, 5.0}, {4, 5.1, 2.8}, {5, 5.1, 2.8}, {3, 3.1, 2.0}, {2, 4.1, 2.0}};
     double best = 1e30;
     bool found = false;
     for (const auto& c : cand) {
         if (!patch_geometry(d, c.v, 1, &a)) continue;
         const long long items = (long long)a.n_mtiles * a.n_ntiles;
-        if (items * 2 < cus) continue;
+        if (items * 2 < cus && c.v != kPatchDlVariant) continue;
+        if (items * 3 < cus) continue;
         const long long rounds = (items + cus - 1) / cus;
-        const double cost = rounds * a.n_chunks * c.cost;
+        const double cost = rounds * (a.n_chunks * c.step + c.item);
         if (cost < best) { best = cost; *variant = c.v; *splits = 1; found = true; }
     }
     return found;
