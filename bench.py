@@ -193,8 +193,8 @@ def main():
                     avg_launch_us=round(dtc / dcnt * 1e6, 2), avg_launch_us_raw=round(dt_s / dcnt * 1e6, 2),
                     event_overhead_us=round(ev_over_us, 2), launches_per_step=dcnt // prof_steps,
                     flop_per_launch=round(dfl / dcnt, 1), algorithmic_bytes_per_launch=round(dby / dcnt, 1))
-    conv_t = sum(corr(v[0], v[3]) for k, v in agg.items() if k[1] in (0, 1, 2, 8, 9))
-    conv_fl = sum(v[1] for k, v in agg.items() if k[1] in (0, 1, 8, 9))
+    conv_t = sum(corr(v[0], v[3]) for k, v in agg.items() if k[1] in (0, 1, 2, 8, 9, 10))
+    conv_fl = sum(v[1] for k, v in agg.items() if k[1] in (0, 1, 8, 9, 10))
     conv_all = dict(tflops=round(conv_fl / conv_t / 1e12, 2), mfma_frac=round(conv_fl / conv_t / PEAK_BF16, 4),
                     us_per_step=round(conv_t / prof_steps * 1e6, 1))
     task.set_profiling(False)

@@ -228,7 +228,8 @@ const void *sgprs_task_stage_output(const sgprs_task_t *task, int stage);
  * sgprs_task_kernel_times returns, for the last run of each stage, one record
  * per launch: HOST arrays of length *count (in: capacity).  kind: 0 conv
  * implicit GEMM, 1 stem conv, 2 split-K reduce, 3 max-pool, 4 avg-pool, 5 FC,
- * 8 LDS-patch 3x3 conv, 9 fused stem conv + max-pool.
+ * 6 BN+ReLU, 7 add+ReLU, 8 LDS-patch 3x3 conv, 9 fused stem conv + max-pool,
+ * 10 two implicit-GEMM convolutions of one input in a single launch.
  * flops/bytes are the algorithmic work of the launch. */
 int sgprs_task_set_profiling(sgprs_task_t *task, int on);
 int sgprs_task_kernel_times(sgprs_task_t *task, int stage, int *count, int *kind, int *variant,

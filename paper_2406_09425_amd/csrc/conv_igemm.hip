@@ -65,8 +65,9 @@ template <> struct Store<SGPRS_BF16> {
 
 __device__ __forceinline__ int swz(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
 
+// One BM x BN output tile: tile column bx, channel block by, split-K slice bz.
 template <int DT, int BM, int BN, int WM, int WN, bool SPLIT>
-__global__ __launch_bounds__(256) void conv_igemm_kernel(const IgemmArgs a)
+__device__ __forceinline__ void igemm_tile(const IgemmArgs& a, int bx, int by, int bz)
 {
     constexpr int ES = DT == SGPRS_BF16 ? 2 : 4;  // element size
     constexpr int KT = 128 / ES;                  // elements per k-tile row
@@ -81,8 +82,8 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const IgemmArgs a)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
-    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
-    const int kt_begin = blockIdx.z * a.kt_per_split;
+    const int m0 = bx * BM, n0 = by * BN;
+    const int kt_begin = bz * a.kt_per_split;
     const int kt_end = min(kt_begin + a.kt_per_split, a.ktiles);
     const int K = a.ktiles * KT;
 
@@ -237,7 +238,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const IgemmArgs a)
             f32x4_t v1 = *(const f32x4_t*)(scr + rr * SROW + c8 + 4);
             if (m >= a.M) continue;
             if constexpr (SPLIT) {
-                float* dst = a.partial + ((size_t)blockIdx.z * a.M + m) * a.Cout + nb;
+                float* dst = a.partial + ((size_t)bz * a.M + m) * a.Cout + nb;
                 *(f32x4_t*)dst = v0;
                 *(f32x4_t*)(dst + 4) = v1;
             } else {
@@ -272,6 +273,28 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const IgemmArgs a)
             }
         }
     }
+}
+
+template <int DT, int BM, int BN, int WM, int WN, bool SPLIT>
+__global__ __launch_bounds__(256) void conv_igemm_kernel(const IgemmArgs a)
+{
+    igemm_tile<DT, BM, BN, WM, WN, SPLIT>(a, blockIdx.x, blockIdx.y, blockIdx.z);
+}
+
+// Two convolutions of the same input in one launch (a BasicBlock's first 3x3
+// convolution and the 1x1 convolution of its shortcut, which reads the centre
+// tap of the same windows): workgroups [0, tiles0) run the first problem, the
+// rest the second.  Neither depends on the other, so the short second problem
+// fills the tail of the first instead of paying a launch of its own.
+template <int DT, int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(256) void conv_igemm_pair_kernel(const IgemmArgs a0, const IgemmArgs a1, int grid_m0,
+                                                              int tiles0, int grid_m1)
+{
+    const int b = blockIdx.x;
+    if (b < tiles0)
+        igemm_tile<DT, BM, BN, WM, WN, false>(a0, b % grid_m0, b / grid_m0, 0);
+    else
+        igemm_tile<DT, BM, BN, WM, WN, false>(a1, (b - tiles0) % grid_m1, (b - tiles0) / grid_m1, 0);
 }
 
 // Second pass of split-K: sums the slices in index order, then scale/shift,
@@ -328,6 +351,43 @@ static int launch_dtype(const IgemmArgs& a, const ConvPlan& p, hipStream_t strea
     }
 }
 
+template <int DT, int BM, int BN, int WM, int WN>
+static int launch_pair_variant(const IgemmArgs& a0, const ConvPlan& p0, const IgemmArgs& a1, const ConvPlan& p1,
+                               hipStream_t stream)
+{
+    const int tiles0 = p0.grid_m * p0.grid_n, tiles1 = p1.grid_m * p1.grid_n;
+    SGPRS_LAUNCH((conv_igemm_pair_kernel<DT, BM, BN, WM, WN>), dim3(tiles0 + tiles1), dim3(256), 2 * (BM + BN) * 128,
+                 stream, a0, a1, p0.grid_m, tiles0, p1.grid_m);
+    SGPRS_HIP(hipGetLastError());
+    return SGPRS_OK;
+}
+
+template <int DT>
+static int launch_pair_dtype(const IgemmArgs& a0, const ConvPlan& p0, const IgemmArgs& a1, const ConvPlan& p1,
+                             hipStream_t stream)
+{
+    switch (p0.variant) {
+        case 0: return launch_pair_variant<DT, 128, 128, 2, 2>(a0, p0, a1, p1, stream);
+        case 1: return launch_pair_variant<DT, 128, 64, 2, 2>(a0, p0, a1, p1, stream);
+        case 2: return launch_pair_variant<DT, 64, 64, 2, 2>(a0, p0, a1, p1, stream);
+        case 3: return launch_pair_variant<DT, 32, 128, 1, 4>(a0, p0, a1, p1, stream);
+        default: return fail(SGPRS_ERR_INVALID_ARG, "bad igemm variant %d", p0.variant);
+    }
+}
+
+// Name as a profiler prints it: v = tile variant + 4 * dtype.
+const char* igemm_pair_variant_name(int v)
+{
+    static const int shape[4][4] = {{128, 128, 2, 2}, {128, 64, 2, 2}, {64, 64, 2, 2}, {32, 128, 1, 4}};
+    static char buf[8][96];
+    static int next = 0;
+    if (v < 0 || v >= 8) return "?";
+    const int* t = shape[v & 3];
+    char* out = buf[next++ & 7];
+    snprintf(out, 96, "conv_igemm_pair_kernel<%d, %d, %d, %d, %d>", (v >> 2) & 1, t[0], t[1], t[2], t[3]);
+    return out;
+}
+
 // Name as a profiler prints it: v = tile variant + 4 * dtype + 8 * split.
 const char* igemm_variant_name(int v)
 {
@@ -356,6 +416,61 @@ int launch_splitk_reduce(int dtype, const float* partial, int splits, size_t tot
     return SGPRS_OK;
 }
 
+// Kernel arguments for plan p; false if the plan does not match the shape
+// (the host-side checks the kernel relies on).
+static bool fill_igemm_args(const sgprs_conv_desc_t& d, const ConvPlan& p, const void* x, const void* w,
+                            const float* scale, const float* shift, const void* residual, void* y, void* ws,
+                            IgemmArgs* out)
+{
+    const int es = (int)dtype_size(d.dtype), kt_el = 128 / es;
+    IgemmArgs& a = *out;
+    a.x = (const unsigned char*)x; a.w = (const unsigned char*)w; a.y = (unsigned char*)y;
+    a.scale = scale; a.shift = shift; a.res = (const unsigned char*)residual; a.partial = (float*)ws;
+    a.H = d.h; a.W = d.w; a.Cin = d.cin; a.Cout = d.cout;
+    a.P = out_dim(d.h, d.r, d.stride, d.pad); a.Q = out_dim(d.w, d.s, d.stride, d.pad);
+    a.S = d.s; a.stride = d.stride; a.pad = d.pad;
+    a.PQ = a.P * a.Q; a.M = d.n * a.PQ;
+    a.ktiles = p.ktiles; a.kt_per_split = (p.ktiles + p.splits - 1) / p.splits;
+    a.cin_tiles = d.cin / kt_el; a.relu = d.relu;
+    return !(d.cin % kt_el || d.cout % p.bn || p.grid_m != (a.M + p.bm - 1) / p.bm || p.grid_n != d.cout / p.bn ||
+             (long long)(p.splits - 1) * a.kt_per_split >= p.ktiles);
+}
+
+// Both convolutions in one launch when both plans are the same implicit-GEMM
+// tile without split-K; *done = false (and nothing launched) otherwise.
+int launch_conv_pair(const sgprs_conv_desc_t& d0, const void* w0, const float* scale0, const float* shift0, void* y0,
+                     const sgprs_conv_desc_t& d1, const void* w1, const float* scale1, const float* shift1, void* y1,
+                     const void* x, hipStream_t stream, int cus, Profiler* prof, bool* done)
+{
+    *done = false;
+    if (d0.dtype != d1.dtype || d0.n != d1.n || d0.h != d1.h || d0.w != d1.w || d0.cin != d1.cin) return SGPRS_OK;
+    const ConvPlan p0 = plan_conv(d0, cus);
+    ConvPlan p1 = plan_conv(d1, cus);
+    if (p0.bm == 0 || p0.kind != 0 || p0.splits != 1 || p1.bm == 0 || p1.kind != 0) return SGPRS_OK;
+    // the second problem takes the first one's tile shape
+    const int es = (int)dtype_size(d1.dtype);
+    const long long M1 = (long long)d1.n * out_dim(d1.h, d1.r, d1.stride, d1.pad) * out_dim(d1.w, d1.s, d1.stride, d1.pad);
+    if (d1.cout % p0.bn) return SGPRS_OK;
+    p1.variant = p0.variant; p1.bm = p0.bm; p1.bn = p0.bn; p1.splits = 1;
+    p1.grid_m = (int)((M1 + p0.bm - 1) / p0.bm); p1.grid_n = d1.cout / p0.bn;
+    p1.ktiles = d1.r * d1.s * d1.cin / (128 / es);
+    IgemmArgs a0, a1;
+    if (!fill_igemm_args(d0, p0, x, w0, scale0, shift0, nullptr, y0, nullptr, &a0) ||
+        !fill_igemm_args(d1, p1, x, w1, scale1, shift1, nullptr, y1, nullptr, &a1))
+        return fail(SGPRS_ERR_INVALID_ARG, "internal: launch plan does not match the shape");
+    const double flops = 2.0 * a0.M * d0.cout * (double)d0.r * d0.s * d0.cin + 2.0 * a1.M * d1.cout * (double)d1.r * d1.s * d1.cin;
+    const double bytes = ((double)d0.n * d0.h * d0.w * d0.cin + (double)d0.cout * d0.r * d0.s * d0.cin +
+                          (double)d1.cout * d1.r * d1.s * d1.cin + (double)a0.M * d0.cout + (double)a1.M * d1.cout) * es;
+    int rc;
+    if (prof && prof->on && (rc = prof->begin(stream, kKindIgemmPair, d0.dtype * 4 + p0.variant, flops, bytes))) return rc;
+    rc = d0.dtype == SGPRS_BF16 ? launch_pair_dtype<SGPRS_BF16>(a0, p0, a1, p1, stream)
+                                : launch_pair_dtype<SGPRS_F32>(a0, p0, a1, p1, stream);
+    if (rc) return rc;
+    if (prof && prof->on && (rc = prof->end(stream))) return rc;
+    *done = true;
+    return SGPRS_OK;
+}
+
 int launch_conv(const sgprs_conv_desc_t& d, const void* x, const void* w, const float* scale,
                 const float* shift, const void* residual, void* y, void* ws, size_t ws_bytes,
                 hipStream_t stream, int cus, Profiler* prof)
@@ -368,19 +483,9 @@ int launch_conv(const sgprs_conv_desc_t& d, const void* x, const void* w, const 
     const size_t need = conv_workspace_bytes(d, p);
     if (need > ws_bytes || (need && !ws))
         return fail(SGPRS_ERR_INVALID_ARG, "split-K workspace %zu bytes needed, %zu given", need, ws_bytes);
-    const int es = (int)dtype_size(d.dtype), kt_el = 128 / es;
+    const int es = (int)dtype_size(d.dtype);
     IgemmArgs a;
-    a.x = (const unsigned char*)x; a.w = (const unsigned char*)w; a.y = (unsigned char*)y;
-    a.scale = scale; a.shift = shift; a.res = (const unsigned char*)residual; a.partial = (float*)ws;
-    a.H = d.h; a.W = d.w; a.Cin = d.cin; a.Cout = d.cout;
-    a.P = out_dim(d.h, d.r, d.stride, d.pad); a.Q = out_dim(d.w, d.s, d.stride, d.pad);
-    a.S = d.s; a.stride = d.stride; a.pad = d.pad;
-    a.PQ = a.P * a.Q; a.M = d.n * a.PQ;
-    a.ktiles = p.ktiles; a.kt_per_split = (p.ktiles + p.splits - 1) / p.splits;
-    a.cin_tiles = d.cin / kt_el; a.relu = d.relu;
-    // host-side shape checks the kernel relies on
-    if (d.cin % kt_el || d.cout % p.bn || p.grid_m != (a.M + p.bm - 1) / p.bm || p.grid_n != d.cout / p.bn ||
-        (long long)(p.splits - 1) * a.kt_per_split >= p.ktiles)
+    if (!fill_igemm_args(d, p, x, w, scale, shift, residual, y, ws, &a))
         return fail(SGPRS_ERR_INVALID_ARG, "internal: launch plan does not match the shape");
     const double flops = 2.0 * a.M * d.cout * (double)d.r * d.s * d.cin;
     const double bytes = ((double)d.n * d.h * d.w * d.cin + (double)d.cout * d.r * d.s * d.cin +

@@ -127,7 +127,8 @@ struct Profiler {
 };
 
 enum KernelKind { kKindIgemm = 0, kKindStem = 1, kKindReduce = 2, kKindMaxpool = 3, kKindAvgpool = 4,
-                  kKindFc = 5, kKindBnRelu = 6, kKindAdd = 7, kKindPatch = 8, kKindStemPool = 9 };
+                  kKindFc = 5, kKindBnRelu = 6, kKindAdd = 7, kKindPatch = 8, kKindStemPool = 9,
+                  kKindIgemmPair = 10 };
 
 // launchers (device pointers; validated by callers)
 int launch_conv(const sgprs_conv_desc_t& d, const void* x, const void* w, const float* scale,
@@ -163,6 +164,10 @@ int launch_splitk_reduce(int dtype, const float* partial, int splits, size_t tot
 extern int g_conv_force_kind;
 
 const char* igemm_variant_name(int v);
+const char* igemm_pair_variant_name(int v);
+int launch_conv_pair(const sgprs_conv_desc_t& d0, const void* w0, const float* scale0, const float* shift0, void* y0,
+                     const sgprs_conv_desc_t& d1, const void* w1, const float* scale1, const float* shift1, void* y1,
+                     const void* x, hipStream_t stream, int cus, Profiler* prof, bool* done);
 int igemm_num_variants();
 
 }  // namespace sgprs

@@ -135,11 +135,20 @@ int run_block(sgprs_task* t, int c1, int c2, int down, int batch, const void* x,
               Profiler* prof)
 {
     int rc;
-    if ((rc = run_conv(t, c1, batch, x, nullptr, t->tmp[0], 1, s, cus, prof))) return rc;
     const void* shortcut = x;
-    if (down >= 0) {
-        if ((rc = run_conv(t, down, batch, x, nullptr, t->tmp[1], 0, s, cus, prof))) return rc;
+    bool paired = false;
+    if (down >= 0) {  // conv1 and the shortcut's 1x1 convolution read the same input: one launch when the plans allow
+        sgprs_conv_desc_t d0 = t->conv[c1].d, d1 = t->conv[down].d;
+        d0.n = d1.n = batch; d0.relu = 1; d1.relu = 0;
+        if ((rc = launch_conv_pair(d0, t->conv[c1].w, t->conv[c1].scale, t->conv[c1].shift, t->tmp[0], d1,
+                                   t->conv[down].w, t->conv[down].scale, t->conv[down].shift, t->tmp[1], x, s, cus, prof,
+                                   &paired)))
+            return rc;
         shortcut = t->tmp[1];
+    }
+    if (!paired) {
+        if ((rc = run_conv(t, c1, batch, x, nullptr, t->tmp[0], 1, s, cus, prof))) return rc;
+        if (down >= 0 && (rc = run_conv(t, down, batch, x, nullptr, t->tmp[1], 0, s, cus, prof))) return rc;
     }
     return run_conv(t, c2, batch, t->tmp[0], shortcut, out, 1, s, cus, prof);
 }
@@ -381,6 +390,7 @@ const char* sgprs_kernel_name(int kind, int variant)
 {
     switch (kind) {
         case kKindIgemm: return igemm_variant_name(variant);
+        case kKindIgemmPair: return igemm_pair_variant_name(variant);
         case kKindPatch: return patch_variant_name(variant);
         case kKindStem: return "conv_stem_kernel";
         case kKindStemPool: return variant == SGPRS_BF16 ? "stem_pool_kernel<1>" : "stem_pool_kernel<0>";

@@ -144,6 +144,30 @@ def test_task_run_across_partitions_matches_single_partition(cfg1):
     pool.destroy()
 
 
+def test_downsample_block_runs_as_one_paired_launch(cfg1):
+    """With enough tiles per CU nothing needs split-K, so the first convolution
+    of a down-sampling block and the 1x1 convolution of its shortcut go out as
+    one launch (kind 10); the stages must still match the oracle."""
+    params = cfg1[0]
+    nb = 8
+    x = make_input(1, 7, (nb, 3, 224, 224))
+    _, outs = oracle.resnet18(params, BN_EPS, x, want_stages=True)
+    pool = S.Pool(1, 8)   # 8 images on 8 CUs: no layer of stages 2-4 is split
+    for dtype in (S.SGPRS_F32, S.SGPRS_BF16):
+        task = S.Task(params, dtype, nb, BN_EPS)
+        task.set_profiling(True)
+        for j in (2, 3, 4):
+            xd = dev_nhwc(outs[j - 1], dtype)
+            o = dev_empty(stage_shape(j, nb), dtype)
+            task.stage_run(j, nb, xd.data_ptr(), o.data_ptr(), pool, 0)
+            pool.sync()
+            assert_close(host_nchw(o), outs[j], dtype, f"paired stage {j} dtype {dtype}")
+            kinds = [r["kind"] for r in task.kernel_times(j)]
+            assert kinds.count(10) == 1, (j, dtype, kinds)
+        task.destroy()
+    pool.destroy()
+
+
 # ------------------------------------------------------------- config 3
 def test_config3_eight_bf16_instances_on_8x32_pool():
     dtype = S.SGPRS_BF16
@@ -233,6 +257,6 @@ def test_kernel_times_records(full_pool, cfg1):
     for j in range(6):
         recs = task.kernel_times(j)
         assert recs and all(r["ms"] >= 0 for r in recs)
-        flops += sum(r["flops"] for r in recs if r["kind"] in (0, 1, 5, 8, 9))
+        flops += sum(r["flops"] for r in recs if r["kind"] in (0, 1, 5, 8, 9, 10))
     assert abs(flops - 2 * 1814073344) / (2 * 1814073344) < 1e-9
     task.destroy()
