@@ -38,6 +38,7 @@ struct IgemmArgs {
     int M, PQ;
     int ktiles, kt_per_split, cin_tiles;
     int relu;
+    unsigned x_bytes, w_bytes;  // buffer-descriptor bounds of x and w
 };
 
 __device__ __forceinline__ float bf16_to_f32(unsigned short b) { return __uint_as_float((unsigned)b << 16); }
@@ -65,7 +66,51 @@ template <> struct Store<SGPRS_BF16> {
 
 __device__ __forceinline__ int swz(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
 
+// Pipeline depth (LDS stages).  Measured on the batch-64 layers, deeper
+// pipelines lose more from the lower occupancy (workgroups per CU) than they
+// gain: the loop is bound by L2 -> LDS bandwidth, not by latency.
+template <int BM, int BN> struct IgemmStages { static constexpr int value = 2; };
+
+// Loads of one pipeline stage (k-tile ktc), straight into LDS at As: A_IT
+// instructions for the input rows, B_IT for the weight rows.  !live: the
+// descriptors have size 0 and nothing is fetched.
+template <int ES, int BM, int A_IT, int B_IT>
+__device__ __forceinline__ void igemm_issue_stage(const IgemmArgs& a, unsigned char* As, bool live, int ktc, int wave,
+                                                  const int (&a_base)[A_IT], const int (&a_h0)[A_IT],
+                                                  const int (&a_w0)[A_IT], const unsigned (&b_off)[B_IT])
+{
+#if __HIP_DEVICE_COMPILE__  // the buffer-resource builtins exist in the device pass only
+    typedef __attribute__((address_space(3))) void* lds_ptr_t;
+    constexpr int KT = 128 / ES;
+    const __amdgpu_buffer_rsrc_t x_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.x, 0, live ? (int)a.x_bytes : 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t w_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, live ? (int)a.w_bytes : 0, 0x00020000);
+    const int tap = ktc / a.cin_tiles;
+    const int c0 = (ktc - tap * a.cin_tiles) * KT;
+    const int r = tap / a.S, s = tap - r * a.S;
+    const int tap_off = (r * a.W + s) * a.Cin + c0;
+#pragma unroll
+    for (int i = 0; i < A_IT; ++i) {
+        const int ih = a_h0[i] + r, iw = a_w0[i] + s;
+        const bool ok = (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+        const unsigned voff = ok ? (unsigned)(a_base[i] + tap_off) * ES : 0x80000000u;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rs, (lds_ptr_t)(As + (i * 32 + wave * 8) * 128), 16, voff, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < B_IT; ++i)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rs, (lds_ptr_t)(As + (BM + i * 32 + wave * 8) * 128), 16, b_off[i],
+                                                 ktc * 128, 0, 0);
+#endif
+}
+
 // One BM x BN output tile: tile column bx, channel block by, split-K slice bz.
+//
+// The k-tiles move global -> LDS directly (buffer loads with the LDS bit; one
+// wavefront instruction fills 8 swizzled rows = 1 KiB), NS stages deep: while
+// k-tile kt feeds the MFMAs, k-tiles kt+1 .. kt+NS-2 are in flight and the
+// loads of kt+NS-1 are issued.  Taps outside the image get a buffer offset
+// beyond the descriptor's size, for which the hardware returns zeros; k-tiles
+// past the end use a descriptor of size 0.  Every stage issues the same number
+// of loads, so "k-tile kt has landed" is a fixed vmcnt.
 template <int DT, int BM, int BN, int WM, int WN, bool SPLIT>
 __device__ __forceinline__ void igemm_tile(const IgemmArgs& a, int bx, int by, int bz)
 {
@@ -74,9 +119,12 @@ __device__ __forceinline__ void igemm_tile(const IgemmArgs& a, int bx, int by, i
     constexpr int CH = 16 / ES;                   // elements per 16-byte chunk
     constexpr int WTM = BM / WM, WTN = BN / WN;   // wavefront tile
     constexpr int TM = WTM / 32, TN = WTN / 32;   // 32x32 MFMA tiles per wavefront
-    constexpr int A_IT = BM / 32, B_IT = BN / 32; // rows loaded per thread
+    constexpr int A_IT = BM / 32, B_IT = BN / 32; // load instructions per thread and stage
     constexpr int STAGE = (BM + BN) * 128;
+    constexpr int NS = IgemmStages<BM, BN>::value;
+    constexpr int LPS = A_IT + B_IT;
     static_assert(WM * WN == 4 && TM >= 1 && TN >= 1, "tile shape");
+    static_assert((NS - 2) * LPS <= 63, "vmcnt range");
 
     extern __shared__ __align__(16) unsigned char smem[];
 
@@ -87,8 +135,10 @@ __device__ __forceinline__ void igemm_tile(const IgemmArgs& a, int bx, int by, i
     const int kt_end = min(kt_begin + a.kt_per_split, a.ktiles);
     const int K = a.ktiles * KT;
 
-    // ---- loader bookkeeping: this thread moves chunk lchunk of rows lrow+32*i
-    const int lchunk = tid & 7, lrow = tid >> 3;
+    // ---- loader bookkeeping: instruction i of this wavefront fills rows
+    // i*32 + wave*8 .. +7 of a stage; this lane's LDS slot (lane & 7) of row
+    // lane >> 3 holds global chunk (lane & 7) ^ (lane >> 3) (the swizzle).
+    const int lrow = wave * 8 + (lane >> 3), gchunk = (lane & 7) ^ (lane >> 3);
     int a_base[A_IT], a_h0[A_IT], a_w0[A_IT];
 #pragma unroll
     for (int i = 0; i < A_IT; ++i) {
@@ -98,40 +148,20 @@ __device__ __forceinline__ void igemm_tile(const IgemmArgs& a, int bx, int by, i
             const int p = rem / a.Q, q = rem - p * a.Q;
             a_h0[i] = p * a.stride - a.pad;
             a_w0[i] = q * a.stride - a.pad;
-            a_base[i] = ((n * a.H + a_h0[i]) * a.W + a_w0[i]) * a.Cin + lchunk * CH;
+            a_base[i] = ((n * a.H + a_h0[i]) * a.W + a_w0[i]) * a.Cin + gchunk * CH;
         } else {
             a_h0[i] = -(1 << 20);  // every tap falls outside the image
             a_w0[i] = 0;
             a_base[i] = 0;
         }
     }
-    const unsigned char* wrow = a.w + ((size_t)(n0 + lrow) * K + lchunk * CH) * ES;
+    unsigned b_off[B_IT];
+#pragma unroll
+    for (int i = 0; i < B_IT; ++i) b_off[i] = (unsigned)((n0 + lrow + 32 * i) * K + gchunk * CH) * ES;
 
-    u32x4_t areg[A_IT], breg[B_IT];
-    auto load_global = [&](int kt) {
-        const int tap = kt / a.cin_tiles;
-        const int c0 = (kt - tap * a.cin_tiles) * KT;
-        const int r = tap / a.S, s = tap - r * a.S;
-        const int tap_off = (r * a.W + s) * a.Cin + c0;
-#pragma unroll
-        for (int i = 0; i < A_IT; ++i) {
-            const int ih = a_h0[i] + r, iw = a_w0[i] + s;
-            const bool ok = (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
-            u32x4_t v = {0u, 0u, 0u, 0u};
-            if (ok) v = *(const u32x4_t*)(a.x + (size_t)(a_base[i] + tap_off) * ES);
-            areg[i] = v;
-        }
-#pragma unroll
-        for (int i = 0; i < B_IT; ++i)
-            breg[i] = *(const u32x4_t*)(wrow + ((size_t)i * 32 * K + (size_t)kt * KT) * ES);
-    };
-    auto store_lds = [&](int buf) {
-        unsigned char* As = smem + buf * STAGE;
-        unsigned char* Bs = As + BM * 128;
-#pragma unroll
-        for (int i = 0; i < A_IT; ++i) *(u32x4_t*)(As + swz(lrow + 32 * i, lchunk)) = areg[i];
-#pragma unroll
-        for (int i = 0; i < B_IT; ++i) *(u32x4_t*)(Bs + swz(lrow + 32 * i, lchunk)) = breg[i];
+    auto issue_stage = [&](int kt, int stage) {
+        igemm_issue_stage<ES, BM, A_IT, B_IT>(a, smem + stage * STAGE, kt < kt_end, kt < kt_end ? kt : kt_begin, wave, a_base,
+                                              a_h0, a_w0, b_off);
     };
 
     f32x16_t acc[TM][TN];
@@ -143,26 +173,30 @@ __device__ __forceinline__ void igemm_tile(const IgemmArgs& a, int bx, int by, i
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
     const int frow = lane & 31, fhalf = lane >> 5;
+    // fragment addresses inside a stage for k-step 0; k-step ks flips bits 5-6
+    unsigned fa_off[TM], fb_off[TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa_off[i] = swz(wm * WTM + i * 32 + frow, fhalf);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb_off[j] = BM * 128 + swz(wn * WTN + j * 32 + frow, fhalf);
 
-    if (kt_begin < kt_end) {
-        load_global(kt_begin);
-        store_lds(0);
-    }
-    __syncthreads();
-    int buf = 0;
+#pragma unroll
+    for (int q = 0; q < NS - 1; ++q) issue_stage(kt_begin + q, q);
+    int stage = 0;
     for (int kt = kt_begin; kt < kt_end; ++kt) {
-        const bool more = kt + 1 < kt_end;
-        if (more) load_global(kt + 1);
-        const unsigned char* As = smem + buf * STAGE;
-        const unsigned char* Bs = As + BM * 128;
+        // k-tile kt has landed once at most the NS-2 younger stages are outstanding
+        __builtin_amdgcn_s_waitcnt(((NS - 2) * LPS & 15) | (((NS - 2) * LPS >> 4) << 14) | 0x0F70);
+        __syncthreads();  // ... for every thread; and the stage read last iteration is free
+        const int free_stage = stage == 0 ? NS - 1 : stage - 1;
+        issue_stage(kt + NS - 1, free_stage);
+        const unsigned char* St = smem + stage * STAGE;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            const int chunk = 2 * ks + fhalf;
             u32x4_t af[TM], bf[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) af[i] = *(const u32x4_t*)(As + swz(wm * WTM + i * 32 + frow, chunk));
+            for (int i = 0; i < TM; ++i) af[i] = *(const u32x4_t*)(St + (fa_off[i] ^ (ks << 5)));
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bf[j] = *(const u32x4_t*)(Bs + swz(wn * WTN + j * 32 + frow, chunk));
+            for (int j = 0; j < TN; ++j) bf[j] = *(const u32x4_t*)(St + (fb_off[j] ^ (ks << 5)));
             if constexpr (DT == SGPRS_BF16) {
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
@@ -182,10 +216,11 @@ __device__ __forceinline__ void igemm_tile(const IgemmArgs& a, int bx, int by, i
                                 __uint_as_float(af[i][u]), __uint_as_float(bf[j][u]), acc[i][j], 0, 0, 0);
             }
         }
-        if (more) store_lds(buf ^ 1);
-        __syncthreads();
-        buf ^= 1;
+        stage = stage == NS - 1 ? 0 : stage + 1;
     }
+    // drain the (empty) loads still in flight before the staging area becomes scratch
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
 
     // ---- epilogue.  32x32 accumulator layout: column = lane % 32,
     // row = 8*(e/4) + 4*(lane/32) + e%4 for register e.
@@ -197,7 +232,7 @@ __device__ __forceinline__ void igemm_tile(const IgemmArgs& a, int bx, int by, i
     constexpr int LPR = WTN / 8;   // lanes per row in the read-back
     constexpr int RPP = 64 / LPR;  // rows per pass
     constexpr int NPASS = 32 / RPP;
-    static_assert(4 * 32 * SROW * 4 <= 2 * STAGE, "epilogue scratch fits the staging buffers");
+    static_assert(4 * 32 * SROW * 4 <= NS * STAGE, "epilogue scratch fits the staging buffers");
     float* scr = (float*)smem + wave * 32 * SROW;
     const int c8 = (lane % LPR) * 8, rsub = lane / LPR;
     const int nb = n0 + wn * WTN + c8;
@@ -278,7 +313,8 @@ __device__ __forceinline__ void igemm_tile(const IgemmArgs& a, int bx, int by, i
 template <int DT, int BM, int BN, int WM, int WN, bool SPLIT>
 __global__ __launch_bounds__(256) void conv_igemm_kernel(const IgemmArgs a)
 {
-    igemm_tile<DT, BM, BN, WM, WN, SPLIT>(a, blockIdx.x, blockIdx.y, blockIdx.z);
+    const int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+    igemm_tile<DT, BM, BN, WM, WN, SPLIT>(a, bx, by, bz);
 }
 
 // Two convolutions of the same input in one launch (a BasicBlock's first 3x3
@@ -330,7 +366,15 @@ template <int DT, int BM, int BN, int WM, int WN>
 static int launch_variant(const IgemmArgs& a, const ConvPlan& p, hipStream_t stream)
 {
     const dim3 grid(p.grid_m, p.grid_n, p.splits), block(256);
-    const size_t lds = 2 * (BM + BN) * 128;
+    const size_t lds = (size_t)IgemmStages<BM, BN>::value * (BM + BN) * 128;
+    static bool raised = false;  // more than the default 64 KiB of dynamic LDS needs an opt-in per kernel
+    if (!raised) {
+        SGPRS_HIP(hipFuncSetAttribute((const void*)conv_igemm_kernel<DT, BM, BN, WM, WN, true>,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        SGPRS_HIP(hipFuncSetAttribute((const void*)conv_igemm_kernel<DT, BM, BN, WM, WN, false>,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        raised = true;
+    }
     if (p.splits > 1)
         SGPRS_LAUNCH((conv_igemm_kernel<DT, BM, BN, WM, WN, true>), grid, block, lds, stream, a);
     else
@@ -356,8 +400,14 @@ static int launch_pair_variant(const IgemmArgs& a0, const ConvPlan& p0, const Ig
                                hipStream_t stream)
 {
     const int tiles0 = p0.grid_m * p0.grid_n, tiles1 = p1.grid_m * p1.grid_n;
-    SGPRS_LAUNCH((conv_igemm_pair_kernel<DT, BM, BN, WM, WN>), dim3(tiles0 + tiles1), dim3(256), 2 * (BM + BN) * 128,
-                 stream, a0, a1, p0.grid_m, tiles0, p1.grid_m);
+    const size_t lds = (size_t)IgemmStages<BM, BN>::value * (BM + BN) * 128;
+    static bool raised = false;
+    if (!raised) {
+        SGPRS_HIP(hipFuncSetAttribute((const void*)conv_igemm_pair_kernel<DT, BM, BN, WM, WN>,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        raised = true;
+    }
+    SGPRS_LAUNCH((conv_igemm_pair_kernel<DT, BM, BN, WM, WN>), dim3(tiles0 + tiles1), dim3(256), lds, stream, a0, a1, p0.grid_m, tiles0, p1.grid_m);
     SGPRS_HIP(hipGetLastError());
     return SGPRS_OK;
 }
@@ -432,6 +482,10 @@ static bool fill_igemm_args(const sgprs_conv_desc_t& d, const ConvPlan& p, const
     a.PQ = a.P * a.Q; a.M = d.n * a.PQ;
     a.ktiles = p.ktiles; a.kt_per_split = (p.ktiles + p.splits - 1) / p.splits;
     a.cin_tiles = d.cin / kt_el; a.relu = d.relu;
+    // x and w are addressed through 31-bit buffer offsets
+    const long long xb = (long long)d.n * d.h * d.w * d.cin * es, wb = (long long)d.cout * d.r * d.s * d.cin * es;
+    if (xb >= (1ll << 31) || wb >= (1ll << 31)) return false;
+    a.x_bytes = (unsigned)xb; a.w_bytes = (unsigned)wb;
     return !(d.cin % kt_el || d.cout % p.bn || p.grid_m != (a.M + p.bm - 1) / p.bm || p.grid_n != d.cout / p.bn ||
              (long long)(p.splits - 1) * a.kt_per_split >= p.ktiles);
 }

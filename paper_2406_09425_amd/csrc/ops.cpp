@@ -72,8 +72,9 @@ int sgprs_conv2d(const sgprs_conv_desc_t* d, const void* x, const void* w_packed
 
 int sgprs_conv_tuning_override(int kind, int variant, int splits)
 {
-    if (kind < -1 || kind > 1) return fail(SGPRS_ERR_INVALID_ARG, "kind %d outside [-1,1]", kind);
-    g_conv_force_kind = kind;
+    if (kind < -1 || kind > 2) return fail(SGPRS_ERR_INVALID_ARG, "kind %d outside [-1,2]", kind);
+    g_conv_force_kind = kind == 2 ? -1 : kind;
+    g_igemm_force_variant = kind == 2 ? variant : -1;
     patch_force(kind == 1 ? variant : -1, splits);
     return SGPRS_OK;
 }

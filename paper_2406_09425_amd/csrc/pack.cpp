@@ -53,6 +53,7 @@ static const Tile kTiles[] = {{128, 128, 1.0}, {128, 64, 0.85}, {64, 64, 0.6}, {
 int igemm_num_variants() { return (int)(sizeof(kTiles) / sizeof(kTiles[0])); }
 
 int g_conv_force_kind = -1;
+int g_igemm_force_variant = -1;
 
 ConvPlan plan_conv(const sgprs_conv_desc_t& d, int cus)
 {
@@ -77,6 +78,9 @@ ConvPlan plan_conv(const sgprs_conv_desc_t& d, int cus)
     for (int v = 0; v < igemm_num_variants(); ++v) {
         const Tile& t = kTiles[v];
         if (d.cout % t.bn) continue;
+        if (g_igemm_force_variant >= 0 && g_igemm_force_variant < igemm_num_variants() && v != g_igemm_force_variant &&
+            d.cout % kTiles[g_igemm_force_variant].bn == 0)
+            continue;
         const long long gm = (M + t.bm - 1) / t.bm, gn = d.cout / t.bn;
         const long long blocks = gm * gn;
         const int occ = 2;  // workgroups resident per CU
