@@ -13,8 +13,9 @@
 // (weights as the row operand, pixels as the column operand) so that a lane's
 // accumulator registers hold 4 consecutive channels of one pixel, which go to
 // the LDS staging area as one 8-byte (bf16) or 16-byte (fp32) write.
-// Positions outside the conv output hold -inf in the staging area, so padding
-// never wins the maximum.
+// Positions outside the conv output hold -inf (fp32) or 0 (bf16, where the
+// post-ReLU values are pooled as unsigned bit patterns) in the staging area, so
+// padding never wins the maximum.
 #include "internal.h"
 
 namespace sgprs {
@@ -24,6 +25,9 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+typedef unsigned short u16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
 
 struct StemPoolArgs {
     const unsigned char* x;
@@ -57,8 +61,7 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemPoolArgs a)
 
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char* Ws = smem;
-    float* SCs = (float*)(smem + W_BYTES);           // scale[64], shift[64]
-    unsigned char* Ps = smem + W_BYTES + 512;        // patch, later the conv staging area
+    unsigned char* Ps = smem + W_BYTES;              // patch, later the conv staging area
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int frow = lane & 31, fhalf = lane >> 5;
@@ -67,7 +70,6 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemPoolArgs a)
         const int row = i / (kStemK * ES / 16), ch = i - row * (kStemK * ES / 16);
         *(u32x4_t*)(Ws + row * WROW + ch * 16) = *(const u32x4_t*)(a.w + (size_t)row * kStemK * ES + ch * 16);
     }
-    if (tid < 64) { SCs[tid] = a.scale[tid]; SCs[64 + tid] = a.shift[tid]; }
 
     // The next tile's input patch is fetched into registers while the current
     // tile computes: PF_IT pixels per thread, 3 channels each.
@@ -86,15 +88,15 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemPoolArgs a)
             const size_t g = ((size_t)(n * a.H + (ok ? ih : 0)) * a.W + (ok ? iw : 0)) * 3;
             if constexpr (DT == SGPRS_BF16) {
                 const unsigned short* xp = (const unsigned short*)a.x + g;
-                unsigned short v0 = 0, v1 = 0, v2 = 0;
-                if (ok) { v0 = xp[0]; v1 = xp[1]; v2 = xp[2]; }
-                pf_lo[it] = (unsigned)v0 | ((unsigned)v1 << 16);
-                pf_hi[it] = (unsigned)v2;
+                // unconditional loads from a clamped (always valid) pixel, zeroed afterwards:
+                // nothing waits on a branch, all loads of the patch are in flight together
+                const unsigned v0 = xp[0], v1 = xp[1], v2 = xp[2];
+                pf_lo[it] = ok ? v0 | (v1 << 16) : 0u;
+                pf_hi[it] = ok ? v2 : 0u;
             } else {
                 const unsigned* xp = (const unsigned*)a.x + g;
-                unsigned v0 = 0, v1 = 0, v2 = 0;
-                if (ok) { v0 = xp[0]; v1 = xp[1]; v2 = xp[2]; }
-                pf_lo[it] = v0; pf_hi[it] = v1; pf_x[it] = v2;
+                const unsigned v0 = xp[0], v1 = xp[1], v2 = xp[2];
+                pf_lo[it] = ok ? v0 : 0u; pf_hi[it] = ok ? v1 : 0u; pf_x[it] = ok ? v2 : 0u;
             }
         }
     };
@@ -112,6 +114,16 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemPoolArgs a)
             }
         }
     };
+
+    // this lane's BN scale / shift: accumulator register 4g+u of channel tile i is channel 32i + 8g + 4*fhalf + u
+    f32x4_t sc[2][4], sh[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            sc[i][g] = *(const f32x4_t*)(a.scale + 32 * i + 8 * g + 4 * fhalf);
+            sh[i][g] = *(const f32x4_t*)(a.shift + 32 * i + 8 * g + 4 * fhalf);
+        }
 
     if ((int)blockIdx.x < a.ntiles) fetch_patch(blockIdx.x);
     for (int tile = blockIdx.x; tile < a.ntiles; tile += gridDim.x) {
@@ -186,21 +198,21 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemPoolArgs a)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const int c = 32 * i + 8 * g + 4 * fhalf;
-                    const f32x4_t sc = *(const f32x4_t*)(SCs + c), sh = *(const f32x4_t*)(SCs + 64 + c);
                     float v[4];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) v[u] = ok ? fmaxf(acc[i][j][4 * g + u] * sc[u] + sh[u], 0.f) : -INFINITY;
+                    for (int u = 0; u < 4; ++u) v[u] = fmaxf(acc[i][j][4 * g + u] * sc[i][g][u] + sh[i][g][u], 0.f);
                     if constexpr (DT == SGPRS_BF16) {
-                        unsigned short h[4];
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            const __bf16 b = (__bf16)v[u];
-                            h[u] = __builtin_bit_cast(unsigned short, b);
-                        }
-                        u32x2_t o = {(unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16)};
+                        // After the ReLU every value is >= 0, so pooling can compare bf16 bit
+                        // patterns as unsigned integers and positions outside the conv output
+                        // hold 0: each pooling window has a real pixel, so 0 never wins wrongly.
+                        // The sign bit is cleared so that a -0 cannot compare as large.
+                        const f32x2_t p0 = {v[0], v[1]}, p1 = {v[2], v[3]};
+                        const unsigned keep = ok ? 0x7fff7fffu : 0u;
+                        u32x2_t o = {__builtin_bit_cast(unsigned, __builtin_convertvector(p0, bf16x2_t)) & keep,
+                                     __builtin_bit_cast(unsigned, __builtin_convertvector(p1, bf16x2_t)) & keep};
                         *(u32x2_t*)(Ps + t * SROWB + c * 2) = o;
                     } else {
-                        f32x4_t o = {v[0], v[1], v[2], v[3]};
+                        f32x4_t o = {ok ? v[0] : -INFINITY, ok ? v[1] : -INFINITY, ok ? v[2] : -INFINITY, ok ? v[3] : -INFINITY};
                         *(f32x4_t*)(Ps + t * SROWB + c * 4) = o;
                     }
                 }
@@ -219,15 +231,13 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemPoolArgs a)
 #pragma unroll
             for (int rs = 1; rs < 9; ++rs) {
                 const u32x4_t t = *(const u32x4_t*)(base + ((rs / 3) * kConvC + rs % 3) * SROWB);
+                if constexpr (DT == SGPRS_BF16) {
+                    // whole-vector form: eight unsigned 16-bit maxima per tap
+                    m = __builtin_bit_cast(u32x4_t, __builtin_elementwise_max(__builtin_bit_cast(u16x8_t, m),
+                                                                              __builtin_bit_cast(u16x8_t, t)));
+                } else {
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    if constexpr (DT == SGPRS_BF16) {
-                        const float alo = __uint_as_float(m[u] << 16), ahi = __uint_as_float(m[u] & 0xffff0000u);
-                        const float blo = __uint_as_float(t[u] << 16), bhi = __uint_as_float(t[u] & 0xffff0000u);
-                        m[u] = (__float_as_uint(fmaxf(alo, blo)) >> 16) | (__float_as_uint(fmaxf(ahi, bhi)) & 0xffff0000u);
-                    } else {
-                        m[u] = __float_as_uint(fmaxf(__uint_as_float(m[u]), __uint_as_float(t[u])));
-                    }
+                    for (int u = 0; u < 4; ++u) m[u] = __float_as_uint(fmaxf(__uint_as_float(m[u]), __uint_as_float(t[u])));
                 }
             }
             *(u32x4_t*)(a.y + (((size_t)(n * a.PP + gp) * a.PQ + gq) * 64) * ES + grp * 16) = m;
@@ -259,7 +269,7 @@ int launch_stem_pool(int dtype, int n, int h, int w, const void* x, const void* 
     a.ntiles = (int)nt;
     const int es = (int)dtype_size(dtype);
     const int patch = kInR * kInC * 4 * es, stg = 256 * (64 * es + 16);
-    const size_t lds = 64 * (kStemK * es + 16) + 512 + (patch > stg ? patch : stg);
+    const size_t lds = 64 * (kStemK * es + 16) + (patch > stg ? patch : stg);
     const int occ = lds <= 80 * 1024 ? 2 : 1;
     const int grid = (int)std::min<long long>(nt, (long long)cus * occ);
     const double flops = 2.0 * n * a.P * a.Q * 64.0 * 147.0;
