@@ -413,7 +413,7 @@ __global__ __launch_bounds__((NW * 64), (PatchCfg<BM, BN, KC, NW>::WAVES_PER_SIM
 // resident (STAT) and only the patch is double buffered.
 __device__ __forceinline__ unsigned dl_swz(unsigned p) { return ((p >> 3) & 1u) | ((p >> 1) & 2u); }
 
-template <bool STAT>
+template <bool STAT, bool SPLIT>
 __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a)
 {
     constexpr int BN = 64, KC = 32, NT = 256;
@@ -429,7 +429,7 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int frow = lane & 31, fhalf = lane >> 5;
-    const int nch = a.n_chunks;
+    static_assert(!(STAT && SPLIT), "resident weights are for whole-K items");
 
     // weight loader: 16-byte unit u = it * 256 + tid is slot u % 4 of tap (u / 4) % 9 of row u / 36
     unsigned w_voff[W_IT];
@@ -480,15 +480,17 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rs, (lds_ptr_t)(smem + W_BASE + c * W_BYTES + (it * NT + wave * 64) * 16),
                                                          16, w_voff[it], c * KC * 2, 0, 0);
     }
-    // loads of the first step
+    // loads of the first step (split-K slice s of an item covers chunks s * chunks_per_split ...)
     patch_offsets(cur.mtile);
     {
+        const int cb0 = SPLIT ? cur.split * a.chunks_per_split : 0;
         const __amdgpu_buffer_rsrc_t x_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.x, 0, (int)a.x_bytes, 0x00020000);
 #pragma unroll
         for (int it = 0; it < P_IT; ++it)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rs, (lds_ptr_t)(smem + (it * NT + wave * 64) * 16), 16, p_voff[it], 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rs, (lds_ptr_t)(smem + (it * NT + wave * 64) * 16), 16, p_voff[it],
+                                                     cb0 * KC * 2, 0, 0);
         if constexpr (!STAT) {
-            const int ws = cur.ntile * BN * 9 * a.Cin * 2;
+            const int ws = (cur.ntile * BN * 9 * a.Cin + cb0 * KC) * 2;
 #pragma unroll
             for (int it = 0; it < W_IT; ++it)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rs, (lds_ptr_t)(smem + W_BASE + (it * NT + wave * 64) * 16), 16, w_voff[it], ws, 0, 0);
@@ -537,6 +539,10 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
 
         // the item after this one (its first step is loaded during this item's last step)
         const PatchItem nxt = decode_item(a, item + (int)gridDim.x);
+        // this item's chunks [cb, ce): an even count, so it starts on buffer 0 and ends on buffer 1
+        const int cb = SPLIT ? cur.split * a.chunks_per_split : 0;
+        const int ce = SPLIT ? min(cb + a.chunks_per_split, a.n_chunks) : a.n_chunks;
+        const int nxt_cb = SPLIT ? nxt.split * a.chunks_per_split : 0;
 
         f32x4_t sc0 = {1.f, 1.f, 1.f, 1.f}, sc1 = sc0, sh0 = {0.f, 0.f, 0.f, 0.f}, sh1 = sh0;
         u32x4_t rres[TM][NPASS];
@@ -544,13 +550,13 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
         // One step: MFMAs of chunk `chunk` from buffer BUF; loads of the following step into the other buffer.
         auto step = [&](auto BUFC, int chunk) {
             constexpr int BUF = decltype(BUFC)::value;
-            const bool last = BUF == 1 && chunk == nch - 1;
+            const bool last = BUF == 1 && chunk == ce - 1;
             const bool has1 = !last || nxt.valid;
             if (last && nxt.valid) patch_offsets(nxt.mtile);
             // without a following step the descriptors have size 0: the loads fetch nothing
             const __amdgpu_buffer_rsrc_t x_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.x, 0, has1 ? (int)a.x_bytes : 0, 0x00020000);
             const __amdgpu_buffer_rsrc_t wn_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, has1 ? (int)a.w_bytes : 0, 0x00020000);
-            const int chunk1 = last ? 0 : chunk + 1;
+            const int chunk1 = last ? nxt_cb : chunk + 1;
             const int xs1 = chunk1 * KC * 2;
             const int ws1 = ((last ? nxt.ntile : cur.ntile) * BN * 9 * a.Cin + chunk1 * KC) * 2;
             auto issue_slot = [&](int k) {
@@ -561,7 +567,7 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(wn_rs, (lds_ptr_t)(smem + W_BASE + (BUF ^ 1) * W_BYTES + ((k - P_IT) * NT + wave * 64) * 16),
                                                              16, w_voff[k - P_IT < W_IT && k >= P_IT ? k - P_IT : 0], ws1, 0, 0);
             };
-            if (BUF == 1 && last) {  // epilogue operands, requested now so that they arrive during the MFMAs
+            if (!SPLIT && BUF == 1 && last) {  // epilogue operands, requested now so that they arrive during the MFMAs
                 sc0 = *(const f32x4_t*)(a.scale + nbase); sc1 = *(const f32x4_t*)(a.scale + nbase + 4);
                 sh0 = *(const f32x4_t*)(a.shift + nbase); sh1 = *(const f32x4_t*)(a.shift + nbase + 4);
 #pragma unroll
@@ -577,7 +583,7 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
             }
             // MFMA loop: 18 k-steps, fragments fetched two k-steps ahead, one load slot per k-step
             const unsigned char* pbuf = smem + BUF * P_PITCH;
-            const unsigned char* wbuf = smem + W_BASE + (STAT ? chunk : BUF) * W_BYTES;
+            const unsigned char* wbuf = smem + W_BASE + (STAT ? chunk : BUF) * W_BYTES;  // STAT: two chunks in all
             u32x4_t fa[3][TM], fb[3][TN];
             auto load_frags = [&](int set, int st) {
                 const int tap = st / KS, ks = st % KS;
@@ -606,7 +612,7 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
             __builtin_amdgcn_s_waitcnt(0);
             __syncthreads();
         };
-        for (int chunk = 0; chunk < nch; chunk += 2) {
+        for (int chunk = cb; chunk < ce; chunk += 2) {
             step(std::integral_constant<int, 0>{}, chunk);
             step(std::integral_constant<int, 1>{}, chunk + 1);
         }
@@ -628,6 +634,12 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
                     f32x4_t v1 = *(const f32x4_t*)(scr + rr * SROW + c8 + 4);
                     if (tt < m_lim) {
                         const size_t m = (size_t)g0 * a.W + tt;
+                        if constexpr (SPLIT) {  // fp32 partial sums; scale, shift, residual and ReLU happen in the reduction
+                            float* dst = a.partial + ((size_t)cur.split * a.NH * a.W + m) * a.Cout + nbase;
+                            *(f32x4_t*)dst = v0;
+                            *(f32x4_t*)(dst + 4) = v1;
+                            continue;
+                        }
                         const u32x4_t rv = rres[i][pass];
                         v0 = v0 * sc0 + sh0;
                         v1 = v1 * sc1 + sh1;
@@ -674,7 +686,7 @@ const char* patch_variant_name(int v)
     const PatchVariant& pv = kPatchVariants[tv];
     char* out = buf[next++ & 7];
     if (tv == kPatchDlVariant) {
-        snprintf(out, 96, "conv3x3_patch_dl_kernel<%s>", (v & 16) ? "true" : "false");
+        snprintf(out, 96, "conv3x3_patch_dl_kernel<%s, %s>", (v & 16) ? "true" : "false", (v & 32) ? "true" : "false");
         return out;
     }
     snprintf(out, 96, "conv3x3_patch_kernel<%d, %d, %d, %s, %s, %d>", pv.bm, pv.bn, pv.kc, (v & 16) ? "true" : "false",
@@ -694,7 +706,7 @@ static bool patch_geometry(const sgprs_conv_desc_t& d, int v, int splits, PatchA
     const PatchVariant& pv = kPatchVariants[v];
     if (d.cout % pv.bn || d.cin % pv.kc || d.w > pv.bm) return false;
     // the direct-to-LDS kernel addresses x and w through 31-bit buffer offsets
-    if (v == kPatchDlVariant && (splits != 1 || (long long)d.n * d.h * d.w * d.cin * 2 >= (1ll << 31) ||
+    if (v == kPatchDlVariant && ((long long)d.n * d.h * d.w * d.cin * 2 >= (1ll << 31) ||
                                  (long long)d.cout * 9 * d.cin * 2 >= (1ll << 31)))
         return false;
     const int TR = pv.bm / d.w, NH = d.n * d.h;
@@ -710,6 +722,8 @@ static bool patch_geometry(const sgprs_conv_desc_t& d, int v, int splits, PatchA
     if (splits < 1 || splits > n_chunks) return false;
     const int cps = (n_chunks + splits - 1) / splits;
     if ((splits - 1) * cps >= n_chunks) return false;
+    // the direct-to-LDS kernel alternates two buffers and wants an even number of chunks per item
+    if (v == kPatchDlVariant && (n_chunks % 2 || (splits > 1 && (cps % 2 || n_chunks % cps)))) return false;
     // exactness of the multiply-high divisions: dividend * divisor < 2^32
     const unsigned long long lim = 1ull << 32;
     if ((unsigned long long)(NH + 2 * d.n + 4) * (d.h + 2) >= lim || (unsigned long long)(cap + 256) * (d.w + 2) >= lim) return false;
@@ -729,8 +743,8 @@ void patch_force(int variant, int splits) { g_force_variant = variant; g_force_s
 // Picks the tile variant: the candidate with the smallest estimated time
 // rounds(items / CUs) * (chunks * cost-per-chunk + cost-per-item); the costs (in
 // microseconds, whole-GPU measurements at batch 64) only rank candidates.
-// Split-K is left to the implicit-GEMM path: when a shape offers too few work
-// items to fill the partition this kernel declines.
+// When a shape offers too few work items to fill the partition this kernel
+// declines and the implicit-GEMM path (with its split-K) takes over.
 bool plan_patch(const sgprs_conv_desc_t& d, int cus, int* variant, int* splits)
 {
     if (!patch_eligible(d)) return false;
@@ -747,13 +761,18 @@ bool plan_patch(const sgprs_conv_desc_t& d, int cus, int* variant, int* splits)
     double best = 1e30;
     bool found = false;
     for (const auto& c : cand) {
-        if (!patch_geometry(d, c.v, 1, &a)) continue;
-        const long long items = (long long)a.n_mtiles * a.n_ntiles;
-        if (items * 2 < cus && c.v != kPatchDlVariant) continue;
-        if (items * 3 < cus) continue;
-        const long long rounds = (items + cus - 1) / cus;
-        const double cost = rounds * (a.n_chunks * c.step + c.item);
-        if (cost < best) { best = cost; *variant = c.v; *splits = 1; found = true; }
+        // split-K (fp32 partial sums plus a reduction pass) only for the direct-to-LDS
+        // variant, for shapes with too few work items to occupy the partition
+        for (int sp = 1; sp <= (c.v == kPatchDlVariant ? 2 : 1); ++sp) {
+            if (!patch_geometry(d, c.v, sp, &a)) continue;
+            const long long items = (long long)a.n_mtiles * a.n_ntiles * sp;
+            if (items * 2 < cus && c.v != kPatchDlVariant) continue;
+            if (items * 3 < cus) continue;
+            const long long rounds = (items + cus - 1) / cus;
+            double cost = rounds * (a.chunks_per_split * c.step + c.item);
+            if (sp > 1) cost += 9.0 + (double)d.n * d.h * d.w * d.cout * 4.0 * (sp + 1) / (3.0e6 * cus / 256.0);
+            if (cost < best) { best = cost; *variant = c.v; *splits = sp; found = true; }
+        }
     }
     return found;
 }
@@ -792,16 +811,20 @@ static int launch_patch_dl(const PatchArgs& a, int grid, hipStream_t stream)
     constexpr int kLds = 2 * (512 * 64 + 4096) + 2 * 64 * 9 * 64;
     static bool raised = false;
     if (!raised) {
-        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<true>,
+        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<true, false>,
                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
-        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<false>,
+        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<false, false>,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
+        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<false, true>,
                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
         raised = true;
     }
-    if (a.n_chunks == 2 && a.n_ntiles == 1)
-        SGPRS_LAUNCH(conv3x3_patch_dl_kernel<true>, dim3(grid), dim3(256), kLds, stream, a);
+    if (a.splits > 1)
+        SGPRS_LAUNCH((conv3x3_patch_dl_kernel<false, true>), dim3(grid), dim3(256), kLds, stream, a);
+    else if (a.n_chunks == 2 && a.n_ntiles == 1)
+        SGPRS_LAUNCH((conv3x3_patch_dl_kernel<true, false>), dim3(grid), dim3(256), kLds, stream, a);
     else
-        SGPRS_LAUNCH(conv3x3_patch_dl_kernel<false>, dim3(grid), dim3(256), kLds, stream, a);
+        SGPRS_LAUNCH((conv3x3_patch_dl_kernel<false, false>), dim3(grid), dim3(256), kLds, stream, a);
     SGPRS_HIP(hipGetLastError());
     return SGPRS_OK;
 }
@@ -832,7 +855,7 @@ int launch_conv3x3_patch(const sgprs_conv_desc_t& d, int variant, int splits, co
     const double flops = 2.0 * M * d.cout * 9.0 * d.cin;
     const double bytes = (M * d.cin + (double)d.cout * 9 * d.cin + M * d.cout * (residual ? 2 : 1)) * 2.0;
     int rc;
-    if (prof && prof->on && (rc = prof->begin(stream, kKindPatch, variant + ((variant == kPatchDlVariant ? (a.n_chunks == 2 && a.n_ntiles == 1) : (stat && variant % 4 == 0)) ? 16 : 0) + (splits > 1 ? 32 : 0), flops, bytes))) return rc;
+    if (prof && prof->on && (rc = prof->begin(stream, kKindPatch, variant + ((variant == kPatchDlVariant ? (a.n_chunks == 2 && a.n_ntiles == 1 && a.splits == 1) : (stat && variant % 4 == 0)) ? 16 : 0) + (splits > 1 ? 32 : 0), flops, bytes))) return rc;
     switch (variant) {
         case 0: rc = launch_patch_variant<256, 64, 64>(a, grid, stat, stream); break;
         case 1: rc = launch_patch_variant<256, 128, 32>(a, grid, stat, stream); break;
