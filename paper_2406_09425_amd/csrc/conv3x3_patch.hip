@@ -51,9 +51,14 @@ __device__ __forceinline__ unsigned fdiv(unsigned x, unsigned magic) { return __
 
 // Work-item index -> (split, channel block, row tile).  Workgroup b of a launch
 // runs on die b % 8 and keeps that die for all its items (the grid is a
-// multiple of 8), so with xcd_groups = 8 / n_ntiles every die only ever touches
-// the weights of one channel block: they stay in that die's L2 while the input
-// patches stream through.
+// multiple of 8).  With up to kRowTilePerDieMaxBlocks channel blocks, row tile
+// 8g + die and all its channel blocks run on one die at about the same time:
+// the input rows they share come from HBM once and hit in that die's L2, and
+// the weights of all channel blocks fit there as well (measured 5-7% faster on
+// the 128- and 256-channel layers).  With more channel blocks the weights would
+// not fit, so each die keeps one channel block (xcd_groups = 8 / n_ntiles) and
+// the input patches stream through.
+constexpr int kRowTilePerDieMaxBlocks = 4;
 struct PatchItem { int split, ntile, mtile; bool valid; };
 __device__ __forceinline__ PatchItem decode_item(const PatchArgs& a, int item)
 {
@@ -61,9 +66,15 @@ __device__ __forceinline__ PatchItem decode_item(const PatchArgs& a, int item)
     if (a.xcd_groups > 0) {
         const int x = item & 7, s = item >> 3;
         r.split = 0;
-        r.ntile = x % a.n_ntiles;
-        r.mtile = s * a.xcd_groups + x / a.n_ntiles;
-        r.valid = item < a.n_slots && r.mtile < a.n_mtiles;
+        if (a.n_ntiles <= kRowTilePerDieMaxBlocks) {
+            r.ntile = s % a.n_ntiles;
+            r.mtile = (s / a.n_ntiles) * 8 + x;
+            r.valid = r.mtile < a.n_mtiles;
+        } else {
+            r.ntile = x % a.n_ntiles;
+            r.mtile = s * a.xcd_groups + x / a.n_ntiles;
+            r.valid = item < a.n_slots && r.mtile < a.n_mtiles;
+        }
     } else {
         r.split = item % a.splits;
         const int t2 = item / a.splits;
@@ -733,7 +744,9 @@ static bool patch_geometry(const sgprs_conv_desc_t& d, int v, int splits, PatchA
     a->TR = TR; a->n_mtiles = n_mtiles; a->n_ntiles = d.cout / pv.bn; a->n_chunks = n_chunks;
     a->chunks_per_split = cps; a->splits = splits; a->relu = d.relu;
     a->xcd_groups = (splits == 1 && a->n_ntiles <= 8 && 8 % a->n_ntiles == 0) ? 8 / a->n_ntiles : 0;
-    a->n_slots = a->xcd_groups ? 8 * ((n_mtiles + a->xcd_groups - 1) / a->xcd_groups) : n_mtiles * a->n_ntiles * splits;
+    a->n_slots = !a->xcd_groups ? n_mtiles * a->n_ntiles * splits
+                 : a->n_ntiles <= kRowTilePerDieMaxBlocks ? (n_mtiles + 7) / 8 * 8 * a->n_ntiles
+                                                          : 8 * ((n_mtiles + a->xcd_groups - 1) / a->xcd_groups);
     return true;
 }
 
