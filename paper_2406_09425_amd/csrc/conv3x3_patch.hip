@@ -424,22 +424,26 @@ __global__ __launch_bounds__((NW * 64), (PatchCfg<BM, BN, KC, NW>::WAVES_PER_SIM
 // resident (STAT) and only the patch is double buffered.
 __device__ __forceinline__ unsigned dl_swz(unsigned p) { return ((p >> 3) & 1u) | ((p >> 1) & 2u); }
 
-template <bool STAT, bool SPLIT>
+template <int BM, bool STAT, bool SPLIT>
 __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a)
 {
+#if __HIP_DEVICE_COMPILE__  // the buffer-resource builtins exist in the device pass only; the host needs just the stub
     constexpr int BN = 64, KC = 32, NT = 256;
-    constexpr int PCAP_PIX = 512, P_IT = PCAP_PIX * 4 / NT, W_IT = BN * 9 * 4 / NT;
+    static_assert(BM == 256 || BM == 128, "row-tile heights");
+    constexpr int WMW = BM / 64, WNW = 4 / WMW;  // wavefront grid: 4 x 1 or 2 x 2, each wavefront 64 rows x 64 / WNW channels
+    constexpr int PCAP_PIX = 2 * BM, P_IT = PCAP_PIX * 4 / NT, W_IT = BN * 9 * 4 / NT;
     constexpr int P_BYTES = PCAP_PIX * 64, P_PITCH = P_BYTES + 4096, W_BYTES = BN * 9 * 64;
     constexpr int W_BASE = 2 * P_PITCH;
-    constexpr int TM = 2, TN = 2, KS = KC / 16, NSTEP = 9 * KS;
-    constexpr int WTN = 64, SROW = WTN + 4, RPP = 8, NPASS = 4;
-    static_assert(P_IT == 8 && W_IT == 9 && NSTEP >= P_IT + W_IT, "loader slots");
+    constexpr int WTN = BN / WNW, TM = 2, TN = WTN / 32, KS = KC / 16, NSTEP = 9 * KS;
+    constexpr int SROW = WTN + 4, LPR = WTN / 8, RPP = 64 / LPR, NPASS = 32 / RPP;
+    static_assert(W_IT == 9 && NSTEP >= P_IT + W_IT, "loader slots");
     static_assert(4 * 32 * SROW * 4 <= P_PITCH, "epilogue scratch fits the patch buffer and its pad");
     typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int frow = lane & 31, fhalf = lane >> 5;
+    const int wm = wave / WNW, wn = wave % WNW;
     static_assert(!(STAT && SPLIT), "resident weights are for whole-K items");
 
     // weight loader: 16-byte unit u = it * 256 + tid is slot u % 4 of tap (u / 4) % 9 of row u / 36
@@ -510,24 +514,24 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
-    const int c8 = (lane % 8) * 8, rsub = lane / 8;
+    const int c8 = (lane % LPR) * 8, rsub = lane / LPR;
     // this lane's weight rows: byte offset inside a weight buffer for k-step parity 0 / 1
     unsigned wb[KS];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) wb[ks] = frow * 576 + (((ks * 2 + fhalf) ^ dl_swz(frow)) << 4);
+    for (int ks = 0; ks < KS; ++ks) wb[ks] = (wn * WTN + frow) * 576 + (((ks * 2 + fhalf) ^ dl_swz(frow)) << 4);
 
     for (;;) {
         // ---- this work item
         const int g0 = cur.mtile * a.TR;
         const int rows_here = min(a.TR, a.NH - g0);
         const int m_lim = rows_here * a.W;
-        const int nbase = cur.ntile * BN + c8;
+        const int nbase = cur.ntile * BN + wn * WTN + c8;
         unsigned aoff[TM][9];  // this lane's patch fragment address for every tap (k-step parity 0)
         {
             const int E0 = g0 + 2 * (int)fdiv(g0, a.mH);
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                const int tt = wave * 64 + i * 32 + frow;
+                const int tt = wm * 64 + i * 32 + frow;
                 const int pr = fdiv(tt, a.mW), q = tt - pr * a.W;
                 const bool ok = pr < rows_here;
                 const int g = g0 + (ok ? pr : 0);
@@ -585,7 +589,7 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int pass = 0; pass < NPASS; ++pass) {
-                        const int tt = wave * 64 + i * 32 + pass * RPP + rsub;
+                        const int tt = wm * 64 + i * 32 + pass * RPP + rsub;
                         u32x4_t rv = {0u, 0u, 0u, 0u};
                         if (a.res && tt < m_lim)
                             rv = *(const u32x4_t*)(a.res + (((size_t)g0 * a.W + tt) * a.Cout + nbase) * 2);
@@ -640,7 +644,7 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
 #pragma unroll
                 for (int pass = 0; pass < NPASS; ++pass) {
                     const int rr = pass * RPP + rsub;
-                    const int tt = wave * 64 + i * 32 + rr;
+                    const int tt = wm * 64 + i * 32 + rr;
                     f32x4_t v0 = *(const f32x4_t*)(scr + rr * SROW + c8);
                     f32x4_t v1 = *(const f32x4_t*)(scr + rr * SROW + c8 + 4);
                     if (tt < m_lim) {
@@ -675,16 +679,20 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
         item += gridDim.x;
         cur = nxt;
     }
+#endif
 }
 
 // ---- host side ---------------------------------------------------------------
 static unsigned magic_for(unsigned d) { return (unsigned)((0x100000000ull + d - 1) / d); }
 
 struct PatchVariant { int bm, bn, kc; };
-// tile variants: 0-3 run 4 wavefronts per workgroup, 4-5 run 8 (two per SIMD)
-static const PatchVariant kPatchVariants[] = {{256, 64, 64}, {256, 128, 32}, {128, 64, 64}, {128, 128, 32}, {256, 64, 64}, {256, 128, 32}, {128, 64, 32}, {256, 64, 32}};
-constexpr int kNumPatchVariants = 8;
-constexpr int kPatchDlVariant = 7;  // the direct-to-LDS kernel
+// tile variants: 0-3 run 4 wavefronts per workgroup, 4-5 run 8 (two per SIMD), 6 is small enough
+// for two workgroups per CU, 7-8 are the direct-to-LDS kernel with 256- and 128-row tiles
+static const PatchVariant kPatchVariants[] = {{256, 64, 64}, {256, 128, 32}, {128, 64, 64}, {128, 128, 32}, {256, 64, 64}, {256, 128, 32}, {128, 64, 32}, {256, 64, 32}, {128, 64, 32}};
+constexpr int kNumPatchVariants = 9;
+constexpr int kPatchDlVariant = 7;       // the direct-to-LDS kernel, 256-row tiles
+constexpr int kPatchDlSmallVariant = 8;  // the same with 128-row tiles, for layers with few row tiles
+static bool is_dl(int v) { return v == kPatchDlVariant || v == kPatchDlSmallVariant; }
 int patch_num_variants() { return kNumPatchVariants; }
 
 // Name as a profiler prints it: v = tile variant + 16 * stationary + 32 * split.
@@ -696,8 +704,8 @@ const char* patch_variant_name(int v)
     if (tv >= kNumPatchVariants) return "?";
     const PatchVariant& pv = kPatchVariants[tv];
     char* out = buf[next++ & 7];
-    if (tv == kPatchDlVariant) {
-        snprintf(out, 96, "conv3x3_patch_dl_kernel<%s, %s>", (v & 16) ? "true" : "false", (v & 32) ? "true" : "false");
+    if (is_dl(tv)) {
+        snprintf(out, 96, "conv3x3_patch_dl_kernel<%d, %s, %s>", pv.bm, (v & 16) ? "true" : "false", (v & 32) ? "true" : "false");
         return out;
     }
     snprintf(out, 96, "conv3x3_patch_kernel<%d, %d, %d, %s, %s, %d>", pv.bm, pv.bn, pv.kc, (v & 16) ? "true" : "false",
@@ -717,7 +725,7 @@ static bool patch_geometry(const sgprs_conv_desc_t& d, int v, int splits, PatchA
     const PatchVariant& pv = kPatchVariants[v];
     if (d.cout % pv.bn || d.cin % pv.kc || d.w > pv.bm) return false;
     // the direct-to-LDS kernel addresses x and w through 31-bit buffer offsets
-    if (v == kPatchDlVariant && ((long long)d.n * d.h * d.w * d.cin * 2 >= (1ll << 31) ||
+    if (is_dl(v) && ((long long)d.n * d.h * d.w * d.cin * 2 >= (1ll << 31) ||
                                  (long long)d.cout * 9 * d.cin * 2 >= (1ll << 31)))
         return false;
     const int TR = pv.bm / d.w, NH = d.n * d.h;
@@ -734,7 +742,7 @@ static bool patch_geometry(const sgprs_conv_desc_t& d, int v, int splits, PatchA
     const int cps = (n_chunks + splits - 1) / splits;
     if ((splits - 1) * cps >= n_chunks) return false;
     // the direct-to-LDS kernel alternates two buffers and wants an even number of chunks per item
-    if (v == kPatchDlVariant && (n_chunks % 2 || (splits > 1 && (cps % 2 || n_chunks % cps)))) return false;
+    if (is_dl(v) && (n_chunks % 2 || (splits > 1 && (cps % 2 || n_chunks % cps)))) return false;
     // exactness of the multiply-high divisions: dividend * divisor < 2^32
     const unsigned long long lim = 1ull << 32;
     if ((unsigned long long)(NH + 2 * d.n + 4) * (d.h + 2) >= lim || (unsigned long long)(cap + 256) * (d.w + 2) >= lim) return false;
@@ -770,16 +778,16 @@ bool plan_patch(const sgprs_conv_desc_t& d, int cus, int* variant, int* splits)
     }
     // {variant, microseconds per chunk, microseconds per work item}
     static const struct { int v; double step, item; } cand[] = {
-        {7, 1.65, 5.0}, {4, 5.1, 2.8}, {5, 5.1, 2.8}, {3, 3.1, 2.0}, {2, 4.1, 2.0}};
+        {7, 1.65, 5.0}, {8, 1.0, 4.5}, {4, 5.1, 2.8}, {5, 5.1, 2.8}, {3, 3.1, 2.0}, {2, 4.1, 2.0}};
     double best = 1e30;
     bool found = false;
     for (const auto& c : cand) {
         // split-K (fp32 partial sums plus a reduction pass) only for the direct-to-LDS
         // variant, for shapes with too few work items to occupy the partition
-        for (int sp = 1; sp <= (c.v == kPatchDlVariant ? 2 : 1); ++sp) {
+        for (int sp = 1; sp <= (is_dl(c.v) ? 2 : 1); ++sp) {
             if (!patch_geometry(d, c.v, sp, &a)) continue;
             const long long items = (long long)a.n_mtiles * a.n_ntiles * sp;
-            if (items * 2 < cus && c.v != kPatchDlVariant) continue;
+            if (items * 2 < cus && !is_dl(c.v)) continue;
             if (items * 3 < cus) continue;
             const long long rounds = (items + cus - 1) / cus;
             double cost = rounds * (a.chunks_per_split * c.step + c.item);
@@ -819,25 +827,26 @@ static int launch_patch_variant(const PatchArgs& a, int grid, bool stat, hipStre
     return launch_patch_inst<BM, BN, KC, false, false, NW>(a, grid, stream);
 }
 
+template <int BM>
 static int launch_patch_dl(const PatchArgs& a, int grid, hipStream_t stream)
 {
-    constexpr int kLds = 2 * (512 * 64 + 4096) + 2 * 64 * 9 * 64;
+    constexpr int kLds = 2 * (2 * BM * 64 + 4096) + 2 * 64 * 9 * 64;
     static bool raised = false;
     if (!raised) {
-        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<true, false>,
+        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<BM, true, false>,
                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
-        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<false, false>,
+        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<BM, false, false>,
                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
-        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<false, true>,
+        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<BM, false, true>,
                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
         raised = true;
     }
     if (a.splits > 1)
-        SGPRS_LAUNCH((conv3x3_patch_dl_kernel<false, true>), dim3(grid), dim3(256), kLds, stream, a);
+        SGPRS_LAUNCH((conv3x3_patch_dl_kernel<BM, false, true>), dim3(grid), dim3(256), kLds, stream, a);
     else if (a.n_chunks == 2 && a.n_ntiles == 1)
-        SGPRS_LAUNCH((conv3x3_patch_dl_kernel<true, false>), dim3(grid), dim3(256), kLds, stream, a);
+        SGPRS_LAUNCH((conv3x3_patch_dl_kernel<BM, true, false>), dim3(grid), dim3(256), kLds, stream, a);
     else
-        SGPRS_LAUNCH((conv3x3_patch_dl_kernel<false, false>), dim3(grid), dim3(256), kLds, stream, a);
+        SGPRS_LAUNCH((conv3x3_patch_dl_kernel<BM, false, false>), dim3(grid), dim3(256), kLds, stream, a);
     SGPRS_HIP(hipGetLastError());
     return SGPRS_OK;
 }
@@ -868,7 +877,7 @@ int launch_conv3x3_patch(const sgprs_conv_desc_t& d, int variant, int splits, co
     const double flops = 2.0 * M * d.cout * 9.0 * d.cin;
     const double bytes = (M * d.cin + (double)d.cout * 9 * d.cin + M * d.cout * (residual ? 2 : 1)) * 2.0;
     int rc;
-    if (prof && prof->on && (rc = prof->begin(stream, kKindPatch, variant + ((variant == kPatchDlVariant ? (a.n_chunks == 2 && a.n_ntiles == 1 && a.splits == 1) : (stat && variant % 4 == 0)) ? 16 : 0) + (splits > 1 ? 32 : 0), flops, bytes))) return rc;
+    if (prof && prof->on && (rc = prof->begin(stream, kKindPatch, variant + ((is_dl(variant) ? (a.n_chunks == 2 && a.n_ntiles == 1 && a.splits == 1) : (stat && variant % 4 == 0)) ? 16 : 0) + (splits > 1 ? 32 : 0), flops, bytes))) return rc;
     switch (variant) {
         case 0: rc = launch_patch_variant<256, 64, 64>(a, grid, stat, stream); break;
         case 1: rc = launch_patch_variant<256, 128, 32>(a, grid, stat, stream); break;
@@ -876,7 +885,8 @@ int launch_conv3x3_patch(const sgprs_conv_desc_t& d, int variant, int splits, co
         case 4: rc = launch_patch_variant<256, 64, 64, 8>(a, grid, stat, stream); break;
         case 5: rc = launch_patch_variant<256, 128, 32, 8>(a, grid, stat, stream); break;
         case 6: rc = launch_patch_variant<128, 64, 32>(a, grid, stat, stream); break;
-        case kPatchDlVariant: rc = launch_patch_dl(a, grid, stream); break;
+        case kPatchDlVariant: rc = launch_patch_dl<256>(a, grid, stream); break;
+        case kPatchDlSmallVariant: rc = launch_patch_dl<128>(a, grid, stream); break;
         default: rc = launch_patch_variant<128, 128, 32>(a, grid, stat, stream); break;
     }
     if (rc) return rc;
