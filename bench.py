@@ -151,21 +151,16 @@ def main():
                 ps = per_stage[j]
                 ps["ms"] += r["ms"]; ps["flops"] += r["flops"]; ps["bytes"] += r["bytes"]
                 ps["roof_s"] += max(r["flops"] / PEAK_BF16, r["bytes"] / PEAK_HBM)
-    # Per-kernel intervals are taken between completion events attached to
-    # consecutive dispatches; attaching an event to every dispatch delays the
-    # next one by a few microseconds.  That constant is measured here, live, as
-    # (sum of per-kernel intervals - duration of an unprofiled step) / launches,
-    # and taken out of every interval.
+    # Per-kernel times are start..stop of each dispatch (both events ride on the
+    # kernel's own packet), i.e. the kernel alone, as a profiler's kernel trace
+    # reports it.  Gaps between kernels are not in them; what the unprofiled
+    # step spends outside kernels is reported as gap_us_per_step.
     launches = sum(v[3] for v in agg.values()) / prof_steps
     sum_prof_us = sum(v[0] for v in agg.values()) / prof_steps * 1e6
-    ev_over_us = max(0.0, (sum_prof_us - ev_ms / args.steps * 1e3) / launches)
-
-    def corr(t_s, cnt):
-        return max(t_s - cnt * ev_over_us * 1e-6, 0.25 * t_s)
+    gap_us = ev_ms / args.steps * 1e3 - sum_prof_us
 
     for j, ps in enumerate(per_stage):
-        nk = len(task.kernel_times(j))
-        t_s = max(ps["ms"] * 1e-3 / prof_steps - nk * ev_over_us * 1e-6, 1e-7)
+        t_s = max(ps["ms"] * 1e-3 / prof_steps, 1e-7)
         stages.append(dict(stage=j, ms=round(t_s * 1e3, 4),
                            images_per_s=round(n / t_s, 1),
                            tflops=round(ps["flops"] / prof_steps / t_s / 1e12, 2),
@@ -174,13 +169,10 @@ def main():
                            roofline_frac=round(ps["roof_s"] / prof_steps / t_s, 4)))
     kernels = []
     for (name, kind), (t_s, fl, by, cnt) in sorted(agg.items(), key=lambda kv: -kv[1][0]):
-        tc = corr(t_s, cnt)
-        kernels.append(dict(kernel=name, launches_per_step=cnt // prof_steps, avg_us=round(tc / cnt * 1e6, 2),
-                            avg_us_raw=round(t_s / cnt * 1e6, 2),
-                            tflops=round(fl / tc / 1e12, 2), gb_per_s=round(by / tc / 1e9, 1)))
-    dom_key = max((k for k in agg if k[1] in (0, 8)), key=lambda k: agg[k][0])
+        kernels.append(dict(kernel=name, launches_per_step=cnt // prof_steps, avg_us=round(t_s / cnt * 1e6, 2),
+                            tflops=round(fl / t_s / 1e12, 2), gb_per_s=round(by / t_s / 1e9, 1)))
+    dom_key = max((k for k in agg if k[1] in (0, 8, 10)), key=lambda k: agg[k][0])
     dt_s, dfl, dby, dcnt = agg[dom_key]
-    dtc = corr(dt_s, dcnt)
     traffic = None
     tr_file = os.path.join(ROOT, "profiles", "resnet18_b64_bf16_hbm_traffic.txt")
     if n == 64 and os.path.exists(tr_file):  # measured once with rocprofv3 --pmc, see profiles/
@@ -188,12 +180,13 @@ def main():
             if dom_key[0] in line:
                 f = line.split()
                 traffic = round((float(f[-2]) + float(f[-1])) * 1e6)
-    roofline = dict(bound="mfma", kernel=dom_key[0], achieved=round(dfl / dtc / 1e12, 2), peak=PEAK_BF16 / 1e12,
-                    unit="TFLOP/s", frac=round(dfl / dtc / PEAK_BF16, 4), traffic=traffic,
-                    avg_launch_us=round(dtc / dcnt * 1e6, 2), avg_launch_us_raw=round(dt_s / dcnt * 1e6, 2),
-                    event_overhead_us=round(ev_over_us, 2), launches_per_step=dcnt // prof_steps,
-                    flop_per_launch=round(dfl / dcnt, 1), algorithmic_bytes_per_launch=round(dby / dcnt, 1))
-    conv_t = sum(corr(v[0], v[3]) for k, v in agg.items() if k[1] in (0, 1, 2, 8, 9, 10))
+    roofline = dict(bound="mfma", kernel=dom_key[0], achieved=round(dfl / dt_s / 1e12, 2), peak=PEAK_BF16 / 1e12,
+                    unit="TFLOP/s", frac=round(dfl / dt_s / PEAK_BF16, 4), traffic=traffic,
+                    avg_launch_us=round(dt_s / dcnt * 1e6, 2), launches_per_step=dcnt // prof_steps,
+                    flop_per_launch=round(dfl / dcnt, 1), algorithmic_bytes_per_launch=round(dby / dcnt, 1),
+                    kernel_us_per_step=round(sum_prof_us, 1), gap_us_per_step=round(gap_us, 1),
+                    launches_all_kernels=round(launches))
+    conv_t = sum(v[0] for k, v in agg.items() if k[1] in (0, 1, 2, 8, 9, 10))
     conv_fl = sum(v[1] for k, v in agg.items() if k[1] in (0, 1, 8, 9, 10))
     conv_all = dict(tflops=round(conv_fl / conv_t / 1e12, 2), mfma_frac=round(conv_fl / conv_t / PEAK_BF16, 4),
                     us_per_step=round(conv_t / prof_steps * 1e6, 1))
@@ -237,6 +230,7 @@ def main():
         out["cu_sweep"] = leg_sweep(S, hip, torch, total_cus, nhwc, with_cpu=not args.no_cpu)
         out["multi_tenant"] = leg_multi_tenant(S, hip, torch, total_cus, nhwc)
         out["memory_bound_ops"] = leg_membound(S, hip, torch, pool, stream)
+        out["oversubscribed_pool"] = leg_oversubscribed(S, torch, total_cus, nhwc, headline_ips=value)
     pool.destroy()
     print(json.dumps(out), flush=True)
 
@@ -423,6 +417,44 @@ def leg_membound(S, hip, torch, pool, stream, reps=20):
           lambda: (torch.randn(cnt, device="cuda").to(tdt), torch.randn(cnt, device="cuda").to(tdt), torch.empty(cnt, dtype=tdt, device="cuda")),
           lambda b: S.sgprs_add_relu(dt, cnt, b[0].data_ptr(), b[1].data_ptr(), b[2].data_ptr(), True, pool, 0))
     return res
+
+
+def leg_oversubscribed(S, torch, total_cus, nhwc, headline_ips, rounds=30):
+    """Two batch-64 bf16 instances on a pool of two partitions that BOTH span all
+    CUs (an over-subscribed context pool): the tails, prologues and idle CUs of
+    one instance's kernels are filled by the other's workgroups."""
+    import numpy as np
+    from workloads import BN_EPS, make_input, make_resnet18_params
+    n, n_p = 64, 2
+    words = S.Pool(1, total_cus).mask(0)
+    pool = S.Pool(n_p, 0, masks=np.stack([words] * n_p))
+    tasks, xs, lgs = [], [], []
+    for i in range(n_p):
+        tasks.append(S.Task(make_resnet18_params(4, 0, bf16=True), S.SGPRS_BF16, n, BN_EPS))
+        xs.append(nhwc(make_input(4, i, (n, 3, 224, 224), bf16=True), torch.bfloat16))
+        lgs.append(torch.empty((n, 1000), dtype=torch.float32, device="cuda"))
+
+    def issue_all():
+        for j in range(6):
+            for i in range(n_p):
+                src = xs[i].data_ptr() if j == 0 else tasks[i].stage_output(j - 1)
+                dst = lgs[i].data_ptr() if j == 5 else tasks[i].stage_output(j)
+                tasks[i].stage_run(j, n, src, dst, pool, i)
+
+    for _ in range(5):
+        issue_all()
+    pool.sync()
+    t0 = time.perf_counter()
+    for _ in range(rounds):
+        issue_all()
+    pool.sync()
+    dt = (time.perf_counter() - t0) / rounds
+    ips = n_p * n / dt
+    for t in tasks:
+        t.destroy()
+    pool.destroy()
+    return dict(instances=n_p, batch=n, partitions="2 x all CUs", ms_per_round=round(dt * 1e3, 4),
+                aggregate_images_per_s=round(ips, 1), vs_single_partition=round(ips / headline_ips, 3))
 
 
 def leg_multi_tenant(S, hip, torch, total_cus, nhwc, n_p=8, rounds=30):

@@ -15,22 +15,23 @@ int Profiler::begin(hipStream_t s, int kind, int variant, double flops, double b
 {
     while (event_pool.size() < next_event + 2) {
         hipEvent_t e;
-        SGPRS_HIP(hipEventCreate(&e));
+        // no system-scope release at the event: a full L2 write-back between kernels would slow down
+        // the memory-heavy ones and the profile would not show the kernels as they run unprofiled
+        SGPRS_HIP(hipEventCreateWithFlags(&e, hipEventDisableSystemFence));
         event_pool.push_back(e);
     }
+    // Both events ride on the kernel's own dispatch packet (hipExtLaunchKernelGGL):
+    // start..stop is the kernel alone, as a profiler's kernel trace reports it,
+    // without the gap to the previous kernel.
     KernelRecord r;
     r.kind = kind; r.variant = variant; r.flops = flops; r.bytes = bytes;
+    r.start = event_pool[next_event++];
     r.stop = event_pool[next_event++];
-    if (prev) {
-        r.start = prev;
-    } else {
-        r.start = event_pool[next_event++];
-        SGPRS_HIP(hipEventRecord(r.start, s));
-    }
     recs.push_back(r);
-    tl_start = nullptr;
+    tl_start = r.start;
     tl_stop = r.stop;
     prev = r.stop;
+    (void)s;
     return SGPRS_OK;
 }
 
