@@ -160,7 +160,7 @@ int sgprs_conv2d(const sgprs_conv_desc_t *d, const void *x, const void *w_packed
  * automatic (default); 0: implicit GEMM only; 1: the LDS-patch kernel with the
  * given tile variant (0..8) and split factor where the shape allows it; 2:
  * automatic, but implicit-GEMM launches use tile variant `variant` (0..3)
- * wherever it divides cout. */
+ * wherever it divides cout, with split-K factor `splits` (0: planner's choice). */
 int sgprs_conv_tuning_override(int kind, int variant, int splits);
 /* Max pooling 3x3, stride 2, pad 1 (padding never wins): [n][h][w][c] ->
  * [n][(h-1)/2+1][(w-1)/2+1][c].  c % 8 == 0 (bf16) or c % 4 == 0 (fp32). */

@@ -453,6 +453,29 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
         const unsigned u = it * NT + tid, row = u / 36, rem = u % 36;
         w_voff[it] = ((row * 9 + rem / 4) * (unsigned)a.Cin + (((rem & 3) ^ dl_swz(row)) * 8)) * 2u;
     }
+    // Work items blockIdx.x + k * gridDim.x; an item is n_chunks steps (n_chunks is
+    // even, so every item starts on buffer 0 and ends on buffer 1).
+    int item = blockIdx.x;
+    PatchItem cur = decode_item(a, item);
+    if (!cur.valid) return;
+
+    const __amdgpu_buffer_rsrc_t w_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, (int)a.w_bytes, 0x00020000);
+    if constexpr (STAT) {  // both weight chunks resident
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int it = 0; it < W_IT; ++it)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rs, (lds_ptr_t)(smem + W_BASE + c * W_BYTES + (it * NT + wave * 64) * 16),
+                                                         16, w_voff[it], c * KC * 2, 0, 0);
+    }
+    const int cb0 = SPLIT ? cur.split * a.chunks_per_split : 0;  // split-K slice s of an item covers chunks s * chunks_per_split ...
+    if constexpr (!STAT) {  // first step's weights: requested before the patch tables are worked out
+        const int ws = (cur.ntile * BN * 9 * a.Cin + cb0 * KC) * 2;
+#pragma unroll
+        for (int it = 0; it < W_IT; ++it)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rs, (lds_ptr_t)(smem + W_BASE + (it * NT + wave * 64) * 16), 16, w_voff[it], ws, 0, 0);
+    }
+
     // patch loader: unit u is slot u % 4 of patch pixel u / 4
     int p_row[P_IT], p_col[P_IT];
     unsigned p_grp[P_IT];
@@ -480,39 +503,16 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
         }
     };
 
-    // Work items blockIdx.x + k * gridDim.x; an item is n_chunks steps (n_chunks is
-    // even, so every item starts on buffer 0 and ends on buffer 1).
-    int item = blockIdx.x;
-    PatchItem cur = decode_item(a, item);
-    if (!cur.valid) return;
-
-    const __amdgpu_buffer_rsrc_t w_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, (int)a.w_bytes, 0x00020000);
-    if constexpr (STAT) {  // both weight chunks resident
-#pragma unroll
-        for (int c = 0; c < 2; ++c)
-#pragma unroll
-            for (int it = 0; it < W_IT; ++it)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rs, (lds_ptr_t)(smem + W_BASE + c * W_BYTES + (it * NT + wave * 64) * 16),
-                                                         16, w_voff[it], c * KC * 2, 0, 0);
-    }
-    // loads of the first step (split-K slice s of an item covers chunks s * chunks_per_split ...)
+    // first step's patch
     patch_offsets(cur.mtile);
     {
-        const int cb0 = SPLIT ? cur.split * a.chunks_per_split : 0;
         const __amdgpu_buffer_rsrc_t x_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.x, 0, (int)a.x_bytes, 0x00020000);
 #pragma unroll
         for (int it = 0; it < P_IT; ++it)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rs, (lds_ptr_t)(smem + (it * NT + wave * 64) * 16), 16, p_voff[it],
                                                      cb0 * KC * 2, 0, 0);
-        if constexpr (!STAT) {
-            const int ws = (cur.ntile * BN * 9 * a.Cin + cb0 * KC) * 2;
-#pragma unroll
-            for (int it = 0; it < W_IT; ++it)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rs, (lds_ptr_t)(smem + W_BASE + (it * NT + wave * 64) * 16), 16, w_voff[it], ws, 0, 0);
-        }
     }
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
+    // (they land while the first item's addresses are set up; the wait is inside the item loop)
 
     const int c8 = (lane % LPR) * 8, rsub = lane / LPR;
     // this lane's weight rows: byte offset inside a weight buffer for k-step parity 0 / 1
@@ -520,6 +520,7 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) wb[ks] = (wn * WTN + frow) * 576 + (((ks * 2 + fhalf) ^ dl_swz(frow)) << 4);
 
+    bool first_item = true;
     for (;;) {
         // ---- this work item
         const int g0 = cur.mtile * a.TR;
@@ -561,6 +562,12 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
 
         f32x4_t sc0 = {1.f, 1.f, 1.f, 1.f}, sc1 = sc0, sh0 = {0.f, 0.f, 0.f, 0.f}, sh1 = sh0;
         u32x4_t rres[TM][NPASS];
+
+        if (first_item) {  // the first step's data: every later step is awaited at the end of the step before it
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+            first_item = false;
+        }
 
         // One step: MFMAs of chunk `chunk` from buffer BUF; loads of the following step into the other buffer.
         auto step = [&](auto BUFC, int chunk) {

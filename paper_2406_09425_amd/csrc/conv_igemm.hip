@@ -425,30 +425,30 @@ static int launch_pair_dtype(const IgemmArgs& a0, const ConvPlan& p0, const Igem
     }
 }
 
-// Name as a profiler prints it: v = tile variant + 4 * dtype.
+static const int kIgemmShape[4][4] = {{128, 128, 2, 2}, {128, 64, 2, 2}, {64, 64, 2, 2}, {32, 128, 1, 4}};
+
+// Name as a profiler prints it: v = tile variant + 8 * dtype.
 const char* igemm_pair_variant_name(int v)
 {
-    static const int shape[4][4] = {{128, 128, 2, 2}, {128, 64, 2, 2}, {64, 64, 2, 2}, {32, 128, 1, 4}};
     static char buf[8][96];
     static int next = 0;
-    if (v < 0 || v >= 8) return "?";
-    const int* t = shape[v & 3];
+    if (v < 0 || v >= 16 || (v & 7) >= 4) return "?";
+    const int* t = kIgemmShape[v & 7];
     char* out = buf[next++ & 7];
-    snprintf(out, 96, "conv_igemm_pair_kernel<%d, %d, %d, %d, %d>", (v >> 2) & 1, t[0], t[1], t[2], t[3]);
+    snprintf(out, 96, "conv_igemm_pair_kernel<%d, %d, %d, %d, %d>", (v >> 3) & 1, t[0], t[1], t[2], t[3]);
     return out;
 }
 
-// Name as a profiler prints it: v = tile variant + 4 * dtype + 8 * split.
+// Name as a profiler prints it: v = tile variant + 8 * dtype + 16 * split.
 const char* igemm_variant_name(int v)
 {
-    static const int shape[4][4] = {{128, 128, 2, 2}, {128, 64, 2, 2}, {64, 64, 2, 2}, {32, 128, 1, 4}};
     static char buf[8][96];
     static int next = 0;
-    if (v < 0 || v >= 16) return "?";
-    const int* t = shape[v & 3];
+    if (v < 0 || v >= 32 || (v & 7) >= 4) return "?";
+    const int* t = kIgemmShape[v & 7];
     char* out = buf[next++ & 7];
-    snprintf(out, 96, "conv_igemm_kernel<%d, %d, %d, %d, %d, %s>", (v >> 2) & 1, t[0], t[1], t[2], t[3],
-             (v & 8) ? "true" : "false");
+    snprintf(out, 96, "conv_igemm_kernel<%d, %d, %d, %d, %d, %s>", (v >> 3) & 1, t[0], t[1], t[2], t[3],
+             (v & 16) ? "true" : "false");
     return out;
 }
 
@@ -516,7 +516,7 @@ int launch_conv_pair(const sgprs_conv_desc_t& d0, const void* w0, const float* s
     const double bytes = ((double)d0.n * d0.h * d0.w * d0.cin + (double)d0.cout * d0.r * d0.s * d0.cin +
                           (double)d1.cout * d1.r * d1.s * d1.cin + (double)a0.M * d0.cout + (double)a1.M * d1.cout) * es;
     int rc;
-    if (prof && prof->on && (rc = prof->begin(stream, kKindIgemmPair, d0.dtype * 4 + p0.variant, flops, bytes))) return rc;
+    if (prof && prof->on && (rc = prof->begin(stream, kKindIgemmPair, d0.dtype * 8 + p0.variant, flops, bytes))) return rc;
     rc = d0.dtype == SGPRS_BF16 ? launch_pair_dtype<SGPRS_BF16>(a0, p0, a1, p1, stream)
                                 : launch_pair_dtype<SGPRS_F32>(a0, p0, a1, p1, stream);
     if (rc) return rc;
@@ -545,7 +545,7 @@ int launch_conv(const sgprs_conv_desc_t& d, const void* x, const void* w, const 
     const double bytes = ((double)d.n * d.h * d.w * d.cin + (double)d.cout * d.r * d.s * d.cin +
                           (double)a.M * d.cout * (residual ? 2 : 1)) * es;
     int rc;
-    if (prof && prof->on && (rc = prof->begin(stream, kKindIgemm, d.dtype * 4 + p.variant + (p.splits > 1 ? 8 : 0), flops, bytes))) return rc;
+    if (prof && prof->on && (rc = prof->begin(stream, kKindIgemm, d.dtype * 8 + p.variant + (p.splits > 1 ? 16 : 0), flops, bytes))) return rc;
     rc = d.dtype == SGPRS_BF16 ? launch_dtype<SGPRS_BF16>(a, p, stream) : launch_dtype<SGPRS_F32>(a, p, stream);
     if (rc) return rc;
     if (prof && prof->on && (rc = prof->end(stream))) return rc;

@@ -162,7 +162,7 @@ int launch_splitk_reduce(int dtype, const float* partial, int splits, size_t tot
                          const float* shift, const void* res, void* y, int relu, hipStream_t stream);
 // tuning override: kind -1 automatic, 0 implicit GEMM only, 1 force patch (variant, splits)
 extern int g_conv_force_kind;
-extern int g_igemm_force_variant;
+extern int g_igemm_force_variant, g_igemm_force_splits;
 
 const char* igemm_variant_name(int v);
 const char* igemm_pair_variant_name(int v);

@@ -76,6 +76,7 @@ int sgprs_conv_tuning_override(int kind, int variant, int splits)
     if (kind < -1 || kind > 2) return fail(SGPRS_ERR_INVALID_ARG, "kind %d outside [-1,2]", kind);
     g_conv_force_kind = kind == 2 ? -1 : kind;
     g_igemm_force_variant = kind == 2 ? variant : -1;
+    g_igemm_force_splits = kind == 2 ? splits : 0;
     patch_force(kind == 1 ? variant : -1, splits);
     return SGPRS_OK;
 }

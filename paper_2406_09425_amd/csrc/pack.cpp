@@ -54,6 +54,7 @@ int igemm_num_variants() { return (int)(sizeof(kTiles) / sizeof(kTiles[0])); }
 
 int g_conv_force_kind = -1;
 int g_igemm_force_variant = -1;
+int g_igemm_force_splits = 0;
 
 ConvPlan plan_conv(const sgprs_conv_desc_t& d, int cus)
 {
@@ -85,6 +86,7 @@ ConvPlan plan_conv(const sgprs_conv_desc_t& d, int cus)
         const long long blocks = gm * gn;
         const int occ = 2;  // workgroups resident per CU
         for (int s = 1; s <= 32; s *= 2) {
+            if (g_igemm_force_variant >= 0 && g_igemm_force_splits > 0 && s != g_igemm_force_splits) continue;
             if (s > 1 && ktiles / s < 2) break;
             const int kt_per = (ktiles + s - 1) / s;
             if (s > 1 && (long long)(s - 1) * kt_per >= ktiles) continue;  // an empty split
