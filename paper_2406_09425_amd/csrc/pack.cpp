@@ -86,8 +86,12 @@ ConvPlan plan_conv(const sgprs_conv_desc_t& d, int cus)
         const long long blocks = gm * gn;
         const int occ = 2;  // workgroups resident per CU
         for (int s = 1; s <= 32; s *= 2) {
-            if (g_igemm_force_variant >= 0 && g_igemm_force_splits > 0 && s != g_igemm_force_splits) continue;
             if (s > 1 && ktiles / s < 2) break;
+            // a forced split factor applies where the shape allows it (else the planner's own choice stands)
+            if (g_igemm_force_variant >= 0 && g_igemm_force_splits > 1 && s != g_igemm_force_splits &&
+                ktiles / g_igemm_force_splits >= 2)
+                continue;
+            if (g_igemm_force_variant >= 0 && g_igemm_force_splits == 1 && s != 1) continue;
             const int kt_per = (ktiles + s - 1) / s;
             if (s > 1 && (long long)(s - 1) * kt_per >= ktiles) continue;  // an empty split
             const double per_block =

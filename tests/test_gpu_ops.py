@@ -254,3 +254,21 @@ def test_conv_planner_choices_agree(pools):
     finally:
         S.sgprs_conv_tuning_override(-1, 0, 1)
     assert rel_err(outs[0], outs[1]) < 1e-2 and rel_err(outs[2], outs[1]) < 1e-2
+
+
+@pytest.mark.parametrize("dtype", [S.SGPRS_F32, S.SGPRS_BF16], ids=["f32", "bf16"])
+def test_igemm_forced_tiles_and_splits_parity(pools, dtype):
+    """Every implicit-GEMM tile shape, with the planner's split factor and with
+    forced ones, on a stride-2 3x3 and a 1x1 layer (ragged last row tile)."""
+    pool = pools["full"]
+    shapes = [(3, 14, 14, 64, 128, 3, 2, 1), (3, 14, 14, 64, 128, 1, 2, 0)]
+    try:
+        for variant in range(4):
+            for splits in (0, 1, 2):
+                for shape in shapes:
+                    S.sgprs_conv_tuning_override(2, variant, splits)
+                    got, ref = conv_case(dtype, *shape, relu=True, with_res=True, seed=70 + variant, pool=pool,
+                                         cus=pool.partition_cus(0))
+                    assert_close(got, ref, dtype, f"igemm variant {variant} splits {splits} {shape}")
+    finally:
+        S.sgprs_conv_tuning_override(-1, 0, 1)
