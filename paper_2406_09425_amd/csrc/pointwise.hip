@@ -26,6 +26,17 @@ template <> struct Vec<SGPRS_F32> {
         f32x4_t t = {v[0], v[1], v[2], v[3]};
         ((f32x4_t*)p)[vec_index] = t;
     }
+    // streaming forms for data touched once: they do not displace reusable lines from L2
+    __device__ __forceinline__ void load_nt(const void* p, size_t vec_index)
+    {
+        const f32x4_t t = __builtin_nontemporal_load((const f32x4_t*)p + vec_index);
+        v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
+    }
+    __device__ __forceinline__ void store_nt(void* p, size_t vec_index) const
+    {
+        f32x4_t t = {v[0], v[1], v[2], v[3]};
+        __builtin_nontemporal_store(t, (f32x4_t*)p + vec_index);
+    }
 };
 template <> struct Vec<SGPRS_BF16> {
     static constexpr int N = 8;
@@ -49,6 +60,26 @@ template <> struct Vec<SGPRS_BF16> {
                    ((unsigned)__builtin_bit_cast(unsigned short, hi) << 16);
         }
         ((u32x4_t*)p)[vec_index] = t;
+    }
+    __device__ __forceinline__ void load_nt(const void* p, size_t vec_index)
+    {
+        const u32x4_t t = __builtin_nontemporal_load((const u32x4_t*)p + vec_index);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(t[i] << 16);
+            v[2 * i + 1] = __uint_as_float(t[i] & 0xffff0000u);
+        }
+    }
+    __device__ __forceinline__ void store_nt(void* p, size_t vec_index) const
+    {
+        u32x4_t t;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const __bf16 lo = (__bf16)v[2 * i], hi = (__bf16)v[2 * i + 1];  // nearest even
+            t[i] = (unsigned)__builtin_bit_cast(unsigned short, lo) |
+                   ((unsigned)__builtin_bit_cast(unsigned short, hi) << 16);
+        }
+        __builtin_nontemporal_store(t, (u32x4_t*)p + vec_index);
     }
 };
 
@@ -107,8 +138,8 @@ __global__ __launch_bounds__(256) void maxpool3x3s2_kernel(const void* __restric
             if (r >= 2) m1.v[i] = fmaxf(m1.v[i], rm);
         }
     }
-    m0.store(y, ((size_t)(n * P + p0) * Q + q) * cv + c);
-    if (p0 + 1 < P) m1.store(y, ((size_t)(n * P + p0 + 1) * Q + q) * cv + c);
+    m0.store_nt(y, ((size_t)(n * P + p0) * Q + q) * cv + c);
+    if (p0 + 1 < P) m1.store_nt(y, ((size_t)(n * P + p0 + 1) * Q + q) * cv + c);
 }
 
 // ---- y = max(0, scale*x + shift) -------------------------------------------
@@ -124,10 +155,10 @@ __global__ __launch_bounds__(256) void bn_relu_kernel(const void* __restrict__ x
     const unsigned cv = C / N;
     const int c0 = (int)((((unsigned)(blockIdx.x % cv) * (256u % cv)) + threadIdx.x) % cv) * N;
     Vec<DT> t;
-    t.load(x, idx);
+    t.load_nt(x, idx);
 #pragma unroll
     for (int i = 0; i < N; ++i) t.v[i] = fmaxf(t.v[i] * scale[c0 + i] + shift[c0 + i], 0.f);
-    t.store(y, idx);
+    t.store_nt(y, idx);
 }
 
 // ---- y = a + b (ReLU optional) ---------------------------------------------
@@ -139,14 +170,14 @@ __global__ __launch_bounds__(256) void add_relu_kernel(const void* __restrict__ 
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= total_vec) return;
     Vec<DT> s, t;
-    s.load(a, idx);
-    t.load(b, idx);
+    s.load_nt(a, idx);
+    t.load_nt(b, idx);
 #pragma unroll
     for (int i = 0; i < N; ++i) {
         s.v[i] += t.v[i];
         if (relu) s.v[i] = fmaxf(s.v[i], 0.f);
     }
-    s.store(y, idx);
+    s.store_nt(y, idx);
 }
 
 // ---- global average pool: x [n][hw][c] -> v [n][c] fp32 ---------------------
