@@ -423,21 +423,31 @@ __global__ __launch_bounds__((NW * 64), (PatchCfg<BM, BN, KC, NW>::WAVES_PER_SIM
 // With two chunks and one channel block (64 -> 64 layers) all weights stay
 // resident (STAT) and only the patch is double buffered.
 __device__ __forceinline__ unsigned dl_swz(unsigned p) { return ((p >> 3) & 1u) | ((p >> 1) & 2u); }
+// The same with 16-channel chunks (32-byte pixels, two slots): slot s holds group s ^ ((p >> 3) & 1),
+// conflict-free for 16 consecutive pixels of one group and for 8 pixels x both groups.
+template <int SL> __device__ __forceinline__ unsigned dl_swz_sl(unsigned p) { return SL == 4 ? dl_swz(p) : (p >> 3) & 1u; }
 
-template <int BM, bool STAT, bool SPLIT>
-__global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a)
+template <int BM, int KC, bool STAT, bool SPLIT>
+__global__ __launch_bounds__(256, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_kernel(const PatchArgs a)
 {
 #if __HIP_DEVICE_COMPILE__  // the buffer-resource builtins exist in the device pass only; the host needs just the stub
-    constexpr int BN = 64, KC = 32, NT = 256;
-    static_assert(BM == 256 || BM == 128, "row-tile heights");
+    constexpr int BN = 64, NT = 256;
+    static_assert((BM == 256 || BM == 128) && (KC == 32 || KC == 16) && !(KC == 16 && (STAT || BM != 256)), "tile shapes");
+    constexpr int PB = KC * 2, SL = PB / 16;     // bytes and 16-byte slots per pixel of one chunk
     constexpr int WMW = BM / 64, WNW = 4 / WMW;  // wavefront grid: 4 x 1 or 2 x 2, each wavefront 64 rows x 64 / WNW channels
-    constexpr int PCAP_PIX = 2 * BM, P_IT = PCAP_PIX * 4 / NT, W_IT = BN * 9 * 4 / NT;
-    constexpr int P_BYTES = PCAP_PIX * 64, P_PITCH = P_BYTES + 4096, W_BYTES = BN * 9 * 64;
-    constexpr int W_BASE = 2 * P_PITCH;
+    constexpr int PCAP_PIX = 2 * BM, P_IT = PCAP_PIX * SL / NT;
+    constexpr int W_UNITS = BN * 9 * SL, W_IT = (W_UNITS + NT - 1) / NT;  // the last weight slot may cover only some wavefronts
+    constexpr int P_BYTES = PCAP_PIX * PB, W_BYTES = BN * 9 * PB, WROW = 9 * PB;
+    // LDS map.  32-channel chunks: [patch 0][pad][patch 1][pad][weights 0][weights 1] (the patch
+    // fragment reads keep 16-bit immediate offsets; the pad lets the epilogue scratch overhang
+    // the patch area).  16-channel chunks: [patch 0][weights 0][patch 1][weights 1], one stage
+    // being exactly the size of the epilogue scratch, so that two workgroups fit one CU.
+    constexpr int P_PITCH = KC == 32 ? P_BYTES + 4096 : P_BYTES + W_BYTES;
+    constexpr int W_BASE = KC == 32 ? 2 * P_PITCH : P_BYTES, W_PITCH = KC == 32 ? W_BYTES : P_PITCH;
     constexpr int WTN = BN / WNW, TM = 2, TN = WTN / 32, KS = KC / 16, NSTEP = 9 * KS;
     constexpr int SROW = WTN + 4, LPR = WTN / 8, RPP = 64 / LPR, NPASS = 32 / RPP;
-    static_assert(W_IT == 9 && NSTEP >= P_IT + W_IT, "loader slots");
-    static_assert(4 * 32 * SROW * 4 <= P_PITCH, "epilogue scratch fits the patch buffer and its pad");
+    static_assert(NSTEP >= P_IT + W_IT, "loader slots");
+    static_assert(4 * 32 * SROW * 4 <= P_PITCH, "epilogue scratch fits the patch buffer and what follows it");
     typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
     extern __shared__ __align__(16) unsigned char smem[];
@@ -446,12 +456,12 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
     const int wm = wave / WNW, wn = wave % WNW;
     static_assert(!(STAT && SPLIT), "resident weights are for whole-K items");
 
-    // weight loader: 16-byte unit u = it * 256 + tid is slot u % 4 of tap (u / 4) % 9 of row u / 36
+    // weight loader: 16-byte unit u = it * 256 + tid is slot u % SL of tap (u / SL) % 9 of row u / (9 * SL)
     unsigned w_voff[W_IT];
 #pragma unroll
     for (int it = 0; it < W_IT; ++it) {
-        const unsigned u = it * NT + tid, row = u / 36, rem = u % 36;
-        w_voff[it] = ((row * 9 + rem / 4) * (unsigned)a.Cin + (((rem & 3) ^ dl_swz(row)) * 8)) * 2u;
+        const unsigned u = it * NT + tid, row = u / (9 * SL), rem = u % (9 * SL);
+        w_voff[it] = ((row * 9 + rem / SL) * (unsigned)a.Cin + (((rem % SL) ^ dl_swz_sl<SL>(row)) * 8)) * 2u;
     }
     // Work items blockIdx.x + k * gridDim.x; an item is n_chunks steps (n_chunks is
     // even, so every item starts on buffer 0 and ends on buffer 1).
@@ -465,7 +475,7 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
         for (int c = 0; c < 2; ++c)
 #pragma unroll
             for (int it = 0; it < W_IT; ++it)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rs, (lds_ptr_t)(smem + W_BASE + c * W_BYTES + (it * NT + wave * 64) * 16),
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rs, (lds_ptr_t)(smem + W_BASE + c * W_PITCH + (it * NT + wave * 64) * 16),
                                                          16, w_voff[it], c * KC * 2, 0, 0);
     }
     const int cb0 = SPLIT ? cur.split * a.chunks_per_split : 0;  // split-K slice s of an item covers chunks s * chunks_per_split ...
@@ -473,18 +483,19 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
         const int ws = (cur.ntile * BN * 9 * a.Cin + cb0 * KC) * 2;
 #pragma unroll
         for (int it = 0; it < W_IT; ++it)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rs, (lds_ptr_t)(smem + W_BASE + (it * NT + wave * 64) * 16), 16, w_voff[it], ws, 0, 0);
+            if (it * NT + wave * 64 < W_UNITS)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rs, (lds_ptr_t)(smem + W_BASE + (it * NT + wave * 64) * 16), 16, w_voff[it], ws, 0, 0);
     }
 
-    // patch loader: unit u is slot u % 4 of patch pixel u / 4
+    // patch loader: unit u is slot u % SL of patch pixel u / SL
     int p_row[P_IT], p_col[P_IT];
     unsigned p_grp[P_IT];
 #pragma unroll
     for (int it = 0; it < P_IT; ++it) {
-        const unsigned u = it * NT + tid, pix = u >> 2;
+        const unsigned u = it * NT + tid, pix = u / SL;
         p_row[it] = fdiv(pix, a.mPW);
         p_col[it] = pix - p_row[it] * a.PW;
-        p_grp[it] = (((u & 3) ^ dl_swz(pix)) * 8) * 2u;
+        p_grp[it] = (((u % SL) ^ dl_swz_sl<SL>(pix)) * 8) * 2u;
     }
     unsigned p_voff[P_IT];  // byte offset of each unit's source inside x for the item being loaded
     auto patch_offsets = [&](int mtile) {
@@ -518,7 +529,7 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
     // this lane's weight rows: byte offset inside a weight buffer for k-step parity 0 / 1
     unsigned wb[KS];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) wb[ks] = (wn * WTN + frow) * 576 + (((ks * 2 + fhalf) ^ dl_swz(frow)) << 4);
+    for (int ks = 0; ks < KS; ++ks) wb[ks] = (wn * WTN + frow) * WROW + (((ks * 2 + fhalf) ^ dl_swz_sl<SL>(frow)) << 4);
 
     bool first_item = true;
     for (;;) {
@@ -541,7 +552,7 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
 #pragma unroll
                 for (int tap = 0; tap < 9; ++tap) {
                     const unsigned p = pp + (tap / 3) * a.PW + (tap % 3);
-                    aoff[i][tap] = (p << 6) + ((fhalf ^ dl_swz(p)) << 4);
+                    aoff[i][tap] = p * PB + ((fhalf ^ dl_swz_sl<SL>(p)) << 4);
                 }
             }
         }
@@ -585,11 +596,11 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
                 if (k < P_IT)
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rs, (lds_ptr_t)(smem + (BUF ^ 1) * P_PITCH + (k * NT + wave * 64) * 16),
                                                              16, p_voff[k < P_IT ? k : 0], xs1, 0, 0);
-                else if (!STAT && k - P_IT < W_IT)
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(wn_rs, (lds_ptr_t)(smem + W_BASE + (BUF ^ 1) * W_BYTES + ((k - P_IT) * NT + wave * 64) * 16),
+                else if (!STAT && k - P_IT < W_IT && (k - P_IT) * NT + wave * 64 < W_UNITS)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(wn_rs, (lds_ptr_t)(smem + W_BASE + (BUF ^ 1) * W_PITCH + ((k - P_IT) * NT + wave * 64) * 16),
                                                              16, w_voff[k - P_IT < W_IT && k >= P_IT ? k - P_IT : 0], ws1, 0, 0);
             };
-            if (!SPLIT && BUF == 1 && last) {  // epilogue operands, requested now so that they arrive during the MFMAs
+            if (!SPLIT && KC == 32 && BUF == 1 && last) {  // epilogue operands, requested now so that they arrive during the MFMAs
                 sc0 = *(const f32x4_t*)(a.scale + nbase); sc1 = *(const f32x4_t*)(a.scale + nbase + 4);
                 sh0 = *(const f32x4_t*)(a.shift + nbase); sh1 = *(const f32x4_t*)(a.shift + nbase + 4);
 #pragma unroll
@@ -603,30 +614,33 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
                         rres[i][pass] = rv;
                     }
             }
-            // MFMA loop: 18 k-steps, fragments fetched two k-steps ahead, one load slot per k-step
+            // MFMA loop: 9 * KS k-steps, fragments fetched two k-steps ahead, one load slot per k-step
             const unsigned char* pbuf = smem + BUF * P_PITCH;
-            const unsigned char* wbuf = smem + W_BASE + (STAT ? chunk : BUF) * W_BYTES;  // STAT: two chunks in all
-            u32x4_t fa[3][TM], fb[3][TN];
+            const unsigned char* wbuf = smem + W_BASE + (STAT ? chunk : BUF) * W_PITCH;  // STAT: two chunks in all
+            // fragments are read AHEAD k-steps before their MFMAs; with two workgroups per CU the other
+            // workgroup hides LDS latency and registers are scarce, so one k-step ahead is enough there
+            constexpr int AHEAD = 2, SETS = AHEAD + 1;
+            u32x4_t fa[SETS][TM], fb[SETS][TN];
             auto load_frags = [&](int set, int st) {
                 const int tap = st / KS, ks = st % KS;
 #pragma unroll
                 for (int i = 0; i < TM; ++i) fa[set][i] = *(const u32x4_t*)(pbuf + (aoff[i][tap] ^ (ks << 5)));
 #pragma unroll
-                for (int j = 0; j < TN; ++j) fb[set][j] = *(const u32x4_t*)(wbuf + wb[ks] + j * 32 * 576 + tap * 64);
+                for (int j = 0; j < TN; ++j) fb[set][j] = *(const u32x4_t*)(wbuf + wb[ks] + j * 32 * WROW + tap * PB);
             };
-            load_frags(0, 0);
-            load_frags(1, 1);
+#pragma unroll
+            for (int q = 0; q < AHEAD; ++q) load_frags(q, q);
 #pragma unroll
             for (int st = 0; st < NSTEP; ++st) {
-                __builtin_amdgcn_sched_barrier(0);  // keep the two-k-steps-ahead order of the LDS reads
-                if (st + 2 < NSTEP) load_frags((st + 2) % 3, st + 2);
+                __builtin_amdgcn_sched_barrier(0);  // keep the read-ahead order of the LDS reads
+                if (st + AHEAD < NSTEP) load_frags((st + AHEAD) % SETS, st + AHEAD);
                 issue_slot(st);  // one per k-step: issuing them faster only stalls on the address queue
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8_t, fa[st % 3][i]), __builtin_bit_cast(bf16x8_t, fb[st % 3][j]),
+                            __builtin_bit_cast(bf16x8_t, fa[st % SETS][i]), __builtin_bit_cast(bf16x8_t, fb[st % SETS][j]),
                             acc[i][j], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -641,6 +655,20 @@ __global__ __launch_bounds__(256) void conv3x3_patch_dl_kernel(const PatchArgs a
 
         {   // epilogue through the patch area of buffer 1 (the next item's first step sits in buffer 0)
             float* scr = (float*)(smem + P_PITCH) + wave * 32 * SROW;
+            if constexpr (!SPLIT && KC == 16) {  // registers are scarce here: the operands are fetched now, the co-resident workgroup covers the wait
+                sc0 = *(const f32x4_t*)(a.scale + nbase); sc1 = *(const f32x4_t*)(a.scale + nbase + 4);
+                sh0 = *(const f32x4_t*)(a.shift + nbase); sh1 = *(const f32x4_t*)(a.shift + nbase + 4);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int pass = 0; pass < NPASS; ++pass) {
+                        const int tt = wm * 64 + i * 32 + pass * RPP + rsub;
+                        u32x4_t rv = {0u, 0u, 0u, 0u};
+                        if (a.res && tt < m_lim)
+                            rv = *(const u32x4_t*)(a.res + (((size_t)g0 * a.W + tt) * a.Cout + nbase) * 2);
+                        rres[i][pass] = rv;
+                    }
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -695,11 +723,12 @@ static unsigned magic_for(unsigned d) { return (unsigned)((0x100000000ull + d - 
 struct PatchVariant { int bm, bn, kc; };
 // tile variants: 0-3 run 4 wavefronts per workgroup, 4-5 run 8 (two per SIMD), 6 is small enough
 // for two workgroups per CU, 7-8 are the direct-to-LDS kernel with 256- and 128-row tiles
-static const PatchVariant kPatchVariants[] = {{256, 64, 64}, {256, 128, 32}, {128, 64, 64}, {128, 128, 32}, {256, 64, 64}, {256, 128, 32}, {128, 64, 32}, {256, 64, 32}, {128, 64, 32}};
-constexpr int kNumPatchVariants = 9;
+static const PatchVariant kPatchVariants[] = {{256, 64, 64}, {256, 128, 32}, {128, 64, 64}, {128, 128, 32}, {256, 64, 64}, {256, 128, 32}, {128, 64, 32}, {256, 64, 32}, {128, 64, 32}, {256, 64, 16}};
+constexpr int kNumPatchVariants = 10;
 constexpr int kPatchDlVariant = 7;       // the direct-to-LDS kernel, 256-row tiles
 constexpr int kPatchDlSmallVariant = 8;  // the same with 128-row tiles, for layers with few row tiles
-static bool is_dl(int v) { return v == kPatchDlVariant || v == kPatchDlSmallVariant; }
+constexpr int kPatchDlPairVariant = 9;   // 16-channel chunks: half the LDS, two workgroups per CU
+static bool is_dl(int v) { return v == kPatchDlVariant || v == kPatchDlSmallVariant || v == kPatchDlPairVariant; }
 int patch_num_variants() { return kNumPatchVariants; }
 
 // Name as a profiler prints it: v = tile variant + 16 * stationary + 32 * split.
@@ -712,7 +741,8 @@ const char* patch_variant_name(int v)
     const PatchVariant& pv = kPatchVariants[tv];
     char* out = buf[next++ & 7];
     if (is_dl(tv)) {
-        snprintf(out, 96, "conv3x3_patch_dl_kernel<%d, %s, %s>", pv.bm, (v & 16) ? "true" : "false", (v & 32) ? "true" : "false");
+        snprintf(out, 96, "conv3x3_patch_dl_kernel<%d, %d, %s, %s>", pv.bm, pv.kc, (v & 16) ? "true" : "false",
+                 (v & 32) ? "true" : "false");
         return out;
     }
     snprintf(out, 96, "conv3x3_patch_kernel<%d, %d, %d, %s, %s, %d>", pv.bm, pv.bn, pv.kc, (v & 16) ? "true" : "false",
@@ -834,26 +864,28 @@ static int launch_patch_variant(const PatchArgs& a, int grid, bool stat, hipStre
     return launch_patch_inst<BM, BN, KC, false, false, NW>(a, grid, stream);
 }
 
-template <int BM>
+template <int BM, int KC>
 static int launch_patch_dl(const PatchArgs& a, int grid, hipStream_t stream)
 {
-    constexpr int kLds = 2 * (2 * BM * 64 + 4096) + 2 * 64 * 9 * 64;
+    constexpr int kLds = KC == 32 ? 2 * (2 * BM * 64 + 4096) + 2 * 64 * 9 * 64 : 2 * (2 * BM * 32 + 64 * 9 * 32);
+    constexpr bool kStatOk = KC == 32;  // resident weights need room for every chunk
     static bool raised = false;
     if (!raised) {
-        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<BM, true, false>,
+        if constexpr (kStatOk)
+            SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<BM, KC, kStatOk, false>,
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
+        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<BM, KC, false, false>,
                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
-        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<BM, false, false>,
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
-        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<BM, false, true>,
+        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<BM, KC, false, true>,
                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
         raised = true;
     }
     if (a.splits > 1)
-        SGPRS_LAUNCH((conv3x3_patch_dl_kernel<BM, false, true>), dim3(grid), dim3(256), kLds, stream, a);
-    else if (a.n_chunks == 2 && a.n_ntiles == 1)
-        SGPRS_LAUNCH((conv3x3_patch_dl_kernel<BM, true, false>), dim3(grid), dim3(256), kLds, stream, a);
+        SGPRS_LAUNCH((conv3x3_patch_dl_kernel<BM, KC, false, true>), dim3(grid), dim3(256), kLds, stream, a);
+    else if (kStatOk && a.n_chunks == 2 && a.n_ntiles == 1)
+        SGPRS_LAUNCH((conv3x3_patch_dl_kernel<BM, KC, kStatOk, false>), dim3(grid), dim3(256), kLds, stream, a);
     else
-        SGPRS_LAUNCH((conv3x3_patch_dl_kernel<BM, false, false>), dim3(grid), dim3(256), kLds, stream, a);
+        SGPRS_LAUNCH((conv3x3_patch_dl_kernel<BM, KC, false, false>), dim3(grid), dim3(256), kLds, stream, a);
     SGPRS_HIP(hipGetLastError());
     return SGPRS_OK;
 }
@@ -875,7 +907,7 @@ int launch_conv3x3_patch(const sgprs_conv_desc_t& d, int variant, int splits, co
     a.scale = scale; a.shift = shift; a.res = (const unsigned char*)residual; a.partial = (float*)ws;
     a.x_bytes = (unsigned)((size_t)d.n * d.h * d.w * d.cin * 2); a.w_bytes = (unsigned)((size_t)d.cout * 9 * d.cin * 2);
     const long long items = (long long)a.n_mtiles * a.n_ntiles * a.splits;
-    const int occ = variant == 6 ? 2 : 1;  // variant 6 is small enough for two workgroups per CU
+    const int occ = variant == 6 || variant == kPatchDlPairVariant ? 2 : 1;  // small enough for two workgroups per CU
     // a multiple of 8 keeps every workgroup on one die across its items
     int grid = (int)std::min<long long>(a.n_slots, (long long)cus * occ);
     if (a.xcd_groups && grid >= 8) grid -= grid % 8;
@@ -884,7 +916,7 @@ int launch_conv3x3_patch(const sgprs_conv_desc_t& d, int variant, int splits, co
     const double flops = 2.0 * M * d.cout * 9.0 * d.cin;
     const double bytes = (M * d.cin + (double)d.cout * 9 * d.cin + M * d.cout * (residual ? 2 : 1)) * 2.0;
     int rc;
-    if (prof && prof->on && (rc = prof->begin(stream, kKindPatch, variant + ((is_dl(variant) ? (a.n_chunks == 2 && a.n_ntiles == 1 && a.splits == 1) : (stat && variant % 4 == 0)) ? 16 : 0) + (splits > 1 ? 32 : 0), flops, bytes))) return rc;
+    if (prof && prof->on && (rc = prof->begin(stream, kKindPatch, variant + ((is_dl(variant) ? (variant != kPatchDlPairVariant && a.n_chunks == 2 && a.n_ntiles == 1 && a.splits == 1) : (stat && variant % 4 == 0)) ? 16 : 0) + (splits > 1 ? 32 : 0), flops, bytes))) return rc;
     switch (variant) {
         case 0: rc = launch_patch_variant<256, 64, 64>(a, grid, stat, stream); break;
         case 1: rc = launch_patch_variant<256, 128, 32>(a, grid, stat, stream); break;
@@ -892,8 +924,9 @@ int launch_conv3x3_patch(const sgprs_conv_desc_t& d, int variant, int splits, co
         case 4: rc = launch_patch_variant<256, 64, 64, 8>(a, grid, stat, stream); break;
         case 5: rc = launch_patch_variant<256, 128, 32, 8>(a, grid, stat, stream); break;
         case 6: rc = launch_patch_variant<128, 64, 32>(a, grid, stat, stream); break;
-        case kPatchDlVariant: rc = launch_patch_dl<256>(a, grid, stream); break;
-        case kPatchDlSmallVariant: rc = launch_patch_dl<128>(a, grid, stream); break;
+        case kPatchDlVariant: rc = launch_patch_dl<256, 32>(a, grid, stream); break;
+        case kPatchDlSmallVariant: rc = launch_patch_dl<128, 32>(a, grid, stream); break;
+        case kPatchDlPairVariant: rc = launch_patch_dl<256, 16>(a, grid, stream); break;
         default: rc = launch_patch_variant<128, 128, 32>(a, grid, stat, stream); break;
     }
     if (rc) return rc;
