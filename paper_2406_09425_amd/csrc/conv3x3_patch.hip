@@ -427,14 +427,17 @@ __device__ __forceinline__ unsigned dl_swz(unsigned p) { return ((p >> 3) & 1u) 
 // conflict-free for 16 consecutive pixels of one group and for 8 pixels x both groups.
 template <int SL> __device__ __forceinline__ unsigned dl_swz_sl(unsigned p) { return SL == 4 ? dl_swz(p) : (p >> 3) & 1u; }
 
-template <int BM, int KC, bool STAT, bool SPLIT>
-__global__ __launch_bounds__(256, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_kernel(const PatchArgs a)
+template <int BM, int KC, bool STAT, bool SPLIT, int NW = 4>
+__global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_kernel(const PatchArgs a)
 {
 #if __HIP_DEVICE_COMPILE__  // the buffer-resource builtins exist in the device pass only; the host needs just the stub
-    constexpr int BN = 64, NT = 256;
+    constexpr int BN = 64, NT = NW * 64;
+    static_assert(NW == 4 || (NW == 8 && BM == 256 && KC == 32), "wavefront counts");
     static_assert((BM == 256 || BM == 128) && (KC == 32 || KC == 16) && !(KC == 16 && (STAT || BM != 256)), "tile shapes");
     constexpr int PB = KC * 2, SL = PB / 16;     // bytes and 16-byte slots per pixel of one chunk
-    constexpr int WMW = BM / 64, WNW = 4 / WMW;  // wavefront grid: 4 x 1 or 2 x 2, each wavefront 64 rows x 64 / WNW channels
+    // wavefront grid: 4 x 1 or 2 x 2 (each wavefront 64 rows x 64 / WNW channels), or 8 x 1 with 32 rows each
+    // (two wavefronts per SIMD: one's waits and epilogue arithmetic overlap the other's MFMAs)
+    constexpr int WMW = NW == 8 ? 8 : BM / 64, WNW = NW / WMW, WTM = BM / WMW;
     constexpr int PCAP_PIX = 2 * BM, P_IT = PCAP_PIX * SL / NT;
     constexpr int W_UNITS = BN * 9 * SL, W_IT = (W_UNITS + NT - 1) / NT;  // the last weight slot may cover only some wavefronts
     constexpr int P_BYTES = PCAP_PIX * PB, W_BYTES = BN * 9 * PB, WROW = 9 * PB;
@@ -444,10 +447,11 @@ __global__ __launch_bounds__(256, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_kern
     // being exactly the size of the epilogue scratch, so that two workgroups fit one CU.
     constexpr int P_PITCH = KC == 32 ? P_BYTES + 4096 : P_BYTES + W_BYTES;
     constexpr int W_BASE = KC == 32 ? 2 * P_PITCH : P_BYTES, W_PITCH = KC == 32 ? W_BYTES : P_PITCH;
-    constexpr int WTN = BN / WNW, TM = 2, TN = WTN / 32, KS = KC / 16, NSTEP = 9 * KS;
+    constexpr int WTN = BN / WNW, TM = WTM / 32, TN = WTN / 32, KS = KC / 16, NSTEP = 9 * KS;
+    constexpr int SCR_ROWS = NW == 8 ? 16 : 32;  // rows a wavefront transposes through its LDS scratch at a time
     constexpr int SROW = WTN + 4, LPR = WTN / 8, RPP = 64 / LPR, NPASS = 32 / RPP;
     static_assert(NSTEP >= P_IT + W_IT, "loader slots");
-    static_assert(4 * 32 * SROW * 4 <= P_PITCH, "epilogue scratch fits the patch buffer and what follows it");
+    static_assert(NW * SCR_ROWS * SROW * 4 <= P_PITCH, "epilogue scratch fits the patch buffer and what follows it");
     typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
     extern __shared__ __align__(16) unsigned char smem[];
@@ -475,8 +479,9 @@ __global__ __launch_bounds__(256, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_kern
         for (int c = 0; c < 2; ++c)
 #pragma unroll
             for (int it = 0; it < W_IT; ++it)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rs, (lds_ptr_t)(smem + W_BASE + c * W_PITCH + (it * NT + wave * 64) * 16),
-                                                         16, w_voff[it], c * KC * 2, 0, 0);
+                if (it * NT + wave * 64 < W_UNITS)  // the last slot covers only some wavefronts
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rs, (lds_ptr_t)(smem + W_BASE + c * W_PITCH + (it * NT + wave * 64) * 16),
+                                                             16, w_voff[it], c * KC * 2, 0, 0);
     }
     const int cb0 = SPLIT ? cur.split * a.chunks_per_split : 0;  // split-K slice s of an item covers chunks s * chunks_per_split ...
     if constexpr (!STAT) {  // first step's weights: requested before the patch tables are worked out
@@ -543,7 +548,7 @@ __global__ __launch_bounds__(256, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_kern
             const int E0 = g0 + 2 * (int)fdiv(g0, a.mH);
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                const int tt = wm * 64 + i * 32 + frow;
+                const int tt = wm * WTM + i * 32 + frow;
                 const int pr = fdiv(tt, a.mW), q = tt - pr * a.W;
                 const bool ok = pr < rows_here;
                 const int g = g0 + (ok ? pr : 0);
@@ -607,7 +612,7 @@ __global__ __launch_bounds__(256, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_kern
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int pass = 0; pass < NPASS; ++pass) {
-                        const int tt = wm * 64 + i * 32 + pass * RPP + rsub;
+                        const int tt = wm * WTM + i * 32 + pass * RPP + rsub;
                         u32x4_t rv = {0u, 0u, 0u, 0u};
                         if (a.res && tt < m_lim)
                             rv = *(const u32x4_t*)(a.res + (((size_t)g0 * a.W + tt) * a.Cout + nbase) * 2);
@@ -654,7 +659,7 @@ __global__ __launch_bounds__(256, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_kern
         }
 
         {   // epilogue through the patch area of buffer 1 (the next item's first step sits in buffer 0)
-            float* scr = (float*)(smem + P_PITCH) + wave * 32 * SROW;
+            float* scr = (float*)(smem + P_PITCH) + wave * SCR_ROWS * SROW;
             if constexpr (!SPLIT && KC == 16) {  // registers are scarce here: the operands are fetched now, the co-resident workgroup covers the wait
                 sc0 = *(const f32x4_t*)(a.scale + nbase); sc1 = *(const f32x4_t*)(a.scale + nbase + 4);
                 sh0 = *(const f32x4_t*)(a.shift + nbase); sh1 = *(const f32x4_t*)(a.shift + nbase + 4);
@@ -662,7 +667,7 @@ __global__ __launch_bounds__(256, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_kern
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int pass = 0; pass < NPASS; ++pass) {
-                        const int tt = wm * 64 + i * 32 + pass * RPP + rsub;
+                        const int tt = wm * WTM + i * 32 + pass * RPP + rsub;
                         u32x4_t rv = {0u, 0u, 0u, 0u};
                         if (a.res && tt < m_lim)
                             rv = *(const u32x4_t*)(a.res + (((size_t)g0 * a.W + tt) * a.Cout + nbase) * 2);
@@ -670,16 +675,20 @@ __global__ __launch_bounds__(256, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_kern
                     }
             }
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int h = 0; h < 32 / SCR_ROWS; ++h) {  // accumulator registers 8h .. 8h+7 are rows 16h .. 16h+15 of the tile
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
                     for (int e = 0; e < 16; ++e)
-                        scr[(8 * (e >> 2) + 4 * fhalf + (e & 3)) * SROW + j * 32 + frow] = acc[i][j][e];
+                        if (SCR_ROWS == 32 || (e >> 3) == h)
+                            scr[(8 * (e >> 2) + 4 * fhalf + (e & 3) - h * SCR_ROWS) * SROW + j * 32 + frow] = acc[i][j][e];
 #pragma unroll
-                for (int pass = 0; pass < NPASS; ++pass) {
-                    const int rr = pass * RPP + rsub;
-                    const int tt = wm * 64 + i * 32 + rr;
+                for (int pp = 0; pp < SCR_ROWS / RPP; ++pp) {
+                    const int pass = h * (SCR_ROWS / RPP) + pp;
+                    const int rr = pp * RPP + rsub;
+                    const int tt = wm * WTM + i * 32 + pass * RPP + rsub;
                     f32x4_t v0 = *(const f32x4_t*)(scr + rr * SROW + c8);
                     f32x4_t v1 = *(const f32x4_t*)(scr + rr * SROW + c8 + 4);
                     if (tt < m_lim) {
@@ -723,12 +732,13 @@ static unsigned magic_for(unsigned d) { return (unsigned)((0x100000000ull + d - 
 struct PatchVariant { int bm, bn, kc; };
 // tile variants: 0-3 run 4 wavefronts per workgroup, 4-5 run 8 (two per SIMD), 6 is small enough
 // for two workgroups per CU, 7-8 are the direct-to-LDS kernel with 256- and 128-row tiles
-static const PatchVariant kPatchVariants[] = {{256, 64, 64}, {256, 128, 32}, {128, 64, 64}, {128, 128, 32}, {256, 64, 64}, {256, 128, 32}, {128, 64, 32}, {256, 64, 32}, {128, 64, 32}, {256, 64, 16}};
-constexpr int kNumPatchVariants = 10;
+static const PatchVariant kPatchVariants[] = {{256, 64, 64}, {256, 128, 32}, {128, 64, 64}, {128, 128, 32}, {256, 64, 64}, {256, 128, 32}, {128, 64, 32}, {256, 64, 32}, {128, 64, 32}, {256, 64, 16}, {256, 64, 32}};
+constexpr int kNumPatchVariants = 11;
 constexpr int kPatchDlVariant = 7;       // the direct-to-LDS kernel, 256-row tiles
 constexpr int kPatchDlSmallVariant = 8;  // the same with 128-row tiles, for layers with few row tiles
 constexpr int kPatchDlPairVariant = 9;   // 16-channel chunks: half the LDS, two workgroups per CU
-static bool is_dl(int v) { return v == kPatchDlVariant || v == kPatchDlSmallVariant || v == kPatchDlPairVariant; }
+constexpr int kPatchDlWideVariant = 10;  // 8 wavefronts of 32 rows: two per SIMD
+static bool is_dl(int v) { return v == kPatchDlVariant || v == kPatchDlSmallVariant || v == kPatchDlPairVariant || v == kPatchDlWideVariant; }
 int patch_num_variants() { return kNumPatchVariants; }
 
 // Name as a profiler prints it: v = tile variant + 16 * stationary + 32 * split.
@@ -741,8 +751,8 @@ const char* patch_variant_name(int v)
     const PatchVariant& pv = kPatchVariants[tv];
     char* out = buf[next++ & 7];
     if (is_dl(tv)) {
-        snprintf(out, 96, "conv3x3_patch_dl_kernel<%d, %d, %s, %s>", pv.bm, pv.kc, (v & 16) ? "true" : "false",
-                 (v & 32) ? "true" : "false");
+        snprintf(out, 96, "conv3x3_patch_dl_kernel<%d, %d, %s, %s, %d>", pv.bm, pv.kc, (v & 16) ? "true" : "false",
+                 (v & 32) ? "true" : "false", tv == kPatchDlWideVariant ? 8 : 4);
         return out;
     }
     snprintf(out, 96, "conv3x3_patch_kernel<%d, %d, %d, %s, %s, %d>", pv.bm, pv.bn, pv.kc, (v & 16) ? "true" : "false",
@@ -815,7 +825,7 @@ bool plan_patch(const sgprs_conv_desc_t& d, int cus, int* variant, int* splits)
     }
     // {variant, microseconds per chunk, microseconds per work item}
     static const struct { int v; double step, item; } cand[] = {
-        {7, 1.65, 5.0}, {8, 1.0, 4.5}, {4, 5.1, 2.8}, {5, 5.1, 2.8}, {3, 3.1, 2.0}, {2, 4.1, 2.0}};
+        {10, 1.5, 5.0}, {7, 1.65, 5.0}, {8, 1.0, 4.5}, {4, 5.1, 2.8}, {5, 5.1, 2.8}, {3, 3.1, 2.0}, {2, 4.1, 2.0}};
     double best = 1e30;
     bool found = false;
     for (const auto& c : cand) {
@@ -864,7 +874,7 @@ static int launch_patch_variant(const PatchArgs& a, int grid, bool stat, hipStre
     return launch_patch_inst<BM, BN, KC, false, false, NW>(a, grid, stream);
 }
 
-template <int BM, int KC>
+template <int BM, int KC, int NW = 4>
 static int launch_patch_dl(const PatchArgs& a, int grid, hipStream_t stream)
 {
     constexpr int kLds = KC == 32 ? 2 * (2 * BM * 64 + 4096) + 2 * 64 * 9 * 64 : 2 * (2 * BM * 32 + 64 * 9 * 32);
@@ -872,20 +882,21 @@ static int launch_patch_dl(const PatchArgs& a, int grid, hipStream_t stream)
     static bool raised = false;
     if (!raised) {
         if constexpr (kStatOk)
-            SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<BM, KC, kStatOk, false>,
+            SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<BM, KC, kStatOk, false, NW>,
                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
-        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<BM, KC, false, false>,
+        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<BM, KC, false, false, NW>,
                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
-        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<BM, KC, false, true>,
+        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<BM, KC, false, true, NW>,
                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
         raised = true;
     }
+    const dim3 block(NW * 64);
     if (a.splits > 1)
-        SGPRS_LAUNCH((conv3x3_patch_dl_kernel<BM, KC, false, true>), dim3(grid), dim3(256), kLds, stream, a);
+        SGPRS_LAUNCH((conv3x3_patch_dl_kernel<BM, KC, false, true, NW>), dim3(grid), block, kLds, stream, a);
     else if (kStatOk && a.n_chunks == 2 && a.n_ntiles == 1)
-        SGPRS_LAUNCH((conv3x3_patch_dl_kernel<BM, KC, kStatOk, false>), dim3(grid), dim3(256), kLds, stream, a);
+        SGPRS_LAUNCH((conv3x3_patch_dl_kernel<BM, KC, kStatOk, false, NW>), dim3(grid), block, kLds, stream, a);
     else
-        SGPRS_LAUNCH((conv3x3_patch_dl_kernel<BM, KC, false, false>), dim3(grid), dim3(256), kLds, stream, a);
+        SGPRS_LAUNCH((conv3x3_patch_dl_kernel<BM, KC, false, false, NW>), dim3(grid), block, kLds, stream, a);
     SGPRS_HIP(hipGetLastError());
     return SGPRS_OK;
 }
@@ -927,6 +938,7 @@ int launch_conv3x3_patch(const sgprs_conv_desc_t& d, int variant, int splits, co
         case kPatchDlVariant: rc = launch_patch_dl<256, 32>(a, grid, stream); break;
         case kPatchDlSmallVariant: rc = launch_patch_dl<128, 32>(a, grid, stream); break;
         case kPatchDlPairVariant: rc = launch_patch_dl<256, 16>(a, grid, stream); break;
+        case kPatchDlWideVariant: rc = launch_patch_dl<256, 32, 8>(a, grid, stream); break;
         default: rc = launch_patch_variant<128, 128, 32>(a, grid, stat, stream); break;
     }
     if (rc) return rc;
