@@ -74,6 +74,8 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip batch-1, CU sweep and multi-tenant legs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle CPU baseline")
     ap.add_argument("--cpu-sample", type=int, default=24, help="images of the batch the oracle is timed on")
+    ap.add_argument("--membound-only", action="store_true",
+                    help="run only the memory-bound operator leg (for profiling it); prints its own JSON line")
     ap.add_argument("--copy-calib", action="store_true",
                     help="also run one plain 256 MiB copy (bn_relu with scale 1, shift 0 on non-negative data), "
                          "the known-size kernel that HBM traffic counters are scaled by")
@@ -96,6 +98,23 @@ def main():
 
     def nhwc(x, tdt):
         return torch.from_numpy(np.ascontiguousarray(x.transpose(0, 2, 3, 1))).to(tdt).cuda().contiguous()
+
+    def copy_calibration():
+        nel = 128 << 20  # 128 Mi bf16 elements = 256 MiB read + 256 MiB written
+        src = torch.ones(nel, dtype=torch.bfloat16, device="cuda")
+        dst = torch.empty_like(src)
+        one = torch.ones(64, dtype=torch.float32, device="cuda")
+        zero = torch.zeros(64, dtype=torch.float32, device="cuda")
+        S.sgprs_bn_relu(S.SGPRS_BF16, nel // 64, 64, src.data_ptr(), one.data_ptr(), zero.data_ptr(), dst.data_ptr(),
+                        pool, 0)
+        pool.sync()
+
+    if args.membound_only:
+        if args.copy_calib:
+            copy_calibration()
+        print(json.dumps(dict(memory_bound_ops=leg_membound(S, hip, torch, pool, stream, reps=6))), flush=True)
+        pool.destroy()
+        return
 
     # ------------------------------------------------------------ headline
     n = args.batch
@@ -125,15 +144,7 @@ def main():
     log(f"headline: {value:.0f} img/s, {ms_per_step:.3f} ms/step (events: {ev_ms / args.steps:.3f} ms/step)")
 
     if args.copy_calib:
-        nel = 128 << 20  # 128 Mi bf16 elements = 256 MiB read + 256 MiB written
-        src = torch.ones(nel, dtype=torch.bfloat16, device="cuda")
-        dst = torch.empty_like(src)
-        one = torch.ones(64, dtype=torch.float32, device="cuda")
-        zero = torch.zeros(64, dtype=torch.float32, device="cuda")
-        S.sgprs_bn_relu(S.SGPRS_BF16, nel // 64, 64, src.data_ptr(), one.data_ptr(), zero.data_ptr(), dst.data_ptr(),
-                        pool, 0)
-        pool.sync()
-        del src, dst
+        copy_calibration()
 
     # ------------------------------------------------------------ per-kernel profile
     task.set_profiling(True)

@@ -34,21 +34,26 @@ def stats(d: str, cmd: str) -> str:
 
 
 def _per_kernel(d: str, counter: str):
+    """Average counter value per dispatch, keyed by (kernel name, grid size): the
+    same kernel launched at different sizes is reported as different rows."""
     tot, cnt = collections.defaultdict(float), collections.Counter()
     for f in _find(d, "*counter_collection.csv"):
         for r in csv.DictReader(open(f)):
             if r["Counter_Name"] == counter:
-                tot[r["Kernel_Name"]] += float(r["Counter_Value"])
-                cnt[r["Kernel_Name"]] += 1
+                key = (r["Kernel_Name"], int(r["Grid_Size"]))
+                tot[key] += float(r["Counter_Value"])
+                cnt[key] += 1
     return {k: (tot[k] / cnt[k], cnt[k]) for k in tot}
 
 
 def pmc(fetch_dir: str, write_dir: str, cmd: str) -> str:
     fetch, write = _per_kernel(fetch_dir, "FETCH_SIZE"), _per_kernel(write_dir, "WRITE_SIZE")
-    calib = [k for k in fetch if "bn_relu_kernel" in k]
-    known_kib = 256.0 * 1024.0  # the calibration copy reads 256 MiB and writes 256 MiB
+    # the calibration copy is the bn_relu launch with the largest grid (256 MiB each way)
+    calib = sorted((k for k in fetch if "bn_relu_kernel" in k[0]), key=lambda k: -k[1])
+    known_kib = 256.0 * 1024.0
     ff = known_kib / fetch[calib[0]][0] if calib else 1.0
     wf = known_kib / write[calib[0]][0] if calib and calib[0] in write else 1.0
+    sizes = collections.Counter(k[0] for k in fetch)
     out = [f"command: {cmd}", "",
            f"calibration copy: FETCH_SIZE reads {fetch[calib[0]][0]:.0f} KiB, WRITE_SIZE reads "
            f"{write[calib[0]][0]:.0f} KiB for 262144 KiB each way -> factors {ff:.4f} (fetch), {wf:.4f} (write)"
@@ -57,7 +62,8 @@ def pmc(fetch_dir: str, write_dir: str, cmd: str) -> str:
     for k in sorted(fetch, key=lambda k: -fetch[k][0]):
         f_mb = fetch[k][0] * ff * 1024 / 1e6
         w_mb = write.get(k, (0.0, 0))[0] * wf * 1024 / 1e6
-        out.append(f"{k[:90]:<92}{fetch[k][1]:>6}{f_mb:>12.2f}{w_mb:>12.2f}")
+        name = k[0][:90] if sizes[k[0]] == 1 else f"{k[0][:70]} [grid {k[1]}]"
+        out.append(f"{name:<92}{fetch[k][1]:>6}{f_mb:>12.2f}{w_mb:>12.2f}")
     return "\n".join(out) + "\n"
 
 
