@@ -503,7 +503,8 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
         p_grp[it] = (((u % SL) ^ dl_swz_sl<SL>(pix)) * 8) * 2u;
     }
     unsigned p_voff[P_IT];  // byte offset of each unit's source inside x for the item being loaded
-    auto patch_offsets = [&](int mtile) {
+    unsigned p_next[P_IT];  // the same for the item after the current one
+    auto patch_offsets = [&](int mtile, unsigned (&voff)[P_IT]) {
         const int g0 = mtile * a.TR;
         const int g1 = min(g0 + a.TR, a.NH) - 1;
         const int E0 = g0 + 2 * (int)fdiv(g0, a.mH);
@@ -514,13 +515,13 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
             const int n = fdiv(E, a.mHE);
             const int hh = E - n * a.HE - 1;
             const bool ok = p_row[it] < R && (unsigned)hh < (unsigned)a.H && p_col[it] >= 1 && p_col[it] <= a.W;
-            p_voff[it] = ok ? ((unsigned)((n * a.H + hh) * a.W + p_col[it] - 1) * (unsigned)a.Cin) * 2u + p_grp[it]
-                            : 0x80000000u;
+            voff[it] = ok ? ((unsigned)((n * a.H + hh) * a.W + p_col[it] - 1) * (unsigned)a.Cin) * 2u + p_grp[it]
+                          : 0x80000000u;
         }
     };
 
     // first step's patch
-    patch_offsets(cur.mtile);
+    patch_offsets(cur.mtile, p_voff);
     {
         const __amdgpu_buffer_rsrc_t x_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.x, 0, (int)a.x_bytes, 0x00020000);
 #pragma unroll
@@ -571,6 +572,7 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
 
         // the item after this one (its first step is loaded during this item's last step)
         const PatchItem nxt = decode_item(a, item + (int)gridDim.x);
+        if (nxt.valid) patch_offsets(nxt.mtile, p_next);
         // this item's chunks [cb, ce): an even count, so it starts on buffer 0 and ends on buffer 1
         const int cb = SPLIT ? cur.split * a.chunks_per_split : 0;
         const int ce = SPLIT ? min(cb + a.chunks_per_split, a.n_chunks) : a.n_chunks;
@@ -590,7 +592,10 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
             constexpr int BUF = decltype(BUFC)::value;
             const bool last = BUF == 1 && chunk == ce - 1;
             const bool has1 = !last || nxt.valid;
-            if (last && nxt.valid) patch_offsets(nxt.mtile);
+            if (last && nxt.valid) {
+#pragma unroll
+                for (int it = 0; it < P_IT; ++it) p_voff[it] = p_next[it];
+            }
             // without a following step the descriptors have size 0: the loads fetch nothing
             const __amdgpu_buffer_rsrc_t x_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.x, 0, has1 ? (int)a.x_bytes : 0, 0x00020000);
             const __amdgpu_buffer_rsrc_t wn_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, has1 ? (int)a.w_bytes : 0, 0x00020000);
@@ -605,6 +610,21 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(wn_rs, (lds_ptr_t)(smem + W_BASE + (BUF ^ 1) * W_PITCH + ((k - P_IT) * NT + wave * 64) * 16),
                                                              16, w_voff[k - P_IT < W_IT && k >= P_IT ? k - P_IT : 0], ws1, 0, 0);
             };
+            if constexpr (KC == 32 && BUF == 0) {
+                // First step of an item: touch every cache line of the NEXT item's patch (4 bytes per
+                // unit into an unused LDS pad), one step before its real loads are issued.  Inputs
+                // that do not fit the L2 come from HBM with a latency of two to three steps; this
+                // way the real loads find their lines in (or on their way to) the L2.
+                if (chunk == cb && nxt.valid) {
+                    const __amdgpu_buffer_rsrc_t pf_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.x, 0, (int)a.x_bytes, 0x00020000);
+                    const int lines = min(a.Cin >> 6, 2);  // 128-byte lines per pixel that are worth the extra instructions
+                    for (int l = 0; l < lines; ++l)
+#pragma unroll
+                        for (int it = 0; it < P_IT; ++it)
+                            __builtin_amdgcn_raw_ptr_buffer_load_lds(pf_rs, (lds_ptr_t)(smem + P_BYTES + wave * 256), 4, p_next[it],
+                                                                     l * 128 + nxt_cb * KC * 2, 0, 0);
+                }
+            }
             if (!SPLIT && KC == 32 && BUF == 1 && last) {  // epilogue operands, requested now so that they arrive during the MFMAs
                 sc0 = *(const f32x4_t*)(a.scale + nbase); sc1 = *(const f32x4_t*)(a.scale + nbase + 4);
                 sh0 = *(const f32x4_t*)(a.shift + nbase); sh1 = *(const f32x4_t*)(a.shift + nbase + 4);
@@ -825,7 +845,7 @@ bool plan_patch(const sgprs_conv_desc_t& d, int cus, int* variant, int* splits)
     }
     // {variant, microseconds per chunk, microseconds per work item}
     static const struct { int v; double step, item; } cand[] = {
-        {10, 1.5, 5.0}, {7, 1.65, 5.0}, {8, 1.0, 4.5}, {4, 5.1, 2.8}, {5, 5.1, 2.8}, {3, 3.1, 2.0}, {2, 4.1, 2.0}};
+        {10, 1.5, 4.3}, {7, 1.65, 5.0}, {8, 1.0, 4.5}, {4, 5.1, 2.8}, {5, 5.1, 2.8}, {3, 3.1, 2.0}, {2, 4.1, 2.0}};
     double best = 1e30;
     bool found = false;
     for (const auto& c : cand) {
