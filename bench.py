@@ -187,10 +187,14 @@ def main():
     traffic = None
     tr_file = os.path.join(ROOT, "profiles", "resnet18_b64_bf16_hbm_traffic.txt")
     if n == 64 and os.path.exists(tr_file):  # measured once with rocprofv3 --pmc, see profiles/
+        tot, disp = 0.0, 0   # a kernel launched at several grid sizes has several rows: dispatch-weighted mean
         for line in open(tr_file):
             if dom_key[0] in line:
                 f = line.split()
-                traffic = round((float(f[-2]) + float(f[-1])) * 1e6)
+                tot += int(f[-3]) * (float(f[-2]) + float(f[-1])) * 1e6
+                disp += int(f[-3])
+        if disp:
+            traffic = round(tot / disp)
     roofline = dict(bound="mfma", kernel=dom_key[0], achieved=round(dfl / dt_s / 1e12, 2), peak=PEAK_BF16 / 1e12,
                     unit="TFLOP/s", frac=round(dfl / dt_s / PEAK_BF16, 4), traffic=traffic,
                     avg_launch_us=round(dt_s / dcnt * 1e6, 2), launches_per_step=dcnt // prof_steps,
