@@ -240,6 +240,12 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu, "conv_all": conv_all, "stages": stages, "kernels": kernels,
     }
 
+    # sustained matrix-core rate of this chip (instruction mix of the conv inner loop, no global traffic)
+    out["roofline"]["sustained_mfma"] = leg_mfma_probe(S, hip, torch, pool, stream, total_cus)
+    rnd = out["roofline"]["sustained_mfma"]["random_data"]["tflops"]
+    out["roofline"]["frac_of_sustained_random_data"] = round(roofline["achieved"] / rnd, 4)
+    out["conv_all"]["frac_of_sustained_random_data"] = round(conv_all["tflops"] / rnd, 4)
+
     if not args.no_extras:
         out["batch1_fp32"] = leg_batch1(S, hip, pool, stream, nhwc, torch, total_cus)
         out["cu_sweep"] = leg_sweep(S, hip, torch, total_cus, nhwc, with_cpu=not args.no_cpu)
@@ -392,6 +398,33 @@ def leg_sweep(S, hip, torch, total_cus, nhwc, with_cpu=True, reps=200):
         for name, r in res[dname].items():
             r["speedup_vs_8"] = [round(r["us"][0] / u, 2) for u in r["us"]]
             log("sweep", dname, name, "us", r["us"], "speedup", r["speedup_vs_8"])
+    return res
+
+
+def leg_mfma_probe(S, hip, torch, pool, stream, total_cus, steps=4000, reps=5):
+    """What the matrix cores sustain on this chip with the conv kernel's inner-loop instruction mix
+    (LDS fragment reads + MFMA 32x32x16 bf16, 8 wavefronts per CU, no global memory traffic), with
+    constant and with pseudo-random operands: under dense MFMA load the shader clock settles well
+    below its 2.4 GHz maximum, and lower still when the operand bits toggle."""
+    out = torch.zeros(3, dtype=torch.int64, device="cuda")
+    res = {}
+    for name, rnd in (("constant_data", False), ("random_data", True)):
+        pool.mfma_probe(0, rnd, 200, out.data_ptr())
+        pool.sync()
+        e0, e1 = hip.event(), hip.event()
+        hip.record(e0, stream)
+        for _ in range(reps):
+            pool.mfma_probe(0, rnd, steps, out.data_ptr())
+        hip.record(e1, stream)
+        pool.sync()
+        sec = hip.elapsed_ms(e0, e1) * 1e-3 / reps
+        ticks, clocks, _ = (int(v) for v in out.cpu().tolist())
+        mfmas_per_simd = steps * 18 * 4 * 2                       # two wavefronts per SIMD
+        flops = 2.0 * 32 * 32 * 16 * steps * 18 * 4 * 8 * total_cus
+        res[name] = dict(tflops=round(flops / sec / 1e12, 1), shader_ghz=round(clocks / (ticks / 100e6) / 1e9, 3),
+                         mfma_pipe_busy=round(mfmas_per_simd * 32 / clocks, 3),
+                         frac_of_published_peak=round(flops / sec / PEAK_BF16, 4))
+        log("mfma_probe", name, json.dumps(res[name]))
     return res
 
 

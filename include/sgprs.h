@@ -116,6 +116,17 @@ int sgprs_pool_sync(sgprs_pool_t *pool);
  * the mask-bit -> die mapping by measurement. */
 int sgprs_partition_probe(sgprs_pool_t *pool, int partition, int n_blocks, int spin_cycles,
                           uint32_t *out);
+/* Diagnostic: the sustained matrix-core rate of the partition.  One 512-thread
+ * workgroup per CU runs `steps` (1..1e6) rounds of 18 k-steps; per k-step every
+ * wavefront reads four 16-byte fragments per lane from LDS and issues four
+ * MFMA 32x32x16 bf16 (the inner loop of the 3x3 convolution kernel without its
+ * global loads): 2 * 32*32*16 * 4 * 18 * 8 * steps FLOP per CU.  random_data
+ * != 0 fills the fragments with pseudo-random bf16 values instead of 1.0 (the
+ * clock the chip sustains depends on it).  out: DEVICE uint64[3], written by
+ * workgroup 0: elapsed ticks of the 100 MHz constant-rate counter, elapsed
+ * shader clocks, a checksum.  Time the launch with events on the partition's
+ * stream for the aggregate rate. */
+int sgprs_mfma_probe(sgprs_pool_t *pool, int partition, int random_data, int steps, uint64_t *out);
 
 /* -------------------------------------------------------- per-operator ----
  * The operators of the paper's "GPU Speedup Analysis": convolution, max
@@ -158,7 +169,7 @@ int sgprs_conv2d(const sgprs_conv_desc_t *d, const void *x, const void *w_packed
 /* Measurement hook, process-wide, not thread-safe: which convolution kernel
  * sgprs_conv2d and the stages pick for 3x3 stride-1 bf16 layers.  kind -1:
  * automatic (default); 0: implicit GEMM only; 1: the LDS-patch kernel with the
- * given tile variant (0..10) and split factor where the shape allows it; 2:
+ * given tile variant (0..11) and split factor where the shape allows it; 2:
  * automatic, but implicit-GEMM launches use tile variant `variant` (0..3)
  * wherever it divides cout, with split-K factor `splits` (0: planner's choice). */
 int sgprs_conv_tuning_override(int kind, int variant, int splits);

@@ -44,7 +44,7 @@ struct PatchArgs {
     int xcd_groups;           // > 0: work items are laid out so that one die keeps one channel block
     int n_slots;              // size of the (possibly padded) work-item index space
     int relu;
-    unsigned x_bytes, w_bytes;  // sizes of x and w (buffer-descriptor bounds of the direct-to-LDS kernel)
+    unsigned x_bytes, w_bytes, y_bytes;  // sizes of x, w and y (buffer-descriptor bounds of the direct-to-LDS kernel)
 };
 
 __device__ __forceinline__ unsigned fdiv(unsigned x, unsigned magic) { return __umulhi(x, magic); }
@@ -422,6 +422,7 @@ __global__ __launch_bounds__((NW * 64), (PatchCfg<BM, BN, KC, NW>::WAVES_PER_SIM
 // weights use the same rule with the output channel in the place of p.
 // With two chunks and one channel block (64 -> 64 layers) all weights stay
 // resident (STAT) and only the patch is double buffered.
+constexpr int kPatchCap512 = 672;  // patch capacity (pixels) of the 512-row tile
 __device__ __forceinline__ unsigned dl_swz(unsigned p) { return ((p >> 3) & 1u) | ((p >> 1) & 2u); }
 // The same with 16-channel chunks (32-byte pixels, two slots): slot s holds group s ^ ((p >> 3) & 1),
 // conflict-free for 16 consecutive pixels of one group and for 8 pixels x both groups.
@@ -432,21 +433,31 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
 {
 #if __HIP_DEVICE_COMPILE__  // the buffer-resource builtins exist in the device pass only; the host needs just the stub
     constexpr int BN = 64, NT = NW * 64;
-    static_assert(NW == 4 || (NW == 8 && BM == 256 && KC == 32), "wavefront counts");
-    static_assert((BM == 256 || BM == 128) && (KC == 32 || KC == 16) && !(KC == 16 && (STAT || BM != 256)), "tile shapes");
+    static_assert(NW == 4 || (NW == 8 && (BM == 256 || BM == 512) && KC == 32), "wavefront counts");
+    static_assert((BM == 512 || BM == 256 || BM == 128) && (KC == 32 || KC == 16) && !(KC == 16 && (STAT || BM != 256)) &&
+                      !(BM == 512 && NW != 8),
+                  "tile shapes");
     constexpr int PB = KC * 2, SL = PB / 16;     // bytes and 16-byte slots per pixel of one chunk
     // wavefront grid: 4 x 1 or 2 x 2 (each wavefront 64 rows x 64 / WNW channels), or 8 x 1 with 32 rows each
-    // (two wavefronts per SIMD: one's waits and epilogue arithmetic overlap the other's MFMAs)
+    // (two wavefronts per SIMD: one's waits and epilogue arithmetic overlap the other's MFMAs); with
+    // 512-row tiles those 8 wavefronts own 64 rows each, i.e. 2 x 2 MFMA tiles and one LDS fragment
+    // read per MFMA instead of one and a half
     constexpr int WMW = NW == 8 ? 8 : BM / 64, WNW = NW / WMW, WTM = BM / WMW;
-    constexpr int PCAP_PIX = 2 * BM, P_IT = PCAP_PIX * SL / NT;
+    // patch capacity in pixels: twice the tile for the small tiles; the 512-row tile has to share
+    // the 160 KB with two weight buffers and gets what is left (enough for 18 rows of a 28-wide
+    // image plus halo across one image border, or 8 rows of a 56-wide one)
+    constexpr int PCAP_PIX = BM == 512 ? kPatchCap512 : 2 * BM;
+    constexpr int P_UNITS = PCAP_PIX * SL, P_IT = (P_UNITS + NT - 1) / NT;  // the last patch slot may cover only some wavefronts
+    static_assert(P_UNITS % 64 == 0, "whole-wavefront patch loads");
     constexpr int W_UNITS = BN * 9 * SL, W_IT = (W_UNITS + NT - 1) / NT;  // the last weight slot may cover only some wavefronts
     constexpr int P_BYTES = PCAP_PIX * PB, W_BYTES = BN * 9 * PB, WROW = 9 * PB;
     // LDS map.  32-channel chunks: [patch 0][pad][patch 1][pad][weights 0][weights 1] (the patch
     // fragment reads keep 16-bit immediate offsets; the pad lets the epilogue scratch overhang
     // the patch area).  16-channel chunks: [patch 0][weights 0][patch 1][weights 1], one stage
     // being exactly the size of the epilogue scratch, so that two workgroups fit one CU.
-    constexpr int P_PITCH = KC == 32 ? P_BYTES + 4096 : P_BYTES + W_BYTES;
+    constexpr int P_PITCH = KC == 32 ? P_BYTES + (BM == 512 ? 0 : 4096) : P_BYTES + W_BYTES;
     constexpr int W_BASE = KC == 32 ? 2 * P_PITCH : P_BYTES, W_PITCH = KC == 32 ? W_BYTES : P_PITCH;
+    constexpr int PF_BASE = BM == 512 ? W_BASE + 2 * W_PITCH : P_BYTES;  // 256 bytes per wavefront that nobody reads
     constexpr int WTN = BN / WNW, TM = WTM / 32, TN = WTN / 32, KS = KC / 16, NSTEP = 9 * KS;
     constexpr int SCR_ROWS = NW == 8 ? 16 : 32;  // rows a wavefront transposes through its LDS scratch at a time
     constexpr int SROW = WTN + 4, LPR = WTN / 8, RPP = 64 / LPR, NPASS = 32 / RPP;
@@ -459,6 +470,8 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
     const int frow = lane & 31, fhalf = lane >> 5;
     const int wm = wave / WNW, wn = wave % WNW;
     static_assert(!(STAT && SPLIT), "resident weights are for whole-K items");
+    // whether the residual and the BN vectors are requested before the last step's MFMAs (registers permitting) or in the epilogue
+    constexpr bool EARLY_RES = KC == 32 && BM != 512;
 
     // weight loader: 16-byte unit u = it * 256 + tid is slot u % SL of tap (u / SL) % 9 of row u / (9 * SL)
     unsigned w_voff[W_IT];
@@ -526,8 +539,9 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
         const __amdgpu_buffer_rsrc_t x_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.x, 0, (int)a.x_bytes, 0x00020000);
 #pragma unroll
         for (int it = 0; it < P_IT; ++it)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rs, (lds_ptr_t)(smem + (it * NT + wave * 64) * 16), 16, p_voff[it],
-                                                     cb0 * KC * 2, 0, 0);
+            if (it * NT + wave * 64 < P_UNITS)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rs, (lds_ptr_t)(smem + (it * NT + wave * 64) * 16), 16, p_voff[it],
+                                                         cb0 * KC * 2, 0, 0);
     }
     // (they land while the first item's addresses are set up; the wait is inside the item loop)
 
@@ -562,6 +576,8 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
                 }
             }
         }
+        // tile row -> output pixel of this item, or -1 past the item's rows
+        auto tile_pixel = [&](int tt) { return tt < m_lim ? tt : -1; };
         f32x16_t acc[TM][TN];
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -603,10 +619,11 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
             const int xs1 = chunk1 * KC * 2;
             const int ws1 = ((last ? nxt.ntile : cur.ntile) * BN * 9 * a.Cin + chunk1 * KC) * 2;
             auto issue_slot = [&](int k) {
-                if (k < P_IT)
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rs, (lds_ptr_t)(smem + (BUF ^ 1) * P_PITCH + (k * NT + wave * 64) * 16),
-                                                             16, p_voff[k < P_IT ? k : 0], xs1, 0, 0);
-                else if (!STAT && k - P_IT < W_IT && (k - P_IT) * NT + wave * 64 < W_UNITS)
+                if (k < P_IT) {
+                    if (k * NT + wave * 64 < P_UNITS)
+                        __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rs, (lds_ptr_t)(smem + (BUF ^ 1) * P_PITCH + (k * NT + wave * 64) * 16),
+                                                                 16, p_voff[k < P_IT ? k : 0], xs1, 0, 0);
+                } else if (!STAT && k - P_IT < W_IT && (k - P_IT) * NT + wave * 64 < W_UNITS)
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(wn_rs, (lds_ptr_t)(smem + W_BASE + (BUF ^ 1) * W_PITCH + ((k - P_IT) * NT + wave * 64) * 16),
                                                              16, w_voff[k - P_IT < W_IT && k >= P_IT ? k - P_IT : 0], ws1, 0, 0);
             };
@@ -621,21 +638,36 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
                     for (int l = 0; l < lines; ++l)
 #pragma unroll
                         for (int it = 0; it < P_IT; ++it)
-                            __builtin_amdgcn_raw_ptr_buffer_load_lds(pf_rs, (lds_ptr_t)(smem + P_BYTES + wave * 256), 4, p_next[it],
-                                                                     l * 128 + nxt_cb * KC * 2, 0, 0);
+                            if (it * NT + wave * 64 < P_UNITS)
+                                __builtin_amdgcn_raw_ptr_buffer_load_lds(pf_rs, (lds_ptr_t)(smem + PF_BASE + wave * 256), 4, p_next[it],
+                                                                         l * 128 + nxt_cb * KC * 2, 0, 0);
                 }
             }
-            if (!SPLIT && KC == 32 && BUF == 1 && last) {  // epilogue operands, requested now so that they arrive during the MFMAs
+            if constexpr (!SPLIT && BM == 512 && BUF == 1 && WNW == 1) {
+                // No registers to spare for the residual here: touch this wavefront's residual lines instead
+                // (one 128-byte line per output row, 4 bytes each into the unused pad), so that the
+                // epilogue's loads hit in the L2.
+                if (last && a.res) {
+                    const __amdgpu_buffer_rsrc_t r_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.res, 0, (int)a.y_bytes, 0x00020000);
+#pragma unroll
+                    for (int r = 0; r < WTM / 64; ++r) {
+                        const int px = tile_pixel(wm * WTM + r * 64 + lane);
+                        const unsigned off = px >= 0 ? (unsigned)((g0 * a.W + px) * a.Cout + cur.ntile * BN) * 2u : 0x80000000u;
+                        __builtin_amdgcn_raw_ptr_buffer_load_lds(r_rs, (lds_ptr_t)(smem + PF_BASE + wave * 256), 4, off, 0, 0, 0);
+                    }
+                }
+            }
+            if (!SPLIT && EARLY_RES && BUF == 1 && last) {  // epilogue operands, requested now so that they arrive during the MFMAs
                 sc0 = *(const f32x4_t*)(a.scale + nbase); sc1 = *(const f32x4_t*)(a.scale + nbase + 4);
                 sh0 = *(const f32x4_t*)(a.shift + nbase); sh1 = *(const f32x4_t*)(a.shift + nbase + 4);
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int pass = 0; pass < NPASS; ++pass) {
-                        const int tt = wm * WTM + i * 32 + pass * RPP + rsub;
+                        const int px = tile_pixel(wm * WTM + i * 32 + pass * RPP + rsub);
                         u32x4_t rv = {0u, 0u, 0u, 0u};
-                        if (a.res && tt < m_lim)
-                            rv = *(const u32x4_t*)(a.res + (((size_t)g0 * a.W + tt) * a.Cout + nbase) * 2);
+                        if (a.res && px >= 0)
+                            rv = *(const u32x4_t*)(a.res + (((size_t)g0 * a.W + px) * a.Cout + nbase) * 2);
                         rres[i][pass] = rv;
                     }
             }
@@ -680,17 +712,17 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
 
         {   // epilogue through the patch area of buffer 1 (the next item's first step sits in buffer 0)
             float* scr = (float*)(smem + P_PITCH) + wave * SCR_ROWS * SROW;
-            if constexpr (!SPLIT && KC == 16) {  // registers are scarce here: the operands are fetched now, the co-resident workgroup covers the wait
+            if constexpr (!SPLIT && !EARLY_RES) {  // registers are scarce here: the operands are fetched now, the other wavefronts of the CU cover the wait
                 sc0 = *(const f32x4_t*)(a.scale + nbase); sc1 = *(const f32x4_t*)(a.scale + nbase + 4);
                 sh0 = *(const f32x4_t*)(a.shift + nbase); sh1 = *(const f32x4_t*)(a.shift + nbase + 4);
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int pass = 0; pass < NPASS; ++pass) {
-                        const int tt = wm * WTM + i * 32 + pass * RPP + rsub;
+                        const int px = tile_pixel(wm * WTM + i * 32 + pass * RPP + rsub);
                         u32x4_t rv = {0u, 0u, 0u, 0u};
-                        if (a.res && tt < m_lim)
-                            rv = *(const u32x4_t*)(a.res + (((size_t)g0 * a.W + tt) * a.Cout + nbase) * 2);
+                        if (a.res && px >= 0)
+                            rv = *(const u32x4_t*)(a.res + (((size_t)g0 * a.W + px) * a.Cout + nbase) * 2);
                         rres[i][pass] = rv;
                     }
             }
@@ -708,11 +740,11 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
                 for (int pp = 0; pp < SCR_ROWS / RPP; ++pp) {
                     const int pass = h * (SCR_ROWS / RPP) + pp;
                     const int rr = pp * RPP + rsub;
-                    const int tt = wm * WTM + i * 32 + pass * RPP + rsub;
+                    const int px = tile_pixel(wm * WTM + i * 32 + pass * RPP + rsub);
                     f32x4_t v0 = *(const f32x4_t*)(scr + rr * SROW + c8);
                     f32x4_t v1 = *(const f32x4_t*)(scr + rr * SROW + c8 + 4);
-                    if (tt < m_lim) {
-                        const size_t m = (size_t)g0 * a.W + tt;
+                    if (px >= 0) {
+                        const size_t m = (size_t)g0 * a.W + px;
                         if constexpr (SPLIT) {  // fp32 partial sums; scale, shift, residual and ReLU happen in the reduction
                             float* dst = a.partial + ((size_t)cur.split * a.NH * a.W + m) * a.Cout + nbase;
                             *(f32x4_t*)dst = v0;
@@ -752,13 +784,14 @@ static unsigned magic_for(unsigned d) { return (unsigned)((0x100000000ull + d - 
 struct PatchVariant { int bm, bn, kc; };
 // tile variants: 0-3 run 4 wavefronts per workgroup, 4-5 run 8 (two per SIMD), 6 is small enough
 // for two workgroups per CU, 7-8 are the direct-to-LDS kernel with 256- and 128-row tiles
-static const PatchVariant kPatchVariants[] = {{256, 64, 64}, {256, 128, 32}, {128, 64, 64}, {128, 128, 32}, {256, 64, 64}, {256, 128, 32}, {128, 64, 32}, {256, 64, 32}, {128, 64, 32}, {256, 64, 16}, {256, 64, 32}};
-constexpr int kNumPatchVariants = 11;
+static const PatchVariant kPatchVariants[] = {{256, 64, 64}, {256, 128, 32}, {128, 64, 64}, {128, 128, 32}, {256, 64, 64}, {256, 128, 32}, {128, 64, 32}, {256, 64, 32}, {128, 64, 32}, {256, 64, 16}, {256, 64, 32}, {512, 64, 32}};
+constexpr int kNumPatchVariants = 12;
 constexpr int kPatchDlVariant = 7;       // the direct-to-LDS kernel, 256-row tiles
 constexpr int kPatchDlSmallVariant = 8;  // the same with 128-row tiles, for layers with few row tiles
 constexpr int kPatchDlPairVariant = 9;   // 16-channel chunks: half the LDS, two workgroups per CU
 constexpr int kPatchDlWideVariant = 10;  // 8 wavefronts of 32 rows: two per SIMD
-static bool is_dl(int v) { return v == kPatchDlVariant || v == kPatchDlSmallVariant || v == kPatchDlPairVariant || v == kPatchDlWideVariant; }
+constexpr int kPatchDlTallVariant = 11;  // 8 wavefronts of 64 rows: 512-row tiles
+static bool is_dl(int v) { return v >= kPatchDlVariant && v <= kPatchDlTallVariant; }
 int patch_num_variants() { return kNumPatchVariants; }
 
 // Name as a profiler prints it: v = tile variant + 16 * stationary + 32 * split.
@@ -772,7 +805,7 @@ const char* patch_variant_name(int v)
     char* out = buf[next++ & 7];
     if (is_dl(tv)) {
         snprintf(out, 96, "conv3x3_patch_dl_kernel<%d, %d, %s, %s, %d>", pv.bm, pv.kc, (v & 16) ? "true" : "false",
-                 (v & 32) ? "true" : "false", tv == kPatchDlWideVariant ? 8 : 4);
+                 (v & 32) ? "true" : "false", tv >= kPatchDlWideVariant ? 8 : 4);
         return out;
     }
     snprintf(out, 96, "conv3x3_patch_kernel<%d, %d, %d, %s, %s, %d>", pv.bm, pv.bn, pv.kc, (v & 16) ? "true" : "false",
@@ -792,18 +825,24 @@ static bool patch_geometry(const sgprs_conv_desc_t& d, int v, int splits, PatchA
     const PatchVariant& pv = kPatchVariants[v];
     if (d.cout % pv.bn || d.cin % pv.kc || d.w > pv.bm) return false;
     // the direct-to-LDS kernel addresses x and w through 31-bit buffer offsets
-    if (is_dl(v) && ((long long)d.n * d.h * d.w * d.cin * 2 >= (1ll << 31) ||
+    if (is_dl(v) && ((long long)d.n * d.h * d.w * d.cin * 2 >= (1ll << 31) || (long long)d.n * d.h * d.w * d.cout * 2 >= (1ll << 31) ||
                                  (long long)d.cout * 9 * d.cin * 2 >= (1ll << 31)))
         return false;
-    const int TR = pv.bm / d.w, NH = d.n * d.h;
-    const int cap = pv.bm == 256 ? 512 : 256;  // patch capacity in pixels
-    const int n_mtiles = (NH + TR - 1) / TR;
-    int rmax = 0;
-    for (int t = 0; t < n_mtiles; ++t) {
-        const int g0 = t * TR, g1 = std::min(g0 + TR, NH) - 1;
-        rmax = std::max(rmax, (g1 + 2 * (g1 / d.h) + 2) - (g0 + 2 * (g0 / d.h)) + 1);
+    const int NH = d.n * d.h;
+    const int cap = pv.bm == 512 ? kPatchCap512 : 2 * pv.bm;  // patch capacity in pixels
+    // the most output rows per tile whose patch (halo rows included, also across image borders) fits
+    int TR = pv.bm / d.w, n_mtiles = 0;
+    for (; TR >= 1; --TR) {
+        n_mtiles = (NH + TR - 1) / TR;
+        int rmax = 0;
+        for (int t = 0; t < n_mtiles; ++t) {
+            const int g0 = t * TR, g1 = std::min(g0 + TR, NH) - 1;
+            rmax = std::max(rmax, (g1 + 2 * (g1 / d.h) + 2) - (g0 + 2 * (g0 / d.h)) + 1);
+        }
+        if (rmax * (d.w + 2) <= cap) break;
+        if (pv.bm != 512) return false;  // the smaller tiles keep their full-height geometry or decline
     }
-    if (rmax * (d.w + 2) > cap) return false;
+    if (TR < 1 || (pv.bm == 512 && TR * d.w * 4 < pv.bm * 3)) return false;  // a 512-row tile less than three quarters full is not worth it
     const int n_chunks = d.cin / pv.kc;
     if (splits < 1 || splits > n_chunks) return false;
     const int cps = (n_chunks + splits - 1) / splits;
@@ -845,7 +884,7 @@ bool plan_patch(const sgprs_conv_desc_t& d, int cus, int* variant, int* splits)
     }
     // {variant, microseconds per chunk, microseconds per work item}
     static const struct { int v; double step, item; } cand[] = {
-        {10, 1.5, 4.3}, {7, 1.65, 5.0}, {8, 1.0, 4.5}, {4, 5.1, 2.8}, {5, 5.1, 2.8}, {3, 3.1, 2.0}, {2, 4.1, 2.0}};
+        {11, 2.4, 6.0}, {10, 1.5, 4.3}, {7, 1.65, 5.0}, {8, 1.0, 4.5}, {4, 5.1, 2.8}, {5, 5.1, 2.8}, {3, 3.1, 2.0}, {2, 4.1, 2.0}};
     double best = 1e30;
     bool found = false;
     for (const auto& c : cand) {
@@ -897,7 +936,10 @@ static int launch_patch_variant(const PatchArgs& a, int grid, bool stat, hipStre
 template <int BM, int KC, int NW = 4>
 static int launch_patch_dl(const PatchArgs& a, int grid, hipStream_t stream)
 {
-    constexpr int kLds = KC == 32 ? 2 * (2 * BM * 64 + 4096) + 2 * 64 * 9 * 64 : 2 * (2 * BM * 32 + 64 * 9 * 32);
+    constexpr int kLds = BM == 512 ? 2 * kPatchCap512 * 64 + 2 * 64 * 9 * 64 + 8 * 256
+                         : KC == 32 ? 2 * (2 * BM * 64 + 4096) + 2 * 64 * 9 * 64
+                                    : 2 * (2 * BM * 32 + 64 * 9 * 32);
+    static_assert(kLds <= 160 * 1024, "LDS of one CU");
     constexpr bool kStatOk = KC == 32;  // resident weights need room for every chunk
     static bool raised = false;
     if (!raised) {
@@ -937,6 +979,7 @@ int launch_conv3x3_patch(const sgprs_conv_desc_t& d, int variant, int splits, co
     a.x = (const unsigned char*)x; a.w = (const unsigned char*)w; a.y = (unsigned char*)y;
     a.scale = scale; a.shift = shift; a.res = (const unsigned char*)residual; a.partial = (float*)ws;
     a.x_bytes = (unsigned)((size_t)d.n * d.h * d.w * d.cin * 2); a.w_bytes = (unsigned)((size_t)d.cout * 9 * d.cin * 2);
+    a.y_bytes = (unsigned)((size_t)d.n * d.h * d.w * d.cout * 2);
     const long long items = (long long)a.n_mtiles * a.n_ntiles * a.splits;
     const int occ = variant == 6 || variant == kPatchDlPairVariant ? 2 : 1;  // small enough for two workgroups per CU
     // a multiple of 8 keeps every workgroup on one die across its items
@@ -959,6 +1002,7 @@ int launch_conv3x3_patch(const sgprs_conv_desc_t& d, int variant, int splits, co
         case kPatchDlSmallVariant: rc = launch_patch_dl<128, 32>(a, grid, stream); break;
         case kPatchDlPairVariant: rc = launch_patch_dl<256, 16>(a, grid, stream); break;
         case kPatchDlWideVariant: rc = launch_patch_dl<256, 32, 8>(a, grid, stream); break;
+        case kPatchDlTallVariant: rc = launch_patch_dl<512, 32, 8>(a, grid, stream); break;
         default: rc = launch_patch_variant<128, 128, 32>(a, grid, stat, stream); break;
     }
     if (rc) return rc;

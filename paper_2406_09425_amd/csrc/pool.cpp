@@ -279,4 +279,15 @@ int sgprs_partition_probe(sgprs_pool_t* pool, int partition, int n_blocks, int s
     return launch_probe(n_blocks, spin_cycles, out, s);
 }
 
+int sgprs_mfma_probe(sgprs_pool_t* pool, int partition, int random_data, int steps, uint64_t* out)
+{
+    hipStream_t s;
+    int c = 0;
+    int rc = resolve(pool, partition, &s, &c);
+    if (rc) return rc;
+    if (!out) return fail(SGPRS_ERR_INVALID_ARG, "out is NULL");
+    if (steps <= 0 || steps > 1000000) return fail(SGPRS_ERR_INVALID_ARG, "steps %d outside [1,1e6]", steps);
+    return launch_mfma_probe(c, steps, random_data != 0, (unsigned long long*)out, s);
+}
+
 }  // extern "C"

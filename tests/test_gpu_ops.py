@@ -221,7 +221,7 @@ PATCH_SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("variant", range(11))
+@pytest.mark.parametrize("variant", range(12))
 @pytest.mark.parametrize("shape", PATCH_SHAPES, ids=lambda s: "x".join(map(str, s)))
 def test_conv3x3_patch_variants_parity(pools, variant, shape):
     n, h, w, cin, cout = shape

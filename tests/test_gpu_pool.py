@@ -90,3 +90,25 @@ def test_explicit_masks_pool():
     pool.destroy()
     with pytest.raises(S.SgprsError):
         S.Pool(1, 0, masks=np.zeros((1, words), dtype=np.uint32))
+
+
+def test_mfma_probe_checksum_and_errors():
+    """The sustained-rate probe really runs its MFMAs: with constant operands (1.0) every
+    accumulator element ends at 16 * 18 * steps, and workgroup 0 reports the sum of its 64."""
+    total = S.Pool(1, 8).info()["total_cus"]
+    pool = S.Pool(1, total)
+    out = torch.zeros(3, dtype=torch.int64, device="cuda")
+    steps = 10
+    pool.mfma_probe(0, False, steps, out.data_ptr())
+    pool.sync()
+    ticks, clocks, bits = (int(v) for v in out.cpu().tolist())
+    assert ticks > 0 and clocks > 0
+    assert np.array([bits], dtype=np.uint32).view(np.float32)[0] == 64.0 * 16 * 18 * steps
+    pool.mfma_probe(0, True, steps, out.data_ptr())
+    pool.sync()
+    assert np.isfinite(np.array([int(out[2])], dtype=np.uint32).view(np.float32)[0])
+    with pytest.raises(S.SgprsError):
+        pool.mfma_probe(0, False, 0, out.data_ptr())
+    with pytest.raises(S.SgprsError):
+        pool.mfma_probe(0, False, 10, 0)
+    pool.destroy()
