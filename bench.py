@@ -240,13 +240,12 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu, "conv_all": conv_all, "stages": stages, "kernels": kernels,
     }
 
-    # sustained matrix-core rate of this chip (instruction mix of the conv inner loop, no global traffic)
-    out["roofline"]["sustained_mfma"] = leg_mfma_probe(S, hip, torch, pool, stream, total_cus)
-    rnd = out["roofline"]["sustained_mfma"]["random_data"]["tflops"]
-    out["roofline"]["frac_of_sustained_random_data"] = round(roofline["achieved"] / rnd, 4)
-    out["conv_all"]["frac_of_sustained_random_data"] = round(conv_all["tflops"] / rnd, 4)
-
     if not args.no_extras:
+        # sustained matrix-core rate of this chip (instruction mix of the conv inner loop, no global traffic)
+        out["roofline"]["sustained_mfma"] = leg_mfma_probe(S, hip, torch, pool, stream, total_cus)
+        rnd = out["roofline"]["sustained_mfma"]["random_data"]["tflops"]
+        out["roofline"]["frac_of_sustained_random_data"] = round(roofline["achieved"] / rnd, 4)
+        out["conv_all"]["frac_of_sustained_random_data"] = round(conv_all["tflops"] / rnd, 4)
         out["batch1_fp32"] = leg_batch1(S, hip, pool, stream, nhwc, torch, total_cus)
         out["cu_sweep"] = leg_sweep(S, hip, torch, total_cus, nhwc, with_cpu=not args.no_cpu)
         out["multi_tenant"] = leg_multi_tenant(S, hip, torch, total_cus, nhwc)
