@@ -197,13 +197,24 @@ __global__ __launch_bounds__(256) void avgpool_kernel(const void* __restrict__ x
     float s[N];
 #pragma unroll
     for (int i = 0; i < N; ++i) s[i] = 0.f;
-    if (c < cv)
-        for (int j = wave; j < HW; j += 4) {
+    if (c < cv) {
+        int j = wave;
+        for (; j + 12 < HW; j += 16) {  // four positions per round trip
+            Vec<DT> t[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) t[u].load(x, (n * HW + j + 4 * u) * cv + c);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int i = 0; i < N; ++i) s[i] += t[u].v[i];
+        }
+        for (; j < HW; j += 4) {
             Vec<DT> t;
             t.load(x, (n * HW + j) * cv + c);
 #pragma unroll
             for (int i = 0; i < N; ++i) s[i] += t.v[i];
         }
+    }
 #pragma unroll
     for (int i = 0; i < N; ++i) part[wave][lane][i] = s[i];
     __syncthreads();
@@ -247,20 +258,40 @@ __global__ __launch_bounds__(256) void fc_kernel(const float* __restrict__ v, co
     const float b = bias ? bias[o] : 0.f;
     const int n_begin = blockIdx.y * img_per_block;
     const int n_end = min(n_begin + img_per_block, Nimg);
-    for (int n = n_begin; n < n_end; ++n) {
-        float s = 0.f;
+    // Four images at a time: their eight vector loads are in flight together (one image per round
+    // trip made the kernel latency-bound), images past the end re-read the last one and are dropped.
+    constexpr int G = 4;
+    for (int n0 = n_begin; n0 < n_end; n0 += G) {
+        f32x4_t v0[G][CPL], v1[G][CPL];
 #pragma unroll
-        for (int j = 0; j < CPL; ++j) {
-            const f32x4_t* vp = (const f32x4_t*)(v + (size_t)n * Cin + j * 512 + lane * 8);
-            const f32x4_t v0 = vp[0], v1 = vp[1];
+        for (int g = 0; g < G; ++g) {
+            const int n = min(n0 + g, n_end - 1);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) s += wr[j][i] * v0[i];
+            for (int j = 0; j < CPL; ++j) {
+                const f32x4_t* vp = (const f32x4_t*)(v + (size_t)n * Cin + j * 512 + lane * 8);
+                v0[g][j] = vp[0];
+                v1[g][j] = vp[1];
+            }
+        }
+        float s[G];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) s += wr[j][4 + i] * v1[i];
+        for (int g = 0; g < G; ++g) {
+            s[g] = 0.f;
+#pragma unroll
+            for (int j = 0; j < CPL; ++j) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) s[g] += wr[j][i] * v0[g][j][i];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) s[g] += wr[j][4 + i] * v1[g][j][i];
+            }
         }
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
-        if (lane == 0) y[(size_t)n * Cout + o] = s + b;
+        for (int off = 32; off >= 1; off >>= 1)
+#pragma unroll
+            for (int g = 0; g < G; ++g) s[g] += __shfl_xor(s[g], off, 64);
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+            if (lane == 0 && n0 + g < n_end) y[(size_t)(n0 + g) * Cout + o] = s[g] + b;
     }
 }
 
@@ -357,7 +388,7 @@ int launch_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void* x
     SGPRS_HIP(hipGetLastError());
     PROF_END();
 
-    const int img_per_block = 16;
+    const int img_per_block = 8;
     const dim3 grid((cout + 3) / 4, (n + img_per_block - 1) / img_per_block);
     const int cpl = cin / 512;
     PROF_BEGIN(kKindFc, dtype, 2.0 * n * cin * cout, (double)cin * cout * es + (double)n * (cin + cout) * 4);
