@@ -167,11 +167,14 @@ int sgprs_conv2d(const sgprs_conv_desc_t *d, const void *x, const void *w_packed
                  const float *scale, const float *shift, const void *residual, void *y,
                  void *workspace, size_t workspace_bytes, sgprs_pool_t *pool, int partition);
 /* Measurement hook, process-wide, not thread-safe: which convolution kernel
- * sgprs_conv2d and the stages pick for 3x3 stride-1 bf16 layers.  kind -1:
- * automatic (default); 0: implicit GEMM only; 1: the LDS-patch kernel with the
+ * sgprs_conv2d and the stages pick for 3x3 bf16 layers.  kind -1: automatic
+ * (default); 0: implicit GEMM only; 1: the stride-1 LDS-patch kernel with the
  * given tile variant (0..11) and split factor where the shape allows it; 2:
  * automatic, but implicit-GEMM launches use tile variant `variant` (0..3)
- * wherever it divides cout, with split-K factor `splits` (0: planner's choice). */
+ * wherever it divides cout, with split-K factor `splits` (0: planner's choice);
+ * 3: automatic, plus the stride-2 LDS-patch kernel (not chosen otherwise) with
+ * tile variant `variant` (0: 256 rows, 1: 128 rows) wherever the shape allows
+ * it; variant 2 switches it off again. */
 int sgprs_conv_tuning_override(int kind, int variant, int splits);
 /* Max pooling 3x3, stride 2, pad 1 (padding never wins): [n][h][w][c] ->
  * [n][(h-1)/2+1][(w-1)/2+1][c].  c % 8 == 0 (bf16) or c % 4 == 0 (fp32). */
@@ -242,7 +245,8 @@ const void *sgprs_task_stage_output(const sgprs_task_t *task, int stage);
  * per launch: HOST arrays of length *count (in: capacity).  kind: 0 conv
  * implicit GEMM, 1 stem conv, 2 split-K reduce, 3 max-pool, 4 avg-pool, 5 FC,
  * 6 BN+ReLU, 7 add+ReLU, 8 LDS-patch 3x3 conv, 9 fused stem conv + max-pool,
- * 10 two implicit-GEMM convolutions of one input in a single launch.
+ * 10 two implicit-GEMM convolutions of one input in a single launch, 11 the
+ * stride-2 LDS-patch 3x3 conv (variant + 4: together with the 1x1 shortcut).
  * flops/bytes are the algorithmic work of the launch. */
 int sgprs_task_set_profiling(sgprs_task_t *task, int on);
 int sgprs_task_kernel_times(sgprs_task_t *task, int stage, int *count, int *kind, int *variant,

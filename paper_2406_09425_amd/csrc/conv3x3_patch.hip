@@ -60,7 +60,7 @@ __device__ __forceinline__ unsigned fdiv(unsigned x, unsigned magic) { return __
 // the input patches stream through.
 constexpr int kRowTilePerDieMaxBlocks = 4;
 struct PatchItem { int split, ntile, mtile; bool valid; };
-__device__ __forceinline__ PatchItem decode_item(const PatchArgs& a, int item)
+template <class Args> __device__ __forceinline__ PatchItem decode_item(const Args& a, int item)
 {
     PatchItem r;
     if (a.xcd_groups > 0) {
@@ -423,6 +423,7 @@ __global__ __launch_bounds__((NW * 64), (PatchCfg<BM, BN, KC, NW>::WAVES_PER_SIM
 // With two chunks and one channel block (64 -> 64 layers) all weights stay
 // resident (STAT) and only the patch is double buffered.
 constexpr int kPatchCap512 = 672;  // patch capacity (pixels) of the 512-row tile
+__host__ __device__ constexpr int s2_patch_cap(int bm) { return bm == 256 ? 1344 : 704; }  // stride-2 kernel: four parity planes
 __device__ __forceinline__ unsigned dl_swz(unsigned p) { return ((p >> 3) & 1u) | ((p >> 1) & 2u); }
 // The same with 16-channel chunks (32-byte pixels, two slots): slot s holds group s ^ ((p >> 3) & 1),
 // conflict-free for 16 consecutive pixels of one group and for 8 pixels x both groups.
@@ -778,6 +779,288 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
 #endif
 }
 
+// ---- stride-2 variant -------------------------------------------------------------
+// 3x3 stride-2 pad-1 (the first convolution of a down-sampling block), optionally
+// together with the block's shortcut, a 1x1 stride-2 convolution of the same
+// input: the shortcut's operand x[2p][2q] is the 3x3's centre tap, so it costs
+// one more k-step per chunk on a second accumulator and no loads of x at all.
+// As an implicit GEMM these layers move 15-30 KB from the L2 per MFLOP and are
+// bound by that; the patch moves 12-17.
+//
+// The patch is kept as four parity planes: extended row e (one zero row above
+// every image, one unused row below, so that an image is H + 2 = even rows) and
+// extended column c go to plane (e & 1, c & 1), position (e >> 1, c >> 1).
+// Output (p, q), tap (r, s) needs extended (2p + r, 2q + s), i.e. plane
+// (r & 1, s & 1) at (p + (r >> 1), q + (s >> 1)): consecutive output pixels read
+// consecutive plane pixels, exactly as with stride 1, and the same swizzle
+// applies.  In half-row units an output row g = n * Ho + p sits at
+// hb(g) = g + g / Ho; a run of output rows needs plane rows hb(g0) .. hb(g1) + 1.
+// Chunks are 16 channels (a 256-pixel tile's patch is 1100-1350 pixels).
+struct S2Args {
+    const unsigned char* x;
+    const unsigned char* w;
+    const unsigned char* w2;  // shortcut weights [Cout][Cin], or nullptr
+    unsigned char* y;
+    unsigned char* y2;
+    const float* scale;
+    const float* shift;
+    const float* scale2;
+    const float* shift2;
+    int H, W, Cin, Cout, Ho, Wo, NHo;  // NHo = N * Ho output rows in total
+    int PWh, HE;                       // Wo + 1, H + 2
+    unsigned mWo, mPWh, mHE, mHo;      // ceil(2^32/d) multipliers for exact division
+    int TR, n_mtiles, n_ntiles, n_chunks, splits, xcd_groups, n_slots, relu;
+    unsigned x_bytes, w_bytes, w2_bytes;
+};
+
+template <int BM, int NW, bool PAIR>
+__global__ __launch_bounds__(NW * 64, 1) void conv3x3s2_patch_kernel(const S2Args a)
+{
+#if __HIP_DEVICE_COMPILE__
+    constexpr int BN = 64, NT = NW * 64, KC = 16, PB = 32, SL = 2;
+    static_assert((BM == 256 && NW == 8) || (BM == 128 && NW == 4), "tile shapes");
+    constexpr int WMW = NW == 8 ? 8 : BM / 64, WNW = NW / WMW, WTM = BM / WMW, WTN = BN / WNW, TM = WTM / 32, TN = WTN / 32;
+    constexpr int PCAP_PIX = s2_patch_cap(BM), PPL = PCAP_PIX / 4;  // pixels per parity plane
+    static_assert(PPL % 16 == 0, "plane pitch keeps the swizzle phase");
+    constexpr int P_UNITS = PCAP_PIX * SL, W_UNITS = BN * 9 * SL, W2_UNITS = PAIR ? BN * SL : 0;
+    constexpr int P_IT = (P_UNITS + NT - 1) / NT, W_IT = (W_UNITS + NT - 1) / NT, W2_IT = PAIR ? 1 : 0;
+    constexpr int P_BYTES = PCAP_PIX * PB, W_BYTES = BN * 9 * PB, W2_BYTES = BN * PB, WROW = 9 * PB;
+    constexpr int STAGE = P_BYTES + W_BYTES + W2_BYTES, W_BASE = P_BYTES, W2_BASE = P_BYTES + W_BYTES;
+    constexpr int NSTEP = PAIR ? 10 : 9;                            // nine taps, then the shortcut on the centre tap's fragments
+    constexpr int SPS = (P_IT + W_IT + W2_IT + NSTEP - 1) / NSTEP;  // load slots per k-step
+    constexpr int SCR_ROWS = NW == 8 ? 16 : 32;
+    constexpr int SROW = WTN + 4, LPR = WTN / 8, RPP = 64 / LPR, NPASS = 32 / RPP;
+    static_assert(NW * SCR_ROWS * SROW * 4 <= P_BYTES, "epilogue scratch fits the patch area");
+    typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int wm = wave / WNW, wn = wave % WNW;
+
+    int item = blockIdx.x;
+    PatchItem cur = decode_item(a, item);
+    if (!cur.valid) return;
+
+    // weight loaders: 16-byte unit u is slot u % 2 of tap (u / 2) % 9 of row u / 18 (shortcut: slot u % 2 of row u / 2)
+    unsigned w_voff[W_IT], w2_voff = 0;
+#pragma unroll
+    for (int it = 0; it < W_IT; ++it) {
+        const unsigned u = it * NT + tid, row = u / (9 * SL), rem = u % (9 * SL);
+        w_voff[it] = ((row * 9 + rem / SL) * (unsigned)a.Cin + (((rem % SL) ^ dl_swz_sl<SL>(row)) * 8)) * 2u;
+    }
+    if constexpr (PAIR) w2_voff = ((unsigned)(tid / SL) * (unsigned)a.Cin + (((tid % SL) ^ dl_swz_sl<SL>(tid / SL)) * 8)) * 2u;
+    // patch loader: unit u is slot u % 2 of patch pixel u / 2 = plane pix / PPL, plane row and column from the rest
+    unsigned p_tab[P_IT];  // plane << 16 | plane row << 8 | plane column
+    unsigned p_grp[P_IT];
+#pragma unroll
+    for (int it = 0; it < P_IT; ++it) {
+        const unsigned u = it * NT + tid, pix = u / SL, pl = pix / PPL, rem = pix % PPL;
+        const unsigned prow = fdiv(rem, a.mPWh), pcol = rem - prow * a.PWh;
+        p_tab[it] = pl << 16 | prow << 8 | pcol;
+        p_grp[it] = (((u % SL) ^ dl_swz_sl<SL>(pix)) * 8) * 2u;
+    }
+    unsigned p_voff[P_IT], p_next[P_IT];
+    auto patch_offsets = [&](int mtile, unsigned (&voff)[P_IT]) {
+        const int g0 = mtile * a.TR;
+        const int g1 = min(g0 + a.TR, a.NHo) - 1;
+        const int hb0 = g0 + (int)fdiv(g0, a.mHo);
+        const int R2 = g1 + (int)fdiv(g1, a.mHo) - hb0 + 2;
+#pragma unroll
+        for (int it = 0; it < P_IT; ++it) {
+            const int pl = p_tab[it] >> 16, prow = (p_tab[it] >> 8) & 255, pcol = p_tab[it] & 255;
+            const int E = 2 * (hb0 + prow) + (pl >> 1);
+            const int n = fdiv(E, a.mHE);
+            const int hh = E - n * a.HE - 1;
+            const int ww = 2 * pcol + (pl & 1) - 1;
+            const bool ok = pl < 4 && prow < R2 && (unsigned)hh < (unsigned)a.H && (unsigned)ww < (unsigned)a.W;
+            voff[it] = ok ? ((unsigned)((n * a.H + hh) * a.W + ww) * (unsigned)a.Cin) * 2u + p_grp[it] : 0x80000000u;
+        }
+    };
+    // One load slot of the step (chunk, channel block ntile, patch offsets voff) into stage `stage`.
+    auto issue_slot = [&](int k, int stage, const unsigned (&voff)[P_IT], int ntile, int chunk, bool live) {
+        unsigned char* st = smem + stage * STAGE;
+        if (k < P_IT) {
+            if (k * NT + wave * 64 < P_UNITS) {
+                const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.x, 0, live ? (int)a.x_bytes : 0, 0x00020000);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr_t)(st + (k * NT + wave * 64) * 16), 16, voff[k < P_IT ? k : 0],
+                                                         chunk * KC * 2, 0, 0);
+            }
+        } else if (k < P_IT + W_IT) {
+            const int kk = k - P_IT;
+            if (kk * NT + wave * 64 < W_UNITS) {
+                const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, live ? (int)a.w_bytes : 0, 0x00020000);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr_t)(st + W_BASE + (kk * NT + wave * 64) * 16), 16,
+                                                         w_voff[kk >= 0 && kk < W_IT ? kk : 0], (ntile * BN * 9 * a.Cin + chunk * KC) * 2, 0, 0);
+            }
+        } else if (PAIR && k == P_IT + W_IT) {
+            if (wave * 64 < W2_UNITS) {
+                const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.w2, 0, live ? (int)a.w2_bytes : 0, 0x00020000);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr_t)(st + W2_BASE + wave * 64 * 16), 16, w2_voff,
+                                                         (ntile * BN * a.Cin + chunk * KC) * 2, 0, 0);
+            }
+        }
+    };
+
+    patch_offsets(cur.mtile, p_voff);
+#pragma unroll
+    for (int k = 0; k < P_IT + W_IT + W2_IT; ++k) issue_slot(k, 0, p_voff, cur.ntile, 0, true);
+
+    const int c8 = (lane % LPR) * 8, rsub = lane / LPR;
+    const unsigned wrow = wn * WTN + frow;
+    const unsigned wb = wrow * WROW + ((fhalf ^ dl_swz_sl<SL>(wrow)) << 4);
+    const unsigned wb2 = wrow * PB + ((fhalf ^ dl_swz_sl<SL>(wrow)) << 4);
+
+    bool first_item = true;
+    for (;;) {
+        const int g0 = cur.mtile * a.TR;
+        const int rows_here = min(a.TR, a.NHo - g0);
+        const int m_lim = rows_here * a.Wo;
+        const int nbase = cur.ntile * BN + wn * WTN + c8;
+        unsigned aoff[TM][9];
+        {
+            const int hb0 = g0 + (int)fdiv(g0, a.mHo);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int tt = wm * WTM + i * 32 + frow;
+                const int pr = fdiv(tt, a.mWo), q = tt - pr * a.Wo;
+                const bool ok = pr < rows_here;
+                const int g = g0 + (ok ? pr : 0);
+                const int rowb = g + (int)fdiv(g, a.mHo) - hb0;
+#pragma unroll
+                for (int tap = 0; tap < 9; ++tap) {
+                    const int r = tap / 3, sx = tap % 3;
+                    const unsigned p = ((r & 1) * 2 + (sx & 1)) * PPL + (rowb + (r >> 1)) * a.PWh + (ok ? q : 0) + (sx >> 1);
+                    aoff[i][tap] = p * PB + ((fhalf ^ dl_swz_sl<SL>(p)) << 4);
+                }
+            }
+        }
+        f32x16_t acc[TM][TN], acc2[PAIR ? TM : 1][PAIR ? TN : 1];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    acc[i][j][e] = 0.f;
+                    if constexpr (PAIR) acc2[i][j][e] = 0.f;
+                }
+
+        const PatchItem nxt = decode_item(a, item + (int)gridDim.x);
+        if (nxt.valid) patch_offsets(nxt.mtile, p_next);
+
+        if (first_item) {
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+            first_item = false;
+        }
+
+        auto step = [&](auto BUFC, int chunk) {
+            constexpr int BUF = decltype(BUFC)::value;
+            const bool last = BUF == 1 && chunk == a.n_chunks - 1;
+            const bool live = !last || nxt.valid;
+            if (last && nxt.valid) {
+#pragma unroll
+                for (int it = 0; it < P_IT; ++it) p_voff[it] = p_next[it];
+            }
+            const int chunk1 = last ? 0 : chunk + 1;
+            const int ntile1 = last ? nxt.ntile : cur.ntile;
+            const unsigned char* pbuf = smem + BUF * STAGE;
+            const unsigned char* wbuf = pbuf + W_BASE;
+            constexpr int AHEAD = 2, SETS = AHEAD + 1;
+            u32x4_t fa[SETS][TM], fb[SETS][TN];
+            auto load_frags = [&](int set, int st) {
+                const int tap = st < 9 ? st : 4;
+#pragma unroll
+                for (int i = 0; i < TM; ++i) fa[set][i] = *(const u32x4_t*)(pbuf + aoff[i][tap]);
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    fb[set][j] = st < 9 ? *(const u32x4_t*)(wbuf + wb + j * 32 * WROW + tap * PB)
+                                        : *(const u32x4_t*)(pbuf + W2_BASE + wb2 + j * 32 * PB);
+            };
+#pragma unroll
+            for (int q = 0; q < AHEAD; ++q) load_frags(q, q);
+#pragma unroll
+            for (int st = 0; st < NSTEP; ++st) {
+                __builtin_amdgcn_sched_barrier(0);
+                if (st + AHEAD < NSTEP) load_frags((st + AHEAD) % SETS, st + AHEAD);
+#pragma unroll
+                for (int k = st * SPS; k < (st + 1) * SPS; ++k) issue_slot(k, BUF ^ 1, p_voff, ntile1, chunk1, live);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        if (st < 9)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                __builtin_bit_cast(bf16x8_t, fa[st % SETS][i]), __builtin_bit_cast(bf16x8_t, fb[st % SETS][j]),
+                                acc[i][j], 0, 0, 0);
+                        else if constexpr (PAIR)
+                            acc2[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                __builtin_bit_cast(bf16x8_t, fa[st % SETS][i]), __builtin_bit_cast(bf16x8_t, fb[st % SETS][j]),
+                                acc2[i][j], 0, 0, 0);
+                    }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+        };
+        for (int chunk = 0; chunk < a.n_chunks; chunk += 2) {
+            step(std::integral_constant<int, 0>{}, chunk);
+            step(std::integral_constant<int, 1>{}, chunk + 1);
+        }
+
+        {   // epilogue through the patch area of stage 1 (the next item's first step sits in stage 0)
+            float* scr = (float*)(smem + STAGE) + wave * SCR_ROWS * SROW;
+            auto write_out = [&](f32x16_t (&av)[TM][TN], const float* scale, const float* shift, unsigned char* y, bool relu) {
+                const f32x4_t sc0 = *(const f32x4_t*)(scale + nbase), sc1 = *(const f32x4_t*)(scale + nbase + 4);
+                const f32x4_t sh0 = *(const f32x4_t*)(shift + nbase), sh1 = *(const f32x4_t*)(shift + nbase + 4);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int h = 0; h < 32 / SCR_ROWS; ++h) {
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+#pragma unroll
+                            for (int e = 0; e < 16; ++e)
+                                if (SCR_ROWS == 32 || (e >> 3) == h)
+                                    scr[(8 * (e >> 2) + 4 * fhalf + (e & 3) - h * SCR_ROWS) * SROW + j * 32 + frow] = av[i][j][e];
+#pragma unroll
+                        for (int pp = 0; pp < SCR_ROWS / RPP; ++pp) {
+                            const int pass = h * (SCR_ROWS / RPP) + pp;
+                            const int rr = pp * RPP + rsub;
+                            const int tt = wm * WTM + i * 32 + pass * RPP + rsub;
+                            f32x4_t v0 = *(const f32x4_t*)(scr + rr * SROW + c8);
+                            f32x4_t v1 = *(const f32x4_t*)(scr + rr * SROW + c8 + 4);
+                            if (tt < m_lim) {
+                                const size_t m = (size_t)g0 * a.Wo + tt;
+                                v0 = v0 * sc0 + sh0;
+                                v1 = v1 * sc1 + sh1;
+                                float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+                                u32x4_t ov;
+#pragma unroll
+                                for (int u = 0; u < 4; ++u) {
+                                    float lo = v[2 * u], hi = v[2 * u + 1];
+                                    if (relu) { lo = fmaxf(lo, 0.f); hi = fmaxf(hi, 0.f); }
+                                    const __bf16 l16 = (__bf16)lo, h16 = (__bf16)hi;
+                                    ov[u] = (unsigned)__builtin_bit_cast(unsigned short, l16) |
+                                            ((unsigned)__builtin_bit_cast(unsigned short, h16) << 16);
+                                }
+                                *(u32x4_t*)(y + (m * a.Cout + nbase) * 2) = ov;
+                            }
+                        }
+                    }
+            };
+            write_out(acc, a.scale, a.shift, a.y, a.relu != 0);
+            if constexpr (PAIR) write_out(acc2, a.scale2, a.shift2, a.y2, false);
+        }
+        if (!nxt.valid) break;
+        __syncthreads();
+        item += gridDim.x;
+        cur = nxt;
+    }
+#endif
+}
+
 // ---- host side ---------------------------------------------------------------
 static unsigned magic_for(unsigned d) { return (unsigned)((0x100000000ull + d - 1) / d); }
 
@@ -820,7 +1103,27 @@ bool patch_eligible(const sgprs_conv_desc_t& d)
 }
 
 // Fills the tile geometry of variant v for this shape; false if it does not fit.
+static bool patch_geometry_uncached(const sgprs_conv_desc_t& d, int v, int splits, PatchArgs* a);
 static bool patch_geometry(const sgprs_conv_desc_t& d, int v, int splits, PatchArgs* a)
+{
+    struct Key { sgprs_conv_desc_t d; int v, splits; };
+    struct Val { bool ok; PatchArgs a; };
+    static thread_local PlanMemo<Key, Val, 512> memo;
+    Key k;
+    memset(&k, 0, sizeof(k));
+    k.d = d; k.v = v; k.splits = splits;
+    const Val* hit = memo.find(k);
+    if (!hit) {
+        Val nv;
+        memset(&nv, 0, sizeof(nv));
+        nv.ok = patch_geometry_uncached(d, v, splits, &nv.a);
+        memo.put(k, nv);
+        hit = memo.find(k);
+    }
+    if (hit->ok) *a = hit->a;
+    return hit->ok;
+}
+static bool patch_geometry_uncached(const sgprs_conv_desc_t& d, int v, int splits, PatchArgs* a)
 {
     const PatchVariant& pv = kPatchVariants[v];
     if (d.cout % pv.bn || d.cin % pv.kc || d.w > pv.bm) return false;
@@ -1016,6 +1319,145 @@ int launch_conv3x3_patch(const sgprs_conv_desc_t& d, int variant, int splits, co
             return rc;
         if (prof && prof->on && (rc = prof->end(stream))) return rc;
     }
+    return SGPRS_OK;
+}
+
+// ---- stride-2 variant: host side ---------------------------------------------------
+struct S2Variant { int bm, nw; };
+static const S2Variant kS2Variants[] = {{256, 8}, {128, 4}};
+constexpr int kNumS2Variants = 2;
+static int g_s2_force = -1;  // -1 automatic, 0 / 1 that tile where the shape allows it, 2 never
+void s2patch_force(int v) { g_s2_force = v; }
+int s2patch_num_variants() { return kNumS2Variants; }
+
+// Name as a profiler prints it: v = tile variant + 4 * paired.
+const char* s2patch_variant_name(int v)
+{
+    static char buf[4][64];
+    static int next = 0;
+    if (v < 0 || (v & 3) >= kNumS2Variants) return "?";
+    char* out = buf[next++ & 3];
+    snprintf(out, 64, "conv3x3s2_patch_kernel<%d, %d, %s>", kS2Variants[v & 3].bm, kS2Variants[v & 3].nw, (v & 4) ? "true" : "false");
+    return out;
+}
+
+static bool s2patch_eligible(const sgprs_conv_desc_t& d)
+{
+    return d.dtype == SGPRS_BF16 && d.r == 3 && d.s == 3 && d.stride == 2 && d.pad == 1 && d.h % 2 == 0 && d.w % 2 == 0 &&
+           d.h >= 2 && d.w >= 2 && d.w <= 128 && d.h <= 252 && d.cin % 32 == 0 && d.cout % 64 == 0 &&
+           (long long)d.n * d.h * d.w * d.cin * 2 < (1ll << 31) && (long long)d.cout * 9 * d.cin * 2 < (1ll << 31) &&
+           (long long)d.n * (d.h + 2) * (d.h + 2) < (1ll << 30);
+}
+
+static bool s2patch_geometry_uncached(const sgprs_conv_desc_t& d, int v, S2Args* a);
+static bool s2patch_geometry(const sgprs_conv_desc_t& d, int v, S2Args* a)
+{
+    struct Key { sgprs_conv_desc_t d; int v; };
+    struct Val { bool ok; S2Args a; };
+    static thread_local PlanMemo<Key, Val, 64> memo;
+    Key k;
+    memset(&k, 0, sizeof(k));
+    k.d = d; k.v = v;
+    const Val* hit = memo.find(k);
+    if (!hit) {
+        Val nv;
+        memset(&nv, 0, sizeof(nv));
+        nv.ok = s2patch_geometry_uncached(d, v, &nv.a);
+        memo.put(k, nv);
+        hit = memo.find(k);
+    }
+    if (hit->ok) *a = hit->a;
+    return hit->ok;
+}
+static bool s2patch_geometry_uncached(const sgprs_conv_desc_t& d, int v, S2Args* a)
+{
+    const int bm = kS2Variants[v].bm;
+    const int Ho = d.h / 2, Wo = d.w / 2, NHo = d.n * Ho, PWh = Wo + 1;
+    if (Wo > bm) return false;
+    const int ppl = s2_patch_cap(bm) / 4;
+    int TR = bm / Wo, n_mtiles = 0;
+    for (; TR >= 1; --TR) {  // the most output rows per tile whose plane rows (one more than output rows, plus one per image border) fit
+        n_mtiles = (NHo + TR - 1) / TR;
+        int rmax = 0;
+        for (int t = 0; t < n_mtiles; ++t) {
+            const int g0 = t * TR, g1 = std::min(g0 + TR, NHo) - 1;
+            rmax = std::max(rmax, (g1 + g1 / Ho) - (g0 + g0 / Ho) + 2);
+        }
+        if (rmax * PWh <= ppl && rmax < 256) break;
+    }
+    if (TR < 1 || TR * Wo * 2 < bm) return false;  // a tile less than half full is left to the implicit GEMM
+    a->H = d.h; a->W = d.w; a->Cin = d.cin; a->Cout = d.cout; a->Ho = Ho; a->Wo = Wo; a->NHo = NHo;
+    a->PWh = PWh; a->HE = d.h + 2;
+    a->mWo = magic_for(Wo); a->mPWh = magic_for(PWh); a->mHE = magic_for(d.h + 2); a->mHo = magic_for(Ho);
+    a->TR = TR; a->n_mtiles = n_mtiles; a->n_ntiles = d.cout / 64; a->n_chunks = d.cin / 16; a->splits = 1;
+    a->relu = d.relu;
+    a->xcd_groups = (a->n_ntiles <= 8 && 8 % a->n_ntiles == 0) ? 8 / a->n_ntiles : 0;
+    a->n_slots = !a->xcd_groups ? n_mtiles * a->n_ntiles
+                 : a->n_ntiles <= kRowTilePerDieMaxBlocks ? (n_mtiles + 7) / 8 * 8 * a->n_ntiles
+                                                          : 8 * ((n_mtiles + a->xcd_groups - 1) / a->xcd_groups);
+    return true;
+}
+
+// The stride-2 kernel runs only when asked for (tuning override): measured at batch 64 on 256 CUs
+// it takes 25-28 / 20-23 / 26-28 us for the three down-sampling blocks of ResNet18 against
+// 24 / 22 / 24-26 us for the paired implicit GEMM.  Its patch moves fewer bytes from the L2, but in
+// 32-byte pieces (16 channels of every other pixel), and a step of nine or ten k-steps is too
+// short for its barrier; chunks of 32 channels would need 172 KB of LDS.
+bool plan_s2patch(const sgprs_conv_desc_t& d, int cus, int* variant)
+{
+    (void)cus;
+    if (g_s2_force < 0 || g_s2_force >= kNumS2Variants || !s2patch_eligible(d)) return false;
+    S2Args a;
+    if (!s2patch_geometry(d, g_s2_force, &a)) return false;
+    *variant = g_s2_force;
+    return true;
+}
+
+template <int BM, int NW>
+static int launch_s2_variant(const S2Args& a, int grid, hipStream_t stream)
+{
+    constexpr int kLds = 2 * (s2_patch_cap(BM) * 32 + 64 * 9 * 32 + 64 * 32);
+    static_assert(kLds <= 160 * 1024, "LDS of one CU");
+    static bool raised = false;
+    if (!raised) {
+        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3s2_patch_kernel<BM, NW, true>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
+        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3s2_patch_kernel<BM, NW, false>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
+        raised = true;
+    }
+    if (a.w2)
+        SGPRS_LAUNCH((conv3x3s2_patch_kernel<BM, NW, true>), dim3(grid), dim3(NW * 64), kLds, stream, a);
+    else
+        SGPRS_LAUNCH((conv3x3s2_patch_kernel<BM, NW, false>), dim3(grid), dim3(NW * 64), kLds, stream, a);
+    SGPRS_HIP(hipGetLastError());
+    return SGPRS_OK;
+}
+
+// d: the 3x3 stride-2 convolution; d2 (may be null): the 1x1 stride-2 shortcut on the same input.
+int launch_conv3x3s2_patch(const sgprs_conv_desc_t& d, int variant, const void* x, const void* w, const float* scale,
+                           const float* shift, void* y, const sgprs_conv_desc_t* d2, const void* w2, const float* scale2,
+                           const float* shift2, void* y2, hipStream_t stream, int cus, Profiler* prof)
+{
+    S2Args a;
+    if (variant < 0 || variant >= kNumS2Variants || !s2patch_eligible(d) || !s2patch_geometry(d, variant, &a))
+        return fail(SGPRS_ERR_INVALID_ARG, "internal: stride-2 patch plan does not match the shape");
+    if (d2 && (d2->dtype != d.dtype || d2->n != d.n || d2->h != d.h || d2->w != d.w || d2->cin != d.cin || d2->cout != d.cout ||
+               d2->r != 1 || d2->s != 1 || d2->stride != 2 || d2->pad != 0 || d2->relu))
+        return fail(SGPRS_ERR_INVALID_ARG, "internal: shortcut does not match the 3x3 convolution");
+    a.x = (const unsigned char*)x; a.w = (const unsigned char*)w; a.y = (unsigned char*)y;
+    a.scale = scale; a.shift = shift;
+    a.w2 = d2 ? (const unsigned char*)w2 : nullptr; a.y2 = (unsigned char*)y2; a.scale2 = scale2; a.shift2 = shift2;
+    a.x_bytes = (unsigned)((size_t)d.n * d.h * d.w * d.cin * 2); a.w_bytes = (unsigned)((size_t)d.cout * 9 * d.cin * 2);
+    a.w2_bytes = (unsigned)((size_t)d.cout * d.cin * 2);
+    int grid = (int)std::min<long long>(a.n_slots, (long long)cus);
+    if (a.xcd_groups && grid >= 8) grid -= grid % 8;
+    const double M = (double)a.NHo * a.Wo;
+    const double flops = 2.0 * M * d.cout * (9.0 + (d2 ? 1.0 : 0.0)) * d.cin;
+    const double bytes = ((double)d.n * d.h * d.w * d.cin + (double)d.cout * (9 + (d2 ? 1 : 0)) * d.cin + M * d.cout * (d2 ? 2 : 1)) * 2.0;
+    int rc;
+    if (prof && prof->on && (rc = prof->begin(stream, kKindS2Patch, variant + (d2 ? 4 : 0), flops, bytes))) return rc;
+    rc = variant == 0 ? launch_s2_variant<256, 8>(a, grid, stream) : launch_s2_variant<128, 4>(a, grid, stream);
+    if (rc) return rc;
+    if (prof && prof->on && (rc = prof->end(stream))) return rc;
     return SGPRS_OK;
 }
 

@@ -529,11 +529,15 @@ int launch_conv(const sgprs_conv_desc_t& d, const void* x, const void* w, const 
                 const float* shift, const void* residual, void* y, void* ws, size_t ws_bytes,
                 hipStream_t stream, int cus, Profiler* prof)
 {
-    const ConvPlan p = plan_conv(d, cus);
+    const ConvPlan p = plan_conv(d, cus, residual != nullptr);
     if (p.bm == 0) return fail(SGPRS_ERR_UNSUPPORTED, "no tile shape fits cout %d", d.cout);
     if (p.kind == 1)
         return launch_conv3x3_patch(d, p.variant, p.splits, x, w, scale, shift, residual, y, ws, ws_bytes, stream, cus,
                                     prof);
+    if (p.kind == 2) {
+        return launch_conv3x3s2_patch(d, p.variant, x, w, scale, shift, y, nullptr, nullptr, nullptr, nullptr, nullptr, stream, cus,
+                                      prof);
+    }
     const size_t need = conv_workspace_bytes(d, p);
     if (need > ws_bytes || (need && !ws))
         return fail(SGPRS_ERR_INVALID_ARG, "split-K workspace %zu bytes needed, %zu given", need, ws_bytes);

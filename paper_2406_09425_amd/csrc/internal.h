@@ -9,6 +9,8 @@
 #include <cstdint>
 #include <cstdio>
 #include <string>
+#include <cstring>
+#include <utility>
 #include <vector>
 
 #include "sgprs.h"
@@ -85,9 +87,34 @@ inline bool is_igemm(const sgprs_conv_desc_t& d)
 int check_conv_desc(const sgprs_conv_desc_t* d);
 inline int out_dim(int in, int k, int stride, int pad) { return (in + 2 * pad - k) / stride + 1; }
 
+// Small per-thread memo for launch planning: the same few shapes are planned again on every
+// launch, and the geometry searches behind a plan walk all row tiles.  Keys are plain structs
+// compared bytewise (fill them with memset first); the oldest entries are dropped.
+template <class K, class V, int CAP = 128> struct PlanMemo {
+    std::vector<std::pair<K, V>> items;
+    const V* find(const K& k)
+    {
+        for (size_t i = 0; i < items.size(); ++i)
+            if (!memcmp(&items[i].first, &k, sizeof(K))) {
+                if (i >= 8) {  // entries in use drift to the front
+                    std::swap(items[i], items[i / 2]);
+                    i /= 2;
+                }
+                return &items[i].second;
+            }
+        return nullptr;
+    }
+    void put(const K& k, const V& v)
+    {
+        if ((int)items.size() >= CAP) items.erase(items.begin(), items.begin() + CAP / 2);
+        items.emplace_back(k, v);
+    }
+};
+extern int g_plan_generation;  // bumped whenever a tuning override changes what the planners return
+
 // Tile configuration of one implicit-GEMM launch.
 struct ConvPlan {
-    int kind = 0;      // 0: implicit GEMM, 1: LDS-patch 3x3 kernel
+    int kind = 0;      // 0: implicit GEMM, 1: LDS-patch 3x3 kernel, 2: its stride-2 variant
     int variant = 0;   // index into the kernel's tile table
     int bm = 0, bn = 0;
     int splits = 1;    // split-K factor (grid.z)
@@ -96,7 +123,8 @@ struct ConvPlan {
 };
 // Chooses tile shape and split-K factor from the GEMM shape and the CU count of
 // the partition the launch will run on.
-ConvPlan plan_conv(const sgprs_conv_desc_t& d, int partition_cus);
+// (has_residual: kernels without a residual input are left out).
+ConvPlan plan_conv(const sgprs_conv_desc_t& d, int partition_cus, bool has_residual = false);
 size_t conv_workspace_bytes(const sgprs_conv_desc_t& d, const ConvPlan& p);
 
 struct KernelRecord {
@@ -128,7 +156,7 @@ struct Profiler {
 
 enum KernelKind { kKindIgemm = 0, kKindStem = 1, kKindReduce = 2, kKindMaxpool = 3, kKindAvgpool = 4,
                   kKindFc = 5, kKindBnRelu = 6, kKindAdd = 7, kKindPatch = 8, kKindStemPool = 9,
-                  kKindIgemmPair = 10 };
+                  kKindIgemmPair = 10, kKindS2Patch = 11 };
 
 // launchers (device pointers; validated by callers)
 int launch_conv(const sgprs_conv_desc_t& d, const void* x, const void* w, const float* scale,
@@ -161,6 +189,14 @@ int launch_conv3x3_patch(const sgprs_conv_desc_t& d, int variant, int splits, co
                          size_t ws_bytes, hipStream_t stream, int cus, Profiler* prof);
 int launch_splitk_reduce(int dtype, const float* partial, int splits, size_t total, int cout, const float* scale,
                          const float* shift, const void* res, void* y, int relu, hipStream_t stream);
+// LDS-patch 3x3 stride-2 kernel (bf16), alone or together with the block's 1x1 stride-2 shortcut
+bool plan_s2patch(const sgprs_conv_desc_t& d, int cus, int* variant);
+void s2patch_force(int v);
+int s2patch_num_variants();
+const char* s2patch_variant_name(int variant);
+int launch_conv3x3s2_patch(const sgprs_conv_desc_t& d, int variant, const void* x, const void* w, const float* scale,
+                           const float* shift, void* y, const sgprs_conv_desc_t* d2, const void* w2, const float* scale2,
+                           const float* shift2, void* y2, hipStream_t stream, int cus, Profiler* prof);
 // tuning override: kind -1 automatic, 0 implicit GEMM only, 1 force patch (variant, splits)
 extern int g_conv_force_kind;
 extern int g_igemm_force_variant, g_igemm_force_splits;

@@ -56,7 +56,24 @@ int g_conv_force_kind = -1;
 int g_igemm_force_variant = -1;
 int g_igemm_force_splits = 0;
 
-ConvPlan plan_conv(const sgprs_conv_desc_t& d, int cus)
+int g_plan_generation = 0;
+
+static ConvPlan plan_conv_uncached(const sgprs_conv_desc_t& d, int cus, bool has_residual);
+
+ConvPlan plan_conv(const sgprs_conv_desc_t& d, int cus, bool has_residual)
+{
+    struct Key { sgprs_conv_desc_t d; int cus, res, gen; };
+    static thread_local PlanMemo<Key, ConvPlan> memo;
+    Key k;
+    memset(&k, 0, sizeof(k));
+    k.d = d; k.cus = cus; k.res = has_residual; k.gen = g_plan_generation;
+    if (const ConvPlan* hit = memo.find(k)) return *hit;
+    const ConvPlan p = plan_conv_uncached(d, cus, has_residual);
+    memo.put(k, p);
+    return p;
+}
+
+static ConvPlan plan_conv_uncached(const sgprs_conv_desc_t& d, int cus, bool has_residual)
 {
     if (g_conv_force_kind != 0) {
         int v = 0, s = 1;
@@ -64,6 +81,12 @@ ConvPlan plan_conv(const sgprs_conv_desc_t& d, int cus)
             ConvPlan p;
             p.kind = 1; p.variant = v; p.splits = s;
             p.bm = 1;  // marks a valid plan
+            return p;
+        }
+        if (g_conv_force_kind != 1 && !has_residual && plan_s2patch(d, cus < 1 ? 1 : cus, &v)) {
+            ConvPlan p;
+            p.kind = 2; p.variant = v; p.splits = 1;
+            p.bm = 1;
             return p;
         }
     }
@@ -195,7 +218,9 @@ int sgprs_conv2d_workspace(const sgprs_conv_desc_t* d, int partition_cus, size_t
     if (rc) return rc;
     if (!bytes) return fail(SGPRS_ERR_INVALID_ARG, "bytes is NULL");
     if (partition_cus <= 0) return fail(SGPRS_ERR_INVALID_ARG, "partition_cus %d <= 0", partition_cus);
-    *bytes = is_stem(*d) ? 0 : conv_workspace_bytes(*d, plan_conv(*d, partition_cus));
+    // the plan may depend on whether a residual is passed: enough for either
+    *bytes = is_stem(*d) ? 0 : std::max(conv_workspace_bytes(*d, plan_conv(*d, partition_cus, false)),
+                                        conv_workspace_bytes(*d, plan_conv(*d, partition_cus, true)));
     return SGPRS_OK;
 }
 

@@ -93,7 +93,7 @@ size_t splitk_need(const sgprs_task* t, int first, int last, int batch, int cus)
         if (is_stem(t->conv[i].d)) continue;
         sgprs_conv_desc_t d = t->conv[i].d;
         d.n = batch;
-        need = std::max(need, conv_workspace_bytes(d, plan_conv(d, cus)));
+        need = std::max(need, std::max(conv_workspace_bytes(d, plan_conv(d, cus, false)), conv_workspace_bytes(d, plan_conv(d, cus, true))));
     }
     return need;
 }
@@ -140,7 +140,14 @@ int run_block(sgprs_task* t, int c1, int c2, int down, int batch, const void* x,
     if (down >= 0) {  // conv1 and the shortcut's 1x1 convolution read the same input: one launch when the plans allow
         sgprs_conv_desc_t d0 = t->conv[c1].d, d1 = t->conv[down].d;
         d0.n = d1.n = batch; d0.relu = 1; d1.relu = 0;
-        if ((rc = launch_conv_pair(d0, t->conv[c1].w, t->conv[c1].scale, t->conv[c1].shift, t->tmp[0], d1,
+        int sv = 0;
+        if (!d0.relu || d1.cout != d0.cout || !plan_s2patch(d0, cus, &sv)) sv = -1;
+        if (sv >= 0) {
+            if ((rc = launch_conv3x3s2_patch(d0, sv, x, t->conv[c1].w, t->conv[c1].scale, t->conv[c1].shift, t->tmp[0], &d1,
+                                             t->conv[down].w, t->conv[down].scale, t->conv[down].shift, t->tmp[1], s, cus, prof)))
+                return rc;
+            paired = true;
+        } else if ((rc = launch_conv_pair(d0, t->conv[c1].w, t->conv[c1].scale, t->conv[c1].shift, t->tmp[0], d1,
                                    t->conv[down].w, t->conv[down].scale, t->conv[down].shift, t->tmp[1], x, s, cus, prof,
                                    &paired)))
             return rc;
@@ -392,6 +399,7 @@ const char* sgprs_kernel_name(int kind, int variant)
         case kKindIgemm: return igemm_variant_name(variant);
         case kKindIgemmPair: return igemm_pair_variant_name(variant);
         case kKindPatch: return patch_variant_name(variant);
+        case kKindS2Patch: return s2patch_variant_name(variant);
         case kKindStem: return "conv_stem_kernel";
         case kKindStemPool: return variant == SGPRS_BF16 ? "stem_pool_kernel<1>" : "stem_pool_kernel<0>";
         case kKindReduce: return "splitk_reduce_kernel";

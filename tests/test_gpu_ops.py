@@ -238,6 +238,38 @@ def test_conv3x3_patch_variants_parity(pools, variant, shape):
         S.sgprs_conv_tuning_override(-1, 0, 1)
 
 
+S2_SHAPES = [
+    # n, h, w, cin, cout: several row tiles and image borders inside a tile, ragged last tile, 2-8 channel blocks
+    (9, 14, 14, 64, 128),
+    (3, 28, 28, 64, 128),
+    (2, 56, 56, 64, 128),
+    (20, 14, 14, 256, 512),
+    (5, 10, 6, 128, 192),
+    (7, 8, 12, 192, 64),
+]
+
+
+@pytest.mark.parametrize("variant", range(2))
+@pytest.mark.parametrize("shape", S2_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_conv3x3s2_patch_variants_parity(pools, variant, shape):
+    """The stride-2 patch kernel alone (no shortcut), both tile shapes, forced; shapes it
+    declines fall back to the implicit GEMM and must match just the same."""
+    n, h, w, cin, cout = shape
+    pool = pools["full"]
+    try:
+        S.sgprs_conv_tuning_override(3, variant, 1)
+        for relu in (True, False):
+            got, ref = conv_case(S.SGPRS_BF16, n, h, w, cin, cout, 3, 2, 1, relu=relu, with_res=False, seed=80 + variant,
+                                 pool=pool, cus=pool.partition_cus(0))
+            assert_close(got, ref, S.SGPRS_BF16, f"stride-2 patch variant {variant} relu {relu} {shape}")
+        # with a residual the planner must leave this kernel out (it has no residual input)
+        got, ref = conv_case(S.SGPRS_BF16, n, h, w, cin, cout, 3, 2, 1, relu=True, with_res=True, seed=83, pool=pool,
+                             cus=pool.partition_cus(0))
+        assert_close(got, ref, S.SGPRS_BF16, f"stride-2 with residual {shape}")
+    finally:
+        S.sgprs_conv_tuning_override(-1, 0, 1)
+
+
 def test_conv_planner_choices_agree(pools):
     """Automatic choice, implicit GEMM only and a forced patch variant give the
     same result to bf16 rounding on a batch large enough for the patch kernel."""

@@ -147,25 +147,33 @@ def test_task_run_across_partitions_matches_single_partition(cfg1):
 def test_downsample_block_runs_as_one_paired_launch(cfg1):
     """With enough tiles per CU nothing needs split-K, so the first convolution
     of a down-sampling block and the 1x1 convolution of its shortcut go out as
-    one launch (kind 10); the stages must still match the oracle."""
+    one launch: the paired implicit GEMM (kind 10), or, when asked for, the
+    stride-2 patch kernel with the shortcut on its centre tap (kind 11, bf16);
+    the stages must match the oracle every time."""
     params = cfg1[0]
     nb = 8
     x = make_input(1, 7, (nb, 3, 224, 224))
     _, outs = oracle.resnet18(params, BN_EPS, x, want_stages=True)
     pool = S.Pool(1, 8)   # 8 images on 8 CUs: no layer of stages 2-4 is split
-    for dtype in (S.SGPRS_F32, S.SGPRS_BF16):
-        task = S.Task(params, dtype, nb, BN_EPS)
-        task.set_profiling(True)
-        for j in (2, 3, 4):
-            xd = dev_nhwc(outs[j - 1], dtype)
-            o = dev_empty(stage_shape(j, nb), dtype)
-            task.stage_run(j, nb, xd.data_ptr(), o.data_ptr(), pool, 0)
-            pool.sync()
-            assert_close(host_nchw(o), outs[j], dtype, f"paired stage {j} dtype {dtype}")
-            kinds = [r["kind"] for r in task.kernel_times(j)]
-            assert kinds.count(10) == 1, (j, dtype, kinds)
-        task.destroy()
-    pool.destroy()
+    try:
+        for dtype, override, want in ((S.SGPRS_F32, (-1, 0, 1), 10), (S.SGPRS_BF16, (-1, 0, 1), 10),
+                                      (S.SGPRS_BF16, (3, 0, 1), 11), (S.SGPRS_BF16, (3, 1, 1), 11),
+                                      (S.SGPRS_BF16, (3, 2, 1), 10)):
+            S.sgprs_conv_tuning_override(*override)
+            task = S.Task(params, dtype, nb, BN_EPS)
+            task.set_profiling(True)
+            for j in (2, 3, 4):
+                xd = dev_nhwc(outs[j - 1], dtype)
+                o = dev_empty(stage_shape(j, nb), dtype)
+                task.stage_run(j, nb, xd.data_ptr(), o.data_ptr(), pool, 0)
+                pool.sync()
+                assert_close(host_nchw(o), outs[j], dtype, f"paired stage {j} dtype {dtype} override {override}")
+                kinds = [r["kind"] for r in task.kernel_times(j)]
+                assert kinds.count(want) == 1 and kinds.count(21 - want) == 0, (j, dtype, override, kinds)
+            task.destroy()
+    finally:
+        S.sgprs_conv_tuning_override(-1, 0, 1)
+        pool.destroy()
 
 
 # ------------------------------------------------------------- config 3
@@ -257,6 +265,6 @@ def test_kernel_times_records(full_pool, cfg1):
     for j in range(6):
         recs = task.kernel_times(j)
         assert recs and all(r["ms"] >= 0 for r in recs)
-        flops += sum(r["flops"] for r in recs if r["kind"] in (0, 1, 5, 8, 9, 10))
+        flops += sum(r["flops"] for r in recs if r["kind"] in (0, 1, 5, 8, 9, 10, 11))
     assert abs(flops - 2 * 1814073344) / (2 * 1814073344) < 1e-9
     task.destroy()
