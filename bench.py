@@ -249,6 +249,7 @@ def main():
         out["batch1_fp32"] = leg_batch1(S, hip, pool, stream, nhwc, torch, total_cus)
         out["cu_sweep"] = leg_sweep(S, hip, torch, total_cus, nhwc, with_cpu=not args.no_cpu)
         out["multi_tenant"] = leg_multi_tenant(S, hip, torch, total_cus, nhwc)
+        out["pool_scaling"] = leg_pool_scaling(S, torch, total_cus, nhwc)
         out["memory_bound_ops"] = leg_membound(S, hip, torch, pool, stream)
         out["oversubscribed_pool"] = leg_oversubscribed(S, torch, total_cus, nhwc, headline_ips=value)
     pool.destroy()
@@ -502,6 +503,44 @@ def leg_oversubscribed(S, torch, total_cus, nhwc, headline_ips, rounds=30):
     pool.destroy()
     return dict(instances=n_p, batch=n, partitions="2 x all CUs", ms_per_round=round(dt * 1e3, 4),
                 aggregate_images_per_s=round(ips, 1), vs_single_partition=round(ips / headline_ips, 3))
+
+
+def leg_pool_scaling(S, torch, total_cus, nhwc, instances=8, rounds=40):
+    """Eight bf16 batch-1 instances spread round-robin over pools of 1, 2, 3, 4 and 8 equal
+    partitions (the paper's question: how does throughput grow with the number of contexts?).
+    Every instance is issued with sgprs_task_run from one host thread, i.e. replayed as a HIP
+    graph after its second run: one host call per inference."""
+    from workloads import BN_EPS, make_input, make_resnet18_params
+    tasks, xs, lgs = [], [], []
+    for i in range(instances):
+        tasks.append(S.Task(make_resnet18_params(3, i, bf16=True), S.SGPRS_BF16, 1, BN_EPS))
+        xs.append(nhwc(make_input(3, i, (1, 3, 224, 224), bf16=True), torch.bfloat16))
+        lgs.append(torch.empty((1, 1000), dtype=torch.float32, device="cuda"))
+    res = []
+    for n_p in (1, 2, 3, 4, 8):
+        cus = total_cus // n_p // 8 * 8
+        pool = S.Pool(n_p, cus)
+
+        def issue():
+            for i in range(instances):
+                tasks[i].run(1, xs[i].data_ptr(), lgs[i].data_ptr(), pool, i % n_p)
+
+        for _ in range(5):
+            issue()
+        pool.sync()
+        t0 = time.perf_counter()
+        for _ in range(rounds):
+            issue()
+        t1 = time.perf_counter()
+        pool.sync()
+        t2 = time.perf_counter()
+        res.append(dict(partitions=n_p, partition_cus=cus, images_per_s=round(instances * rounds / (t2 - t0), 1),
+                        us_per_round=round((t2 - t0) / rounds * 1e6, 1), host_issue_us_per_round=round((t1 - t0) / rounds * 1e6, 1)))
+        log("pool_scaling", json.dumps(res[-1]))
+        pool.destroy()
+    for t in tasks:
+        t.destroy()
+    return res
 
 
 def leg_multi_tenant(S, hip, torch, total_cus, nhwc, n_p=8, rounds=30):

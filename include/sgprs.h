@@ -116,6 +116,12 @@ int sgprs_pool_sync(sgprs_pool_t *pool);
  * the mask-bit -> die mapping by measurement. */
 int sgprs_partition_probe(sgprs_pool_t *pool, int partition, int n_blocks, int spin_cycles,
                           uint32_t *out);
+/* Diagnostic: the same probe, but recorded into a HIP graph by stream capture
+ * and launched as a graph on the partition's stream (synchronous).  Shows
+ * whether graph launches keep to the partition's CUs, which sgprs_task_run
+ * relies on when it replays a captured task. */
+int sgprs_partition_probe_graph(sgprs_pool_t *pool, int partition, int n_blocks, int spin_cycles,
+                                uint32_t *out);
 /* Diagnostic: the sustained matrix-core rate of the partition.  One 512-thread
  * workgroup per CU runs `steps` (1..1e6) rounds of 18 k-steps; per k-step every
  * wavefront reads four 16-byte fragments per lane from LDS and issues four
@@ -232,7 +238,11 @@ int sgprs_stage_run(sgprs_task_t *task, int stage, int batch, const void *in, vo
  * otherwise HOST int[6] and consecutive stages on different partitions are
  * chained with events.  in: [batch][224][224][3]; logits: fp32 [batch][1000].
  * The call returns once everything is queued; completion is observed on the
- * last stage's partition. */
+ * last stage's partition.  When all stages run on one partition and per-kernel
+ * timing is off, the second call with the same (batch, in, logits, pool,
+ * partition) records the kernels into a HIP graph and later calls replay it:
+ * one host call per inference.  The buffers are read and written at replay
+ * time as usual; only the pointers are fixed. */
 int sgprs_task_run(sgprs_task_t *task, int batch, const void *in, float *logits,
                    sgprs_pool_t *pool, int partition, const int *partition_per_stage);
 /* DEVICE pointer to the task-owned buffer holding stage j's output (j in 0..4)

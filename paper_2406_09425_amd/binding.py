@@ -80,6 +80,7 @@ def lib():
         "sgprs_pool_sync": (c_int, [vp]),
         "sgprs_partition_probe": (c_int, [vp, c_int, c_int, c_int, vp]),
         "sgprs_mfma_probe": (c_int, [vp, c_int, c_int, c_int, vp]),
+        "sgprs_partition_probe_graph": (c_int, [vp, c_int, c_int, c_int, vp]),
         "sgprs_fold_bn": (c_int, [fp, fp, fp, fp, c_float, c_int, fp, fp]),
         "sgprs_conv_packed_weight_bytes": (c_int, [POINTER(ConvDesc), POINTER(c_size_t)]),
         "sgprs_pack_conv_weights": (c_int, [POINTER(ConvDesc), fp, vp, c_size_t]),
@@ -225,6 +226,9 @@ class Pool:
 
     def probe(self, p: int, n_blocks: int, spin_cycles: int, out_ptr: int) -> None:
         _check(lib().sgprs_partition_probe(self.handle, p, n_blocks, spin_cycles, out_ptr))
+
+    def probe_graph(self, p: int, n_blocks: int, spin_cycles: int, out_ptr: int) -> None:
+        _check(lib().sgprs_partition_probe_graph(self.handle, p, n_blocks, spin_cycles, out_ptr))
 
     def mfma_probe(self, p: int, random_data: bool, steps: int, out_ptr: int) -> None:
         _check(lib().sgprs_mfma_probe(self.handle, p, int(bool(random_data)), steps, out_ptr))

@@ -140,8 +140,14 @@ struct KernelRecord {
 // there is none: separately recorded event packets would add microseconds of
 // their own latency to every interval.
 extern thread_local hipEvent_t tl_start, tl_stop;
-#define SGPRS_LAUNCH(kernel, grid, block, lds, stream, ...) \
-    hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, ::sgprs::tl_start, ::sgprs::tl_stop, 0, __VA_ARGS__)
+// (Plain launches when no timing is attached: those are what stream capture records.)
+#define SGPRS_LAUNCH(kernel, grid, block, lds, stream, ...)                                                             \
+    do {                                                                                                                \
+        if (::sgprs::tl_start || ::sgprs::tl_stop)                                                                      \
+            hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, ::sgprs::tl_start, ::sgprs::tl_stop, 0, __VA_ARGS__); \
+        else                                                                                                            \
+            hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);                                          \
+    } while (0)
 struct Profiler {
     bool on = false;
     std::vector<KernelRecord> recs;      // records of the stage being run

@@ -279,6 +279,36 @@ int sgprs_partition_probe(sgprs_pool_t* pool, int partition, int n_blocks, int s
     return launch_probe(n_blocks, spin_cycles, out, s);
 }
 
+int sgprs_partition_probe_graph(sgprs_pool_t* pool, int partition, int n_blocks, int spin_cycles, uint32_t* out)
+{
+    hipStream_t s;
+    int c = 0;
+    int rc = resolve(pool, partition, &s, &c);
+    if (rc) return rc;
+    if (!out) return fail(SGPRS_ERR_INVALID_ARG, "out is NULL");
+    if (n_blocks <= 0 || n_blocks > 65536)
+        return fail(SGPRS_ERR_INVALID_ARG, "n_blocks %d outside [1,65536]", n_blocks);
+    if (spin_cycles < 0 || spin_cycles > 10000000)
+        return fail(SGPRS_ERR_INVALID_ARG, "spin_cycles %d outside [0,1e7]", spin_cycles);
+    SGPRS_HIP(hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+    rc = launch_probe(n_blocks, spin_cycles, out, s);
+    hipGraph_t g = nullptr;
+    const hipError_t e = hipStreamEndCapture(s, &g);
+    if (rc || e != hipSuccess || !g) {
+        (void)hipGetLastError();
+        if (g) (void)hipGraphDestroy(g);
+        return rc ? rc : fail(SGPRS_ERR_HIP, "stream capture failed: %s", hipGetErrorString(e));
+    }
+    hipGraphExec_t x = nullptr;
+    hipError_t e2 = hipGraphInstantiate(&x, g, nullptr, nullptr, 0);
+    if (e2 == hipSuccess) e2 = hipGraphLaunch(x, s);
+    if (e2 == hipSuccess) e2 = hipStreamSynchronize(s);
+    if (x) (void)hipGraphExecDestroy(x);
+    (void)hipGraphDestroy(g);
+    if (e2 != hipSuccess) return fail(SGPRS_ERR_HIP, "graph launch failed: %s", hipGetErrorString(e2));
+    return SGPRS_OK;
+}
+
 int sgprs_mfma_probe(sgprs_pool_t* pool, int partition, int random_data, int steps, uint64_t* out)
 {
     hipStream_t s;

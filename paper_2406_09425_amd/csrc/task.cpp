@@ -51,6 +51,21 @@ struct sgprs_task {
     sgprs::Profiler prof[SGPRS_RESNET18_STAGES];
     bool profiling = false;
     hipEvent_t chain[SGPRS_RESNET18_STAGES] = {};
+    // Whole-task launches with the same arguments are captured into a HIP graph the second time
+    // they are seen and replayed from then on (one host call instead of 20-33 kernel launches).
+    struct Replay {
+        int batch = 0, partition = 0;
+        const void* in = nullptr;
+        float* logits = nullptr;
+        const sgprs_pool_t* pool = nullptr;
+        hipStream_t stream = nullptr;
+        int generation = 0;  // tuning-override generation the capture was made under
+        int seen = 0;
+        hipGraph_t graph = nullptr;
+        hipGraphExec_t exec = nullptr;
+    };
+    std::vector<Replay> replays;
+    bool use_graphs = true;
 };
 
 namespace {
@@ -77,8 +92,17 @@ int upload(sgprs_task* t, const void* host, size_t bytes, void** out)
     return SGPRS_OK;
 }
 
+void drop_replay(sgprs_task::Replay& r)
+{
+    if (r.exec) (void)hipGraphExecDestroy(r.exec);
+    if (r.graph) (void)hipGraphDestroy(r.graph);
+    r.exec = nullptr;
+    r.graph = nullptr;
+}
+
 void destroy_task(sgprs_task* t)
 {
+    for (auto& r : t->replays) drop_replay(r);
     for (void* p : t->allocs) (void)hipFree(p);
     if (t->splitk) (void)hipFree(t->splitk);
     for (hipEvent_t e : t->chain)
@@ -339,6 +363,49 @@ int sgprs_task_run(sgprs_task_t* t, int batch, const void* in, float* logits, sg
     for (int j = 0; j < SGPRS_RESNET18_STAGES; ++j)
         if ((rc = resolve(pool, pps ? pps[j] : partition, &s[j], &cus[j]))) return rc;
     if (pool->device != t->device) return fail(SGPRS_ERR_INVALID_ARG, "pool and task live on different devices");
+
+    // ---- graph replay: one partition, no per-kernel timing ----
+    bool one_stream = true;
+    for (int j = 1; j < SGPRS_RESNET18_STAGES; ++j) one_stream = one_stream && s[j] == s[0];
+    sgprs_task::Replay* rp = nullptr;
+    if (t->use_graphs && one_stream && !t->profiling) {
+        for (auto& r : t->replays)
+            if (r.batch == batch && r.in == in && r.logits == logits && r.pool == pool && r.stream == s[0] &&
+                r.generation == g_plan_generation)
+                rp = &r;
+        if (!rp) {
+            if (t->replays.size() >= 8) {  // a handful of argument sets per task; the oldest goes
+                drop_replay(t->replays.front());
+                t->replays.erase(t->replays.begin());
+            }
+            sgprs_task::Replay r;
+            r.batch = batch; r.partition = partition; r.in = in; r.logits = logits; r.pool = pool; r.stream = s[0];
+            r.generation = g_plan_generation;
+            t->replays.push_back(r);
+            rp = &t->replays.back();
+        }
+        if (rp->exec) {
+            SGPRS_HIP(hipGraphLaunch(rp->exec, s[0]));
+            return SGPRS_OK;
+        }
+        ++rp->seen;
+    }
+    // The second sighting of an argument set is captured (the first ran eagerly, so every one-time
+    // set-up, allocation and attribute call is behind us); a failed capture switches replay off.
+    const bool capture = rp && rp->seen == 2;
+    if (capture) {
+        for (int j = 1; j <= 4 && !rc; ++j) {  // scratch must not grow while capturing
+            const int first = j == 1 ? 1 : 5 + 5 * (j - 2), last = j == 1 ? 4 : first + 4;
+            rc = ensure_splitk(t, splitk_need(t, first, last, batch, cus[j]), s[0]);
+        }
+        if (rc) return rc;
+        if (hipStreamBeginCapture(s[0], hipStreamCaptureModeThreadLocal) != hipSuccess) {
+            (void)hipGetLastError();
+            t->use_graphs = false;
+            rp = nullptr;
+        }
+    }
+    const bool capturing = capture && rp;
     for (int j = 0; j < SGPRS_RESNET18_STAGES; ++j) {
         if (j > 0 && s[j] != s[j - 1]) {
             SGPRS_HIP(hipEventRecord(t->chain[j], s[j - 1]));
@@ -350,9 +417,25 @@ int sgprs_task_run(sgprs_task_t* t, int batch, const void* in, float* logits, sg
         // kernel from the predecessor's last completion event
         hipEvent_t prev = nullptr;
         if (t->profiling && j > 0 && s[j] == s[j - 1] && !t->prof[j - 1].recs.empty()) prev = t->prof[j - 1].recs.back().stop;
-        if ((rc = run_stage(t, j, batch, src, dst, s[j], cus[j], prev))) return rc;
+        if ((rc = run_stage(t, j, batch, src, dst, s[j], cus[j], prev))) break;
     }
-    return SGPRS_OK;
+    if (capturing) {
+        hipGraph_t g = nullptr;
+        const hipError_t e = hipStreamEndCapture(s[0], &g);
+        hipGraphExec_t x = nullptr;
+        if (!rc && e == hipSuccess && g && hipGraphInstantiate(&x, g, nullptr, nullptr, 0) == hipSuccess) {
+            rp->graph = g;
+            rp->exec = x;
+            SGPRS_HIP(hipGraphLaunch(x, s[0]));
+            return SGPRS_OK;
+        }
+        (void)hipGetLastError();
+        if (g) (void)hipGraphDestroy(g);
+        t->use_graphs = false;  // nothing was executed while capturing: run this call eagerly
+        if (rc) return rc;
+        return sgprs_task_run(t, batch, in, logits, pool, partition, pps);
+    }
+    return rc;
 }
 
 const void* sgprs_task_stage_output(const sgprs_task_t* t, int stage)

@@ -112,3 +112,21 @@ def test_mfma_probe_checksum_and_errors():
     with pytest.raises(S.SgprsError):
         pool.mfma_probe(0, False, 10, 0)
     pool.destroy()
+
+
+def test_graph_launch_keeps_to_the_partition():
+    """A kernel recorded by stream capture and launched as a HIP graph on a partition's stream
+    runs on that partition's CUs only (sgprs_task_run replays captured tasks this way)."""
+    total = S.Pool(1, 8).info()["total_cus"]
+    pool = S.Pool(8, total // 8)
+    n_blocks = 4096
+    for p in (0, 3, 7):
+        sets = []
+        for graph in (False, True):
+            out = torch.zeros(2 * n_blocks, dtype=torch.int32, device="cuda")
+            (pool.probe_graph if graph else pool.probe)(p, n_blocks, 20000, out.data_ptr())
+            pool.sync(p)
+            a = out.cpu().numpy().astype(np.uint32).reshape(n_blocks, 2)
+            sets.append(set(zip((a[:, 0] & 0xF).tolist(), ((a[:, 1] >> 8) & 0x7F).tolist())))
+        assert sets[1] == sets[0] and len(sets[0]) == total // 8, (p, len(sets[0]), len(sets[1]))
+    pool.destroy()

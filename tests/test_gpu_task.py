@@ -252,6 +252,39 @@ def test_config4_batch64_bf16_sampled_against_oracle(full_pool):
     task.destroy()
 
 
+def test_task_run_graph_replay_matches_eager(full_pool, cfg1):
+    """sgprs_task_run captures a task into a HIP graph on the second call with the same arguments
+    and replays it afterwards.  Replays are interleaved with eager work on the same stream, with
+    changed input contents, and with synchronisations, and every one is compared with the eager
+    result (stage by stage through sgprs_stage_run, which never uses a graph)."""
+    params, x, _, _ = cfg1
+    for dtype in (S.SGPRS_F32, S.SGPRS_BF16):
+        task = S.Task(params, dtype, 1, BN_EPS)
+        xd = dev_nhwc(x, dtype)
+        x2 = dev_nhwc(make_input(1, 9, (1, 3, 224, 224)), dtype)
+        xin = torch.empty_like(xd)
+        lg = torch.full((1, 1000), float("nan"), dtype=torch.float32, device="cuda")
+        scratch = torch.zeros(1 << 20, dtype=torch.float32, device="cuda")
+        for it in range(8):
+            src = xd if it % 2 == 0 else x2
+            xin.copy_(src)
+            torch.cuda.synchronize()
+            # eager reference: the six stages one by one
+            ref = torch.full((1, 1000), float("nan"), dtype=torch.float32, device="cuda")
+            for j in range(6):
+                a = xin.data_ptr() if j == 0 else task.stage_output(j - 1)
+                b = ref.data_ptr() if j == 5 else task.stage_output(j)
+                task.stage_run(j, 1, a, b, full_pool, 0)
+            full_pool.sync()
+            lg.fill_(float("nan"))
+            scratch.add_(1.0)                      # unrelated eager work between the replays
+            torch.cuda.synchronize()
+            task.run(1, xin.data_ptr(), lg.data_ptr(), full_pool, 0)   # call 1 eager, call 2 captures, then replays
+            full_pool.sync()
+            assert torch.equal(lg, ref), (dtype, it)
+        task.destroy()
+
+
 # ------------------------------------------------------------- profiling hook
 def test_kernel_times_records(full_pool, cfg1):
     params, x, _, _ = cfg1
