@@ -129,6 +129,13 @@ int ensure_splitk(sgprs_task* t, size_t need, hipStream_t stream)
 {
     if (need <= t->splitk_bytes) return SGPRS_OK;
     SGPRS_HIP(hipStreamSynchronize(stream));
+    // captured graphs hold the old scratch pointer and go with it; they may have been launched on
+    // other streams, so the whole device is drained first (this path runs once per new shape)
+    if (!t->replays.empty()) {
+        SGPRS_HIP(hipDeviceSynchronize());
+        for (auto& r : t->replays) drop_replay(r);
+        t->replays.clear();
+    }
     if (t->splitk) SGPRS_HIP(hipFree(t->splitk));
     t->splitk = nullptr;
     t->splitk_bytes = 0;
@@ -369,6 +376,11 @@ int sgprs_task_run(sgprs_task_t* t, int batch, const void* in, float* logits, sg
     for (int j = 1; j < SGPRS_RESNET18_STAGES; ++j) one_stream = one_stream && s[j] == s[0];
     sgprs_task::Replay* rp = nullptr;
     if (t->use_graphs && one_stream && !t->profiling) {
+        // the split-K scratch must neither grow while capturing nor move under a captured graph
+        for (int j = 1; j <= 4; ++j) {
+            const int first = j == 1 ? 1 : 5 + 5 * (j - 2), last = j == 1 ? 4 : first + 4;
+            if ((rc = ensure_splitk(t, splitk_need(t, first, last, batch, cus[j]), s[0]))) return rc;
+        }
         for (auto& r : t->replays)
             if (r.batch == batch && r.in == in && r.logits == logits && r.pool == pool && r.stream == s[0] &&
                 r.generation == g_plan_generation)
@@ -394,11 +406,6 @@ int sgprs_task_run(sgprs_task_t* t, int batch, const void* in, float* logits, sg
     // set-up, allocation and attribute call is behind us); a failed capture switches replay off.
     const bool capture = rp && rp->seen == 2;
     if (capture) {
-        for (int j = 1; j <= 4 && !rc; ++j) {  // scratch must not grow while capturing
-            const int first = j == 1 ? 1 : 5 + 5 * (j - 2), last = j == 1 ? 4 : first + 4;
-            rc = ensure_splitk(t, splitk_need(t, first, last, batch, cus[j]), s[0]);
-        }
-        if (rc) return rc;
         if (hipStreamBeginCapture(s[0], hipStreamCaptureModeThreadLocal) != hipSuccess) {
             (void)hipGetLastError();
             t->use_graphs = false;

@@ -285,6 +285,37 @@ def test_task_run_graph_replay_matches_eager(full_pool, cfg1):
         task.destroy()
 
 
+def test_graph_replay_survives_other_batches_and_partitions(cfg1):
+    """Captured graphs must stay valid (or be rebuilt) when the same task later runs other batch
+    sizes or partitions, which may grow the split-K scratch the graphs point into."""
+    params, x, _, _ = cfg1
+    dtype = S.SGPRS_BF16
+    total = S.Pool(1, 8).info()["total_cus"]
+    pool = S.Pool(2, total // 2)
+    task = S.Task(params, dtype, 16, BN_EPS)
+    x1 = dev_nhwc(x, dtype)
+    xb = dev_nhwc(make_input(1, 11, (6, 3, 224, 224)), dtype)
+    l1 = torch.full((1, 1000), float("nan"), dtype=torch.float32, device="cuda")
+    lb = torch.full((6, 1000), float("nan"), dtype=torch.float32, device="cuda")
+    seen1, seenb = [], []
+    for rnd in range(3):
+        for _ in range(3):                      # eager, capture, replay
+            l1.fill_(float("nan"))
+            task.run(1, x1.data_ptr(), l1.data_ptr(), pool, 0)
+            pool.sync()
+            seen1.append(l1.clone())
+        for part in (1, 0):
+            for _ in range(3):
+                lb.fill_(float("nan"))
+                task.run(6, xb.data_ptr(), lb.data_ptr(), pool, part)
+                pool.sync()
+                seenb.append(lb.clone())
+    assert all(torch.equal(a, seen1[0]) for a in seen1) and bool(torch.isfinite(seen1[0]).all())
+    assert all(torch.equal(a, seenb[0]) for a in seenb) and bool(torch.isfinite(seenb[0]).all())
+    task.destroy()
+    pool.destroy()
+
+
 # ------------------------------------------------------------- profiling hook
 def test_kernel_times_records(full_pool, cfg1):
     params, x, _, _ = cfg1
