@@ -112,6 +112,29 @@ def test_workspace_planning_is_deterministic_and_bounded():
         S.sgprs_conv2d_workspace(S.ConvDesc(1, 8, 8, 64, 64, 3, 3, 1, 1, 0, 0), 0)
 
 
+def test_memoised_plans_follow_tuning_overrides():
+    """Plans are memoised; an override must not be answered from a stale entry.  A batch-1
+    14x14x256 layer is split over K by the planner (workspace > 0); forcing splits = 1 needs no
+    workspace; back to automatic gives the first answer again."""
+    d = S.ConvDesc(1, 14, 14, 256, 256, 3, 3, 1, 1, S.SGPRS_BF16, 1)
+    try:
+        auto = S.sgprs_conv2d_workspace(d, 256)
+        assert auto > 0
+        S.sgprs_conv_tuning_override(2, 2, 1)
+        assert S.sgprs_conv2d_workspace(d, 256) == 0
+        S.sgprs_conv_tuning_override(2, 2, 2)
+        two = S.sgprs_conv2d_workspace(d, 256)
+        assert two == 2 * 196 * 256 * 4
+        S.sgprs_conv_tuning_override(-1, 0, 1)
+        assert S.sgprs_conv2d_workspace(d, 256) == auto
+        with pytest.raises(S.SgprsError):
+            S.sgprs_conv_tuning_override(5, 0, 1)
+        with pytest.raises(S.SgprsError):
+            S.sgprs_conv_tuning_override(3, 7, 1)
+    finally:
+        S.sgprs_conv_tuning_override(-1, 0, 1)
+
+
 def test_no_device_is_an_error_not_a_crash():
     import torch
     if torch.cuda.is_available():
