@@ -238,9 +238,10 @@ int sgprs_stage_run(sgprs_task_t *task, int stage, int batch, const void *in, vo
  * otherwise HOST int[6] and consecutive stages on different partitions are
  * chained with events.  in: [batch][224][224][3]; logits: fp32 [batch][1000].
  * The call returns once everything is queued; completion is observed on the
- * last stage's partition.  When all stages run on one partition and per-kernel
- * timing is off, the second call with the same (batch, in, logits, pool,
- * partition) records the kernels into a HIP graph and later calls replay it:
+ * last stage's partition.  When all stages run on one partition, per-kernel
+ * timing is off and graph replay applies (sgprs_task_set_graph_replay), the
+ * second call with the same (batch, in, logits, pool, partition) records the
+ * kernels into a HIP graph and later calls replay it:
  * one host call per inference.  The buffers are read and written at replay
  * time as usual; only the pointers are fixed. */
 int sgprs_task_run(sgprs_task_t *task, int batch, const void *in, float *logits,
@@ -259,6 +260,12 @@ const void *sgprs_task_stage_output(const sgprs_task_t *task, int stage);
  * stride-2 LDS-patch 3x3 conv (variant + 4: together with the 1x1 shortcut).
  * flops/bytes are the algorithmic work of the launch. */
 int sgprs_task_set_profiling(sgprs_task_t *task, int on);
+/* Graph replay of sgprs_task_run (see there): mode 1 always, 0 never (every
+ * call enqueues its kernels one by one), -1 automatic (default): batches of up
+ * to 8 images.  A replay costs about 5 us of GPU time and saves 50-90 us of
+ * host time: it pays when one host thread feeds several partitions with short
+ * inferences.  Graphs already captured are kept. */
+int sgprs_task_set_graph_replay(sgprs_task_t *task, int mode);
 int sgprs_task_kernel_times(sgprs_task_t *task, int stage, int *count, int *kind, int *variant,
                             float *ms, double *flops, double *bytes);
 /* Name of the kernel instantiation behind (kind, variant), for matching

@@ -100,6 +100,7 @@ def lib():
         "sgprs_task_run": (c_int, [vp, c_int, vp, vp, vp, c_int, ip]),
         "sgprs_task_stage_output": (vp, [vp, c_int]),
         "sgprs_task_set_profiling": (c_int, [vp, c_int]),
+        "sgprs_task_set_graph_replay": (c_int, [vp, c_int]),
         "sgprs_task_kernel_times": (c_int, [vp, c_int, ip, ip, ip, fp, POINTER(c_double), POINTER(c_double)]),
         "sgprs_kernel_name": (c_char_p, [c_int, c_int]),
     }
@@ -324,6 +325,10 @@ class Task:
         if not p:
             raise SgprsError(-1, sgprs_last_error())
         return p
+
+    def set_graph_replay(self, mode: int) -> None:
+        """1 always, 0 never, -1 automatic (small batches)."""
+        _check(lib().sgprs_task_set_graph_replay(self.handle, int(mode)))
 
     def set_profiling(self, on: bool) -> None:
         _check(lib().sgprs_task_set_profiling(self.handle, int(on)))

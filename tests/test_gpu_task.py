@@ -293,6 +293,7 @@ def test_graph_replay_survives_other_batches_and_partitions(cfg1):
     total = S.Pool(1, 8).info()["total_cus"]
     pool = S.Pool(2, total // 2)
     task = S.Task(params, dtype, 16, BN_EPS)
+    task.set_graph_replay(1)   # also for the batch of six
     x1 = dev_nhwc(x, dtype)
     xb = dev_nhwc(make_input(1, 11, (6, 3, 224, 224)), dtype)
     l1 = torch.full((1, 1000), float("nan"), dtype=torch.float32, device="cuda")
