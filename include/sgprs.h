@@ -175,7 +175,7 @@ int sgprs_conv2d(const sgprs_conv_desc_t *d, const void *x, const void *w_packed
 /* Measurement hook, process-wide, not thread-safe: which convolution kernel
  * sgprs_conv2d and the stages pick for 3x3 bf16 layers.  kind -1: automatic
  * (default); 0: implicit GEMM only; 1: the stride-1 LDS-patch kernel with the
- * given tile variant (0..11) and split factor where the shape allows it; 2:
+ * given tile variant (0..4) and split factor where the shape allows it; 2:
  * automatic, but implicit-GEMM launches use tile variant `variant` (0..3)
  * wherever it divides cout, with split-K factor `splits` (0: planner's choice);
  * 3: automatic, plus the stride-2 LDS-patch kernel (not chosen otherwise) with

@@ -3,17 +3,17 @@
 // A plain implicit GEMM re-reads every input pixel once per filter tap; at
 // ResNet18's shapes that makes the kernel bound by L2->CU traffic long before
 // the matrix cores are busy.  Here a workgroup owns TR whole output rows
-// (TR*W <= BM pixels, rows counted across the batch) and BN output channels.
+// (TR*W <= BM pixels, rows counted across the batch) and 64 output channels.
 // For each chunk of KC input channels it stages in LDS
 //   * the input patch: the TR+2 (plus image-boundary padding) input rows of
 //     width W+2, zero filled outside the image, read once and reused by all
 //     nine taps, and
-//   * the weights of that chunk for its BN channels and all nine taps,
-// and then runs 9 * KC/16 MFMA k-steps straight out of LDS with no predicates.
-// The next chunk's patch and weights are fetched into registers while the
-// MFMAs of the current chunk run.  Workgroups are persistent over their work
-// items; when a layer has a single chunk and a single channel block (64->64)
-// the weights stay resident in LDS for the whole launch.
+//   * the weights of that chunk for its 64 channels and all nine taps,
+// and then runs 9 * KC/16 MFMA k-steps straight out of LDS with no predicates,
+// while the next chunk's patch and weights are on their way into the other LDS
+// buffer.  Workgroups are persistent over their work items; when a layer has
+// two chunks and a single channel block (64->64) the weights stay resident in
+// LDS for the whole launch.
 //
 // Rows are addressed in an "extended" row space in which every image has one
 // zero row above and below it: output row g = n*H + p maps to extended row
@@ -85,328 +85,8 @@ template <class Args> __device__ __forceinline__ PatchItem decode_item(const Arg
     return r;
 }
 
-template <int BM, int BN, int KC, int NW = 4> struct PatchCfg {
-    static constexpr int NT = NW * 64;                  // threads per workgroup
-    static constexpr int CPP = KC / 8;                  // 16-byte chunks per pixel
-    static constexpr int PS = KC * 2;                   // bytes per pixel of one chunk
-    static constexpr int PSP = PS + 16;                 // padded LDS pixel stride: 16 consecutive pixels hit 16 distinct bank groups
-    static constexpr int PCAP_PIX = BM == 256 ? 512 : 256;  // patch capacity in pixels
-    static constexpr int PCAP_IDS = PCAP_PIX * CPP;
-    static constexpr int P_IT = PCAP_IDS / NT;
-    static constexpr int PATCH_BYTES = PCAP_PIX * PSP;
-    static constexpr int WROWB = 9 * KC * 2 + 16;       // padded weight row
-    static constexpr int W_IDS = BN * 9 * CPP;
-    static constexpr int W_IT = W_IDS / NT;
-    static constexpr int LDS_BYTES = PATCH_BYTES + BN * WROWB;
-    static constexpr int WM = NW == 8 ? 4 : (BM == 256 && BN == 64) ? 4 : 2;
-    static constexpr int WN = NW / WM;
-    static constexpr int OCC = LDS_BYTES <= 80 * 1024 ? 2 : 1;  // workgroups per CU
-    static constexpr int WAVES_PER_SIMD = OCC * NW / 4;
-    static_assert(PCAP_IDS % NT == 0 && W_IDS % NT == 0 && PATCH_BYTES % 16 == 0, "loader shape");
-};
-
-template <int BM, int BN, int KC, bool STAT, bool SPLIT, int NW>
-__global__ __launch_bounds__((NW * 64), (PatchCfg<BM, BN, KC, NW>::WAVES_PER_SIMD)) void conv3x3_patch_kernel(const PatchArgs a)
-{
-    using C = PatchCfg<BM, BN, KC, NW>;
-    constexpr int NT = C::NT;
-    constexpr int CPP = C::CPP, PS = C::PS, PSP = C::PSP, P_IT = C::P_IT, W_IT = C::W_IT, WROWB = C::WROWB;
-    constexpr int WM = C::WM, WN = C::WN;
-    constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
-    constexpr int KS = KC / 16;
-    // With one wavefront per SIMD nothing else hides the residual's latency, so it
-    // is requested before the last chunk's MFMA loop (when the tile is small
-    // enough to afford the registers); with two wavefronts per SIMD requesting it
-    // at the start of the epilogue measured faster.
-    constexpr bool PRE_RES = C::WAVES_PER_SIMD == 1 && TM * TN <= 4;
-
-    extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char* Ps = smem;
-    unsigned char* Ws = smem + C::PATCH_BYTES;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WN, wn = wave % WN;
-    const int frow = lane & 31, fhalf = lane >> 5;
-
-    u32x4_t preg[P_IT];
-    u32x4_t wreg[STAT ? 1 : W_IT];
-
-    const int n_items = a.n_slots;
-
-    // Loader tables, fixed for the whole launch: which patch row / byte offset
-    // inside an input row this thread's it-th 16-byte chunk comes from, and the
-    // byte offset of its it-th weight chunk inside a (channel block, chunk) slab.
-    int p_row[P_IT];
-    unsigned p_goff[P_IT];  // ~0u: the chunk lies in the zero halo column
-#pragma unroll
-    for (int it = 0; it < P_IT; ++it) {
-        const int id = it * NT + tid;
-        const int pix = id / CPP, ch = id % CPP;
-        const int prow = fdiv(pix, a.mPW), pcol = pix - prow * a.PW;
-        p_row[it] = prow;
-        p_goff[it] = (pcol >= 1 && pcol <= a.W) ? ((unsigned)(pcol - 1) * (unsigned)a.Cin + ch * 8) * 2u : ~0u;
-    }
-    unsigned w_goff[STAT ? 1 : W_IT];
-    if constexpr (!STAT) {
-#pragma unroll
-        for (int it = 0; it < W_IT; ++it) {
-            const int id = it * NT + tid;
-            const int row = id / (9 * CPP), rem = id % (9 * CPP);
-            w_goff[it] = ((unsigned)(row * 9 + rem / CPP) * (unsigned)a.Cin + (rem % CPP) * 8) * 2u;
-        }
-    }
-    const unsigned row_bytes = (unsigned)a.W * (unsigned)a.Cin * 2u;
-
-    // (item, chunk) -> registers.  Offsets are 32-bit byte offsets from the
-    // tensor base (tensors are below 2^31 elements).
-    auto fetch = [&](int item, int chunk) {
-        const PatchItem pi = decode_item(a, item);
-        const int ntile = pi.ntile, mtile = pi.mtile;
-        const int c0 = (pi.split * a.chunks_per_split + chunk) * KC;
-        const int g0 = mtile * a.TR;
-        const int g1 = min(g0 + a.TR, a.NH) - 1;
-        const int E0 = g0 + 2 * (int)fdiv(g0, a.mH);                 // e(g0) - 1
-        const int R = (g1 + 2 * (int)fdiv(g1, a.mH) + 2) - E0 + 1;   // e(g1) + 1 - E0 + 1
-        const unsigned char* xc = a.x + (size_t)c0 * 2;
-#pragma unroll
-        for (int it = 0; it < P_IT; ++it) {
-            const int E = E0 + p_row[it];
-            const int n = fdiv(E, a.mHE);
-            const int hh = E - n * a.HE - 1;
-            const bool ok = p_row[it] < R && (unsigned)hh < (unsigned)a.H && p_goff[it] != ~0u;
-            u32x4_t v = {0u, 0u, 0u, 0u};
-            if (ok) v = *(const u32x4_t*)(xc + ((unsigned)(n * a.H + hh) * row_bytes + p_goff[it]));
-            preg[it] = v;
-        }
-        if constexpr (!STAT) {
-            const unsigned char* wc = a.w + ((size_t)ntile * BN * 9 * a.Cin + c0) * 2;
-#pragma unroll
-            for (int it = 0; it < W_IT; ++it) wreg[it] = *(const u32x4_t*)(wc + w_goff[it]);
-        }
-    };
-    auto stage = [&]() {
-#pragma unroll
-        for (int it = 0; it < P_IT; ++it) {
-            const int id = it * NT + tid;
-            *(u32x4_t*)(Ps + (id / CPP) * PSP + (id % CPP) * 16) = preg[it];
-        }
-        if constexpr (!STAT) {
-#pragma unroll
-            for (int it = 0; it < W_IT; ++it) {
-                const int id = it * NT + tid;
-                *(u32x4_t*)(Ws + (id / (9 * CPP)) * WROWB + (id % (9 * CPP)) * 16) = wreg[it];
-            }
-        }
-    };
-
-    if constexpr (STAT) {  // single chunk, single channel block: weights loaded once
-#pragma unroll
-        for (int it = 0; it < W_IT; ++it) {
-            const int id = it * NT + tid;
-            const int row = id / (9 * CPP), rem = id % (9 * CPP);
-            const int tap = rem / CPP, ch = rem % CPP;
-            *(u32x4_t*)(Ws + row * WROWB + rem * 16) =
-                *(const u32x4_t*)(a.w + ((size_t)(row * 9 + tap) * a.Cin + ch * 8) * 2);
-        }
-    }
-
-    int item = blockIdx.x;
-    if (!decode_item(a, item).valid) return;  // invalid slots only exist at the tail of a die's sequence
-    fetch(item, 0);
-
-    // epilogue geometry: after the LDS transpose every lane owns 8 consecutive
-    // channels (c8) of row rsub + pass*RPP of each 32-row piece
-    constexpr int SROW = WTN + 4;   // padded scratch row (floats)
-    constexpr int LPR = WTN / 8;    // lanes per row in the read-back
-    constexpr int RPP = 64 / LPR;   // rows per pass
-    constexpr int NPASS = 32 / RPP;
-    const int c8 = (lane % LPR) * 8, rsub = lane / LPR;
-
-    while (item < n_items) {
-        const PatchItem pi = decode_item(a, item);
-        if (!pi.valid) break;
-        const int split = pi.split, ntile = pi.ntile, mtile = pi.mtile;
-        const int nch = min(a.chunks_per_split, a.n_chunks - split * a.chunks_per_split);
-        const int g0 = mtile * a.TR;
-        const int E0 = g0 + 2 * (int)fdiv(g0, a.mH);
-        const int rows_here = min(a.TR, a.NH - g0);
-        const int m_lim = rows_here * a.W;
-        const int nbase = ntile * BN + wn * WTN + c8;
-
-        // this lane's output pixels (A-fragment rows) -> byte address of their
-        // top-left patch pixel; a tile is TR whole rows, so its output pixels
-        // are contiguous from g0*W
-        int pbase[TM];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int t = wm * WTM + i * 32 + frow;
-            const int pr = fdiv(t, a.mW), q = t - pr * a.W;
-            const bool ok = pr < rows_here;
-            const int g = g0 + (ok ? pr : 0);
-            const int e1 = g + 2 * (int)fdiv(g, a.mH);  // e(g) - 1
-            pbase[i] = ((e1 - E0) * a.PW + (ok ? q : 0)) * PSP + fhalf * 16;
-        }
-
-        f32x4_t sc0 = {1.f, 1.f, 1.f, 1.f}, sc1 = sc0, sh0 = {0.f, 0.f, 0.f, 0.f}, sh1 = sh0;
-        u32x4_t rres[TM][NPASS];
-        auto load_residual = [&]() {
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int pass = 0; pass < NPASS; ++pass) {
-                    const int t = wm * WTM + i * 32 + pass * RPP + rsub;
-                    u32x4_t rv = {0u, 0u, 0u, 0u};
-                    if (a.res && t < m_lim)
-                        rv = *(const u32x4_t*)(a.res + (((size_t)g0 * a.W + t) * a.Cout + nbase) * 2);
-                    rres[i][pass] = rv;
-                }
-        };
-
-        f32x16_t acc[TM][TN];
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-        const int wbase = C::PATCH_BYTES + (wn * WTN + frow) * WROWB + fhalf * 16;
-        constexpr bool DEEP = NW == 4;  // one wavefront per SIMD: fragments are fetched two k-steps ahead
-        u32x4_t fa[DEEP ? 3 : 2][TM], fb[DEEP ? 3 : 2][TN];
-        // fragments of k-step (tap, ks): tap offsets are added to the lane's
-        // base addresses, the k-step is an immediate offset
-        auto load_frags = [&](int set, int pa_off, int wb_off, int ks) {
-#pragma unroll
-            for (int i = 0; i < TM; ++i) fa[set][i] = *(const u32x4_t*)(smem + pbase[i] + pa_off + ks * 32);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) fb[set][j] = *(const u32x4_t*)(smem + wbase + wb_off + j * 32 * WROWB + ks * 32);
-        };
-
-        for (int chunk = 0; chunk < nch; ++chunk) {
-            __syncthreads();  // the previous chunk's fragment reads (or epilogue scratch) are done
-            stage();
-            __syncthreads();
-            // prefetch what comes next while this chunk computes
-            if (chunk + 1 < nch) fetch(item, chunk + 1);
-            else if (decode_item(a, item + gridDim.x).valid) fetch(item + gridDim.x, 0);
-            if constexpr (!SPLIT) {
-                // epilogue operands: requested during the last chunk so that they
-                // arrive while its MFMAs run
-                if (chunk + 1 == nch) {
-                    sc0 = *(const f32x4_t*)(a.scale + nbase); sc1 = *(const f32x4_t*)(a.scale + nbase + 4);
-                    sh0 = *(const f32x4_t*)(a.shift + nbase); sh1 = *(const f32x4_t*)(a.shift + nbase + 4);
-                    if constexpr (PRE_RES) load_residual();
-                }
-            }
-            if constexpr (DEEP) {
-                // one filter row (3 taps) per loop trip; its 3*KS k-steps are unrolled with
-                // three rotating fragment sets, loads running two k-steps ahead of the MFMAs
-                constexpr int STEPS = 3 * KS;
-                static_assert(STEPS % 3 == 0, "set rotation must close over a filter row");
-                load_frags(0, 0, 0, 0);
-                load_frags(1, KS == 1 ? PSP : 0, KS == 1 ? PS : 0, KS == 1 ? 0 : 1);
-#pragma unroll 1
-                for (int g = 0; g < 3; ++g) {
-                    const int pa_row = g * a.PW * PSP, wb_row = g * 3 * PS;
-#pragma unroll
-                    for (int u = 0; u < STEPS; ++u) {
-                        const int u2 = u + 2;  // the k-step to fetch now
-                        if (u2 < STEPS) load_frags(u2 % 3, pa_row + (u2 / KS) * PSP, wb_row + (u2 / KS) * PS, u2 % KS);
-                        else if (g < 2)
-                            load_frags(u2 % 3, pa_row + a.PW * PSP + ((u2 - STEPS) / KS) * PSP,
-                                       wb_row + 3 * PS + ((u2 - STEPS) / KS) * PS, (u2 - STEPS) % KS);
-#pragma unroll
-                        for (int i = 0; i < TM; ++i)
-#pragma unroll
-                            for (int j = 0; j < TN; ++j)
-                                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                                    __builtin_bit_cast(bf16x8_t, fa[u % 3][i]), __builtin_bit_cast(bf16x8_t, fb[u % 3][j]),
-                                    acc[i][j], 0, 0, 0);
-                    }
-                }
-            } else {
-            load_frags(0, 0, 0, 0);
-            int r = 0, s = 0;
-#pragma unroll 1
-            for (int tap = 0; tap < 9; ++tap) {
-                int s2 = s + 1, r2 = r;
-                if (s2 == 3) { s2 = 0; r2 = r + 1; }
-                const int pa_cur = (r * a.PW + s) * PSP, pa_next = (r2 * a.PW + s2) * PSP;
-                const int wb_cur = tap * PS, wb_next = wb_cur + PS;
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    const int cur = ks & 1;
-                    if (ks + 1 < KS) load_frags(cur ^ 1, pa_cur, wb_cur, ks + 1);
-                    else if (tap + 1 < 9) load_frags(cur ^ 1, pa_next, wb_next, 0);
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-#pragma unroll
-                        for (int j = 0; j < TN; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                                __builtin_bit_cast(bf16x8_t, fa[cur][i]), __builtin_bit_cast(bf16x8_t, fb[cur][j]),
-                                acc[i][j], 0, 0, 0);
-                }
-                r = r2; s = s2;
-            }
-            }
-        }
-
-        // ---- epilogue.  Accumulator register e of a 32x32 tile holds column
-        // lane%32, row 8*(e/4) + 4*(lane/32) + e%4.  Each wavefront transposes one
-        // 32-row x WTN-column piece at a time through its own LDS scratch so that
-        // every lane then owns 8 consecutive channels of one pixel: 16-byte
-        // residual loads and output stores, scale/shift/residual/ReLU in fp32.
-        if constexpr (!SPLIT && !PRE_RES) load_residual();
-        __syncthreads();  // all fragment reads of the last chunk are done: LDS is free
-        {
-            float* scr = (float*)smem + wave * 32 * SROW;
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e)
-                        scr[(8 * (e >> 2) + 4 * fhalf + (e & 3)) * SROW + j * 32 + frow] = acc[i][j][e];
-                // same wavefront wrote and reads: LDS ops of a wave complete in order
-#pragma unroll
-                for (int pass = 0; pass < NPASS; ++pass) {
-                    const int rr = pass * RPP + rsub;
-                    const int t = wm * WTM + i * 32 + rr;
-                    f32x4_t v0 = *(const f32x4_t*)(scr + rr * SROW + c8);
-                    f32x4_t v1 = *(const f32x4_t*)(scr + rr * SROW + c8 + 4);
-                    if (t < m_lim) {
-                        const size_t m = (size_t)g0 * a.W + t;
-                        if constexpr (SPLIT) {
-                            float* dst = a.partial + ((size_t)split * a.NH * a.W + m) * a.Cout + nbase;
-                            *(f32x4_t*)dst = v0;
-                            *(f32x4_t*)(dst + 4) = v1;
-                        } else {
-                            const u32x4_t rv = rres[i][pass];
-                            v0 = v0 * sc0 + sh0;
-                            v1 = v1 * sc1 + sh1;
-                            float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
-                            u32x4_t ov;
-#pragma unroll
-                            for (int u = 0; u < 4; ++u) {
-                                float lo = v[2 * u] + __uint_as_float(rv[u] << 16);
-                                float hi = v[2 * u + 1] + __uint_as_float(rv[u] & 0xffff0000u);
-                                if (a.relu) { lo = fmaxf(lo, 0.f); hi = fmaxf(hi, 0.f); }
-                                const __bf16 l16 = (__bf16)lo, h16 = (__bf16)hi;
-                                ov[u] = (unsigned)__builtin_bit_cast(unsigned short, l16) |
-                                        ((unsigned)__builtin_bit_cast(unsigned short, h16) << 16);
-                            }
-                            *(u32x4_t*)(a.y + (m * a.Cout + nbase) * 2) = ov;
-                        }
-                    }
-                }
-            }
-        }
-        item += gridDim.x;
-    }
-}
-
-// ---- direct-to-LDS variant -------------------------------------------------------
-// Same decomposition with BM = 256, BN = 64 and chunks of 32 channels, but the
+// ---- the kernel --------------------------------------------------------------------
+// Tiles of 512, 256 or 128 rows x 64 channels, chunks of 32 (or 16) channels.  The
 // global loads write LDS directly (buffer loads with the LDS bit: 64 lanes x 16
 // bytes land in one contiguous KiB), so no registers, no LDS-store instructions
 // and no address arithmetic are spent on staging.  Two LDS buffers: while the
@@ -1065,16 +745,13 @@ __global__ __launch_bounds__(NW * 64, 1) void conv3x3s2_patch_kernel(const S2Arg
 static unsigned magic_for(unsigned d) { return (unsigned)((0x100000000ull + d - 1) / d); }
 
 struct PatchVariant { int bm, bn, kc; };
-// tile variants: 0-3 run 4 wavefronts per workgroup, 4-5 run 8 (two per SIMD), 6 is small enough
-// for two workgroups per CU, 7-8 are the direct-to-LDS kernel with 256- and 128-row tiles
-static const PatchVariant kPatchVariants[] = {{256, 64, 64}, {256, 128, 32}, {128, 64, 64}, {128, 128, 32}, {256, 64, 64}, {256, 128, 32}, {128, 64, 32}, {256, 64, 32}, {128, 64, 32}, {256, 64, 16}, {256, 64, 32}, {512, 64, 32}};
-constexpr int kNumPatchVariants = 12;
-constexpr int kPatchDlVariant = 7;       // the direct-to-LDS kernel, 256-row tiles
-constexpr int kPatchDlSmallVariant = 8;  // the same with 128-row tiles, for layers with few row tiles
-constexpr int kPatchDlPairVariant = 9;   // 16-channel chunks: half the LDS, two workgroups per CU
-constexpr int kPatchDlWideVariant = 10;  // 8 wavefronts of 32 rows: two per SIMD
-constexpr int kPatchDlTallVariant = 11;  // 8 wavefronts of 64 rows: 512-row tiles
-static bool is_dl(int v) { return v >= kPatchDlVariant && v <= kPatchDlTallVariant; }
+static const PatchVariant kPatchVariants[] = {{256, 64, 32}, {128, 64, 32}, {256, 64, 16}, {256, 64, 32}, {512, 64, 32}};
+constexpr int kNumPatchVariants = 5;
+constexpr int kPatchDlVariant = 0;       // 256-row tiles, 4 wavefronts
+constexpr int kPatchDlSmallVariant = 1;  // 128-row tiles, for layers with few row tiles
+constexpr int kPatchDlPairVariant = 2;   // 16-channel chunks: half the LDS, two workgroups per CU
+constexpr int kPatchDlWideVariant = 3;   // 256-row tiles, 8 wavefronts of 32 rows: two per SIMD
+constexpr int kPatchDlTallVariant = 4;   // 512-row tiles, 8 wavefronts of 64 rows
 int patch_num_variants() { return kNumPatchVariants; }
 
 // Name as a profiler prints it: v = tile variant + 16 * stationary + 32 * split.
@@ -1086,13 +763,8 @@ const char* patch_variant_name(int v)
     if (tv >= kNumPatchVariants) return "?";
     const PatchVariant& pv = kPatchVariants[tv];
     char* out = buf[next++ & 7];
-    if (is_dl(tv)) {
-        snprintf(out, 96, "conv3x3_patch_dl_kernel<%d, %d, %s, %s, %d>", pv.bm, pv.kc, (v & 16) ? "true" : "false",
-                 (v & 32) ? "true" : "false", tv >= kPatchDlWideVariant ? 8 : 4);
-        return out;
-    }
-    snprintf(out, 96, "conv3x3_patch_kernel<%d, %d, %d, %s, %s, %d>", pv.bm, pv.bn, pv.kc, (v & 16) ? "true" : "false",
-             (v & 32) ? "true" : "false", (tv == 4 || tv == 5) ? 8 : 4);
+    snprintf(out, 96, "conv3x3_patch_dl_kernel<%d, %d, %s, %s, %d>", pv.bm, pv.kc, (v & 16) ? "true" : "false",
+             (v & 32) ? "true" : "false", tv >= kPatchDlWideVariant ? 8 : 4);
     return out;
 }
 
@@ -1127,8 +799,8 @@ static bool patch_geometry_uncached(const sgprs_conv_desc_t& d, int v, int split
 {
     const PatchVariant& pv = kPatchVariants[v];
     if (d.cout % pv.bn || d.cin % pv.kc || d.w > pv.bm) return false;
-    // the direct-to-LDS kernel addresses x and w through 31-bit buffer offsets
-    if (is_dl(v) && ((long long)d.n * d.h * d.w * d.cin * 2 >= (1ll << 31) || (long long)d.n * d.h * d.w * d.cout * 2 >= (1ll << 31) ||
+    // x, w and the residual are addressed through 31-bit buffer offsets
+    if (((long long)d.n * d.h * d.w * d.cin * 2 >= (1ll << 31) || (long long)d.n * d.h * d.w * d.cout * 2 >= (1ll << 31) ||
                                  (long long)d.cout * 9 * d.cin * 2 >= (1ll << 31)))
         return false;
     const int NH = d.n * d.h;
@@ -1151,7 +823,7 @@ static bool patch_geometry_uncached(const sgprs_conv_desc_t& d, int v, int split
     const int cps = (n_chunks + splits - 1) / splits;
     if ((splits - 1) * cps >= n_chunks) return false;
     // the direct-to-LDS kernel alternates two buffers and wants an even number of chunks per item
-    if (is_dl(v) && (n_chunks % 2 || (splits > 1 && (cps % 2 || n_chunks % cps)))) return false;
+    if (n_chunks % 2 || (splits > 1 && (cps % 2 || n_chunks % cps))) return false;
     // exactness of the multiply-high divisions: dividend * divisor < 2^32
     const unsigned long long lim = 1ull << 32;
     if ((unsigned long long)(NH + 2 * d.n + 4) * (d.h + 2) >= lim || (unsigned long long)(cap + 256) * (d.w + 2) >= lim) return false;
@@ -1187,16 +859,15 @@ bool plan_patch(const sgprs_conv_desc_t& d, int cus, int* variant, int* splits)
     }
     // {variant, microseconds per chunk, microseconds per work item}
     static const struct { int v; double step, item; } cand[] = {
-        {11, 2.4, 6.0}, {10, 1.5, 4.3}, {7, 1.65, 5.0}, {8, 1.0, 4.5}, {4, 5.1, 2.8}, {5, 5.1, 2.8}, {3, 3.1, 2.0}, {2, 4.1, 2.0}};
+        {kPatchDlTallVariant, 2.4, 6.0}, {kPatchDlWideVariant, 1.5, 4.3}, {kPatchDlVariant, 1.65, 5.0}, {kPatchDlSmallVariant, 1.0, 4.5}};
     double best = 1e30;
     bool found = false;
     for (const auto& c : cand) {
-        // split-K (fp32 partial sums plus a reduction pass) only for the direct-to-LDS
-        // variant, for shapes with too few work items to occupy the partition
-        for (int sp = 1; sp <= (is_dl(c.v) ? 2 : 1); ++sp) {
+        // split-K (fp32 partial sums plus a reduction pass) for shapes with too few work items to
+        // occupy the partition
+        for (int sp = 1; sp <= 2; ++sp) {
             if (!patch_geometry(d, c.v, sp, &a)) continue;
             const long long items = (long long)a.n_mtiles * a.n_ntiles * sp;
-            if (items * 2 < cus && !is_dl(c.v)) continue;
             if (items * 3 < cus) continue;
             const long long rounds = (items + cus - 1) / cus;
             double cost = rounds * (a.chunks_per_split * c.step + c.item);
@@ -1210,30 +881,6 @@ bool plan_patch(const sgprs_conv_desc_t& d, int cus, int* variant, int* splits)
 size_t patch_workspace_bytes(const sgprs_conv_desc_t& d, int splits)
 {
     return splits > 1 ? (size_t)splits * d.n * d.h * d.w * d.cout * sizeof(float) : 0;
-}
-
-template <int BM, int BN, int KC, bool STAT, bool SPLIT, int NW>
-static int launch_patch_inst(const PatchArgs& a, int grid, hipStream_t stream)
-{
-    using C = PatchCfg<BM, BN, KC, NW>;
-    static bool raised = false;
-    if (!raised) {
-        SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_kernel<BM, BN, KC, STAT, SPLIT, NW>,
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
-        raised = true;
-    }
-    SGPRS_LAUNCH((conv3x3_patch_kernel<BM, BN, KC, STAT, SPLIT, NW>), dim3(grid), dim3(C::NT), C::LDS_BYTES, stream, a);
-    SGPRS_HIP(hipGetLastError());
-    return SGPRS_OK;
-}
-
-template <int BM, int BN, int KC, int NW = 4>
-static int launch_patch_variant(const PatchArgs& a, int grid, bool stat, hipStream_t stream)
-{
-    if (a.splits > 1) return launch_patch_inst<BM, BN, KC, false, true, NW>(a, grid, stream);
-    if constexpr (BM == 256 && BN == 64 && KC == 64)
-        if (stat) return launch_patch_inst<BM, BN, KC, true, false, NW>(a, grid, stream);
-    return launch_patch_inst<BM, BN, KC, false, false, NW>(a, grid, stream);
 }
 
 template <int BM, int KC, int NW = 4>
@@ -1284,29 +931,22 @@ int launch_conv3x3_patch(const sgprs_conv_desc_t& d, int variant, int splits, co
     a.x_bytes = (unsigned)((size_t)d.n * d.h * d.w * d.cin * 2); a.w_bytes = (unsigned)((size_t)d.cout * 9 * d.cin * 2);
     a.y_bytes = (unsigned)((size_t)d.n * d.h * d.w * d.cout * 2);
     const long long items = (long long)a.n_mtiles * a.n_ntiles * a.splits;
-    const int occ = variant == 6 || variant == kPatchDlPairVariant ? 2 : 1;  // small enough for two workgroups per CU
+    const int occ = variant == kPatchDlPairVariant ? 2 : 1;  // small enough for two workgroups per CU
     // a multiple of 8 keeps every workgroup on one die across its items
     int grid = (int)std::min<long long>(a.n_slots, (long long)cus * occ);
     if (a.xcd_groups && grid >= 8) grid -= grid % 8;
-    const bool stat = a.n_chunks == 1 && a.n_ntiles == 1 && a.splits == 1;
+    const bool stat = variant != kPatchDlPairVariant && a.n_chunks == 2 && a.n_ntiles == 1 && a.splits == 1;  // resident weights
     const double M = (double)d.n * d.h * d.w;
     const double flops = 2.0 * M * d.cout * 9.0 * d.cin;
     const double bytes = (M * d.cin + (double)d.cout * 9 * d.cin + M * d.cout * (residual ? 2 : 1)) * 2.0;
     int rc;
-    if (prof && prof->on && (rc = prof->begin(stream, kKindPatch, variant + ((is_dl(variant) ? (variant != kPatchDlPairVariant && a.n_chunks == 2 && a.n_ntiles == 1 && a.splits == 1) : (stat && variant % 4 == 0)) ? 16 : 0) + (splits > 1 ? 32 : 0), flops, bytes))) return rc;
+    if (prof && prof->on && (rc = prof->begin(stream, kKindPatch, variant + (stat ? 16 : 0) + (splits > 1 ? 32 : 0), flops, bytes))) return rc;
     switch (variant) {
-        case 0: rc = launch_patch_variant<256, 64, 64>(a, grid, stat, stream); break;
-        case 1: rc = launch_patch_variant<256, 128, 32>(a, grid, stat, stream); break;
-        case 2: rc = launch_patch_variant<128, 64, 64>(a, grid, stat, stream); break;
-        case 4: rc = launch_patch_variant<256, 64, 64, 8>(a, grid, stat, stream); break;
-        case 5: rc = launch_patch_variant<256, 128, 32, 8>(a, grid, stat, stream); break;
-        case 6: rc = launch_patch_variant<128, 64, 32>(a, grid, stat, stream); break;
         case kPatchDlVariant: rc = launch_patch_dl<256, 32>(a, grid, stream); break;
         case kPatchDlSmallVariant: rc = launch_patch_dl<128, 32>(a, grid, stream); break;
         case kPatchDlPairVariant: rc = launch_patch_dl<256, 16>(a, grid, stream); break;
         case kPatchDlWideVariant: rc = launch_patch_dl<256, 32, 8>(a, grid, stream); break;
-        case kPatchDlTallVariant: rc = launch_patch_dl<512, 32, 8>(a, grid, stream); break;
-        default: rc = launch_patch_variant<128, 128, 32>(a, grid, stat, stream); break;
+        default: rc = launch_patch_dl<512, 32, 8>(a, grid, stream); break;
     }
     if (rc) return rc;
     if (prof && prof->on && (rc = prof->end(stream))) return rc;

@@ -221,7 +221,7 @@ PATCH_SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("variant", range(12))
+@pytest.mark.parametrize("variant", range(5))
 @pytest.mark.parametrize("shape", PATCH_SHAPES, ids=lambda s: "x".join(map(str, s)))
 def test_conv3x3_patch_variants_parity(pools, variant, shape):
     n, h, w, cin, cout = shape
@@ -278,7 +278,7 @@ def test_conv_planner_choices_agree(pools):
     outs = []
     try:
         for kind in (-1, 0, 1):
-            S.sgprs_conv_tuning_override(kind, 4, 1)
+            S.sgprs_conv_tuning_override(kind, 3, 1)
             got, ref = conv_case(S.SGPRS_BF16, *shape, relu=True, with_res=True, seed=61, pool=pool,
                                  cus=pool.partition_cus(0))
             assert_close(got, ref, S.SGPRS_BF16, f"kind {kind}")
