@@ -930,7 +930,6 @@ int launch_conv3x3_patch(const sgprs_conv_desc_t& d, int variant, int splits, co
     a.scale = scale; a.shift = shift; a.res = (const unsigned char*)residual; a.partial = (float*)ws;
     a.x_bytes = (unsigned)((size_t)d.n * d.h * d.w * d.cin * 2); a.w_bytes = (unsigned)((size_t)d.cout * 9 * d.cin * 2);
     a.y_bytes = (unsigned)((size_t)d.n * d.h * d.w * d.cout * 2);
-    const long long items = (long long)a.n_mtiles * a.n_ntiles * a.splits;
     const int occ = variant == kPatchDlPairVariant ? 2 : 1;  // small enough for two workgroups per CU
     // a multiple of 8 keeps every workgroup on one die across its items
     int grid = (int)std::min<long long>(a.n_slots, (long long)cus * occ);
