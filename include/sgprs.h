@@ -194,7 +194,9 @@ int sgprs_add_relu(int dtype, size_t count, const void *a, const void *b, void *
                    sgprs_pool_t *pool, int partition);
 /* Global average pool over hw positions, then FC: x [n][hw][cin] (dtype),
  * w [cout][cin] (dtype, DEVICE), bias NULL or fp32[cout], logits fp32 [n][cout].
- * workspace: DEVICE fp32[n*cin] for the pooled vectors.  cin is 512, 1024 or 2048. */
+ * workspace: DEVICE fp32[n*cin] for the pooled vectors.  cin is 512, 1024 or 2048.
+ * Up to 8 images with cin 512 or 1024 take one fused launch that leaves the
+ * workspace untouched; its logits are bit-identical to the two-kernel path's. */
 int sgprs_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void *x, const void *w,
                      const float *bias, float *logits, float *workspace, sgprs_pool_t *pool,
                      int partition);
@@ -254,7 +256,8 @@ const void *sgprs_task_stage_output(const sgprs_task_t *task, int stage);
  * latency; keep it off when timing throughput).  After synchronising,
  * sgprs_task_kernel_times returns, for the last run of each stage, one record
  * per launch: HOST arrays of length *count (in: capacity).  kind: 0 conv
- * implicit GEMM, 1 stem conv, 2 split-K reduce, 3 max-pool, 4 avg-pool, 5 FC,
+ * implicit GEMM, 1 stem conv, 2 split-K reduce, 3 max-pool, 4 avg-pool, 5 FC
+ * (variant >= 2: avg-pool and FC in one launch),
  * 6 BN+ReLU, 7 add+ReLU, 8 LDS-patch 3x3 conv, 9 fused stem conv + max-pool,
  * 10 two implicit-GEMM convolutions of one input in a single launch, 11 the
  * stride-2 LDS-patch 3x3 conv (variant + 4: together with the 1x1 shortcut).

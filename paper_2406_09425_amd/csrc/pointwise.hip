@@ -226,6 +226,94 @@ __global__ __launch_bounds__(256) void avgpool_kernel(const void* __restrict__ x
     }
 }
 
+// ---- avg-pool + FC in one launch, for a few images ---------------------------------
+// Every workgroup pools its image once more (the 50 KB come from the L2) with exactly the
+// arithmetic of avgpool_kernel, keeps the vector in LDS, and its four wavefronts then compute
+// four output rows each with exactly the arithmetic of fc_kernel: one kernel less at batch 1-8,
+// the same bits.
+template <int DT, int CPL /* 512-element passes */>
+__global__ __launch_bounds__(256) void avgpool_fc_kernel(const void* __restrict__ x, const void* __restrict__ w,
+                                                         const float* __restrict__ bias, float* __restrict__ y, int HW,
+                                                         int Cout)
+{
+    constexpr int N = Vec<DT>::N, C = CPL * 512, CV = C / N, VP = CV / 64, R = 4;
+    __shared__ float part[4][CV][N];
+    __shared__ __align__(16) float pooled[C];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const size_t n = blockIdx.y;
+    // the weight rows do not depend on the pooling: fetch them first so both latencies overlap
+    float wr[R][CPL][8];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int o = min((int)(blockIdx.x * 4 + wave) * R + r, Cout - 1);
+#pragma unroll
+        for (int j = 0; j < CPL; ++j) {
+            const size_t e0 = (size_t)o * C + j * 512 + lane * 8;
+            if constexpr (DT == SGPRS_BF16) {
+                Vec<SGPRS_BF16> t;
+                t.load(w, e0 / 8);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) wr[r][j][i] = t.v[i];
+            } else {
+                Vec<SGPRS_F32> t0, t1;
+                t0.load(w, e0 / 4);
+                t1.load(w, e0 / 4 + 1);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) { wr[r][j][i] = t0.v[i]; wr[r][j][4 + i] = t1.v[i]; }
+            }
+        }
+    }
+#pragma unroll
+    for (int vp = 0; vp < VP; ++vp) {
+        const int c = vp * 64 + lane;
+        float s[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) s[i] = 0.f;
+        int j = wave;
+        for (; j + 12 < HW; j += 16) {
+            Vec<DT> t[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) t[u].load(x, (n * HW + j + 4 * u) * CV + c);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int i = 0; i < N; ++i) s[i] += t[u].v[i];
+        }
+        for (; j < HW; j += 4) {
+            Vec<DT> t;
+            t.load(x, (n * HW + j) * CV + c);
+#pragma unroll
+            for (int i = 0; i < N; ++i) s[i] += t.v[i];
+        }
+#pragma unroll
+        for (int i = 0; i < N; ++i) part[wave][c][i] = s[i];
+    }
+    __syncthreads();
+    const float hw = (float)HW;
+    for (int e = threadIdx.x; e < C; e += 256) {
+        const int c = e / N, i = e % N;
+        pooled[e] = (((part[0][c][i] + part[1][c][i]) + part[2][c][i]) + part[3][c][i]) / hw;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int o = (blockIdx.x * 4 + wave) * R + r;
+        if (o >= Cout) break;
+        float sum = 0.f;
+#pragma unroll
+        for (int j = 0; j < CPL; ++j) {
+            const f32x4_t v0 = *(const f32x4_t*)(pooled + j * 512 + lane * 8), v1 = *(const f32x4_t*)(pooled + j * 512 + lane * 8 + 4);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) sum += wr[r][j][i] * v0[i];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) sum += wr[r][j][4 + i] * v1[i];
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
+        if (lane == 0) y[n * Cout + o] = sum + (bias ? bias[o] : 0.f);
+    }
+}
+
 // ---- FC: logits[n][o] = sum_c w[o][c] v[n][c] + b[o] ------------------------
 // One wavefront per output row o; its weights stay in registers (8 per lane per
 // 512 inputs) while it walks a chunk of images; wavefront reduction by
@@ -379,6 +467,21 @@ int launch_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void* x
 {
     const int vec = dtype == SGPRS_BF16 ? 8 : 4;
     const size_t es = dtype_size(dtype);
+    if (n <= 8 && (cin == 512 || cin == 1024)) {  // a few images: one launch (its bits equal the two-kernel path's)
+        const dim3 fgrid((cout + 15) / 16, n);
+        PROF_BEGIN(kKindFc, 2 + dtype, 2.0 * n * cin * cout,
+                   (double)cin * cout * es + (double)n * hw * cin * es + (double)n * cout * 4);
+        if (dtype == SGPRS_BF16) {
+            if (cin == 512) SGPRS_LAUNCH((avgpool_fc_kernel<SGPRS_BF16, 1>), fgrid, dim3(256), 0, stream, x, w, bias, logits, hw, cout);
+            else SGPRS_LAUNCH((avgpool_fc_kernel<SGPRS_BF16, 2>), fgrid, dim3(256), 0, stream, x, w, bias, logits, hw, cout);
+        } else {
+            if (cin == 512) SGPRS_LAUNCH((avgpool_fc_kernel<SGPRS_F32, 1>), fgrid, dim3(256), 0, stream, x, w, bias, logits, hw, cout);
+            else SGPRS_LAUNCH((avgpool_fc_kernel<SGPRS_F32, 2>), fgrid, dim3(256), 0, stream, x, w, bias, logits, hw, cout);
+        }
+        SGPRS_HIP(hipGetLastError());
+        PROF_END();
+        return SGPRS_OK;
+    }
     PROF_BEGIN(kKindAvgpool, dtype, (double)n * hw * cin, (double)n * hw * cin * es + (double)n * cin * 4);
     const dim3 pgrid((cin / vec + 63) / 64, n);
     if (dtype == SGPRS_BF16)

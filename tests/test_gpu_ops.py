@@ -195,6 +195,29 @@ def test_avgpool_fc_parity(pools, dtype, n):
     assert_close(yd.cpu().numpy().astype(np.float64), ref - bias, dtype, "avgpool_fc no bias")
 
 
+@pytest.mark.parametrize("dtype", DTYPES, ids=DT_ID.get)
+@pytest.mark.parametrize("cin,hw", [(512, 49), (1024, 21), (512, 3)])
+def test_avgpool_fc_one_launch_equals_two(pools, dtype, cin, hw):
+    """Up to 8 images take the single fused launch, more take avg-pool then FC: the same bits."""
+    tdt = torch.bfloat16 if dtype == S.SGPRS_BF16 else torch.float32
+    g = torch.Generator().manual_seed(cin + hw)
+    xd = torch.randn((9, hw, cin), generator=g).to(tdt).cuda()
+    wd = (torch.randn((1000, cin), generator=g) * 0.05).to(tdt).cuda()
+    bd = torch.randn((1000,), generator=g).cuda()
+    ws = torch.empty(9 * cin, dtype=torch.float32, device="cuda")
+    two = torch.full((9, 1000), float("nan"), dtype=torch.float32, device="cuda")
+    one = torch.full((8, 1000), float("nan"), dtype=torch.float32, device="cuda")
+    S.sgprs_avgpool_fc(dtype, 9, hw, cin, 1000, xd.data_ptr(), wd.data_ptr(), bd.data_ptr(), two.data_ptr(),
+                       ws.data_ptr(), pools["full"], 0)
+    S.sgprs_avgpool_fc(dtype, 8, hw, cin, 1000, xd.data_ptr(), wd.data_ptr(), bd.data_ptr(), one.data_ptr(),
+                       ws.data_ptr(), pools["full"], 0)
+    pools["full"].sync()
+    assert torch.isfinite(one).all()
+    assert torch.equal(one, two[:8])
+    ref = (xd.double().mean(dim=1) @ wd.double().T + bd.double()).cpu()[:8]
+    assert (one.cpu().double() - ref).abs().max() <= 1e-4 * ref.abs().max()
+
+
 def test_error_paths_enqueue_nothing(pools):
     pool = pools["full"]
     x = torch.zeros(64, device="cuda")
