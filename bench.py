@@ -468,41 +468,46 @@ def leg_membound(S, hip, torch, pool, stream, reps=20):
 
 
 def leg_oversubscribed(S, torch, total_cus, nhwc, headline_ips, rounds=30):
-    """Two batch-64 bf16 instances on a pool of two partitions that BOTH span all
-    CUs (an over-subscribed context pool): the tails, prologues and idle CUs of
-    one instance's kernels are filled by the other's workgroups."""
+    """Two bf16 instances on a pool of two partitions that BOTH span all CUs (an
+    over-subscribed context pool): the tails, prologues and idle CUs of one
+    instance's kernels are filled by the other's workgroups.  Measured with two
+    batch-64 instances (twice the headline's work per round) and with two batch-32
+    instances (the headline's 64 images per round, as two halves)."""
     import numpy as np
     from workloads import BN_EPS, make_input, make_resnet18_params
-    n, n_p = 64, 2
+    n_p = 2
     words = S.Pool(1, total_cus).mask(0)
     pool = S.Pool(n_p, 0, masks=np.stack([words] * n_p))
-    tasks, xs, lgs = [], [], []
-    for i in range(n_p):
-        tasks.append(S.Task(make_resnet18_params(4, 0, bf16=True), S.SGPRS_BF16, n, BN_EPS))
-        xs.append(nhwc(make_input(4, i, (n, 3, 224, 224), bf16=True), torch.bfloat16))
-        lgs.append(torch.empty((n, 1000), dtype=torch.float32, device="cuda"))
+    res = []
+    for n in (64, 32):
+        tasks, xs, lgs = [], [], []
+        for i in range(n_p):
+            tasks.append(S.Task(make_resnet18_params(4, 0, bf16=True), S.SGPRS_BF16, n, BN_EPS))
+            xs.append(nhwc(make_input(4, i, (n, 3, 224, 224), bf16=True), torch.bfloat16))
+            lgs.append(torch.empty((n, 1000), dtype=torch.float32, device="cuda"))
 
-    def issue_all():
-        for j in range(6):
-            for i in range(n_p):
-                src = xs[i].data_ptr() if j == 0 else tasks[i].stage_output(j - 1)
-                dst = lgs[i].data_ptr() if j == 5 else tasks[i].stage_output(j)
-                tasks[i].stage_run(j, n, src, dst, pool, i)
+        def issue_all():
+            for j in range(6):
+                for i in range(n_p):
+                    src = xs[i].data_ptr() if j == 0 else tasks[i].stage_output(j - 1)
+                    dst = lgs[i].data_ptr() if j == 5 else tasks[i].stage_output(j)
+                    tasks[i].stage_run(j, n, src, dst, pool, i)
 
-    for _ in range(5):
-        issue_all()
-    pool.sync()
-    t0 = time.perf_counter()
-    for _ in range(rounds):
-        issue_all()
-    pool.sync()
-    dt = (time.perf_counter() - t0) / rounds
-    ips = n_p * n / dt
-    for t in tasks:
-        t.destroy()
+        for _ in range(5):
+            issue_all()
+        pool.sync()
+        t0 = time.perf_counter()
+        for _ in range(rounds):
+            issue_all()
+        pool.sync()
+        dt = (time.perf_counter() - t0) / rounds
+        ips = n_p * n / dt
+        for t in tasks:
+            t.destroy()
+        res.append(dict(instances=n_p, batch=n, partitions="2 x all CUs", ms_per_round=round(dt * 1e3, 4),
+                        aggregate_images_per_s=round(ips, 1), vs_single_partition=round(ips / headline_ips, 3)))
     pool.destroy()
-    return dict(instances=n_p, batch=n, partitions="2 x all CUs", ms_per_round=round(dt * 1e3, 4),
-                aggregate_images_per_s=round(ips, 1), vs_single_partition=round(ips / headline_ips, 3))
+    return res
 
 
 def leg_pool_scaling(S, torch, total_cus, nhwc, instances=8, rounds=40):
