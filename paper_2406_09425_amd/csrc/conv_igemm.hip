@@ -71,37 +71,6 @@ __device__ __forceinline__ int swz(int row, int chunk) { return row * 128 + ((ch
 // gain: the loop is bound by L2 -> LDS bandwidth, not by latency.
 template <int BM, int BN> struct IgemmStages { static constexpr int value = 2; };
 
-// Loads of one pipeline stage (k-tile ktc), straight into LDS at As: A_IT
-// instructions for the input rows, B_IT for the weight rows.  !live: the
-// descriptors have size 0 and nothing is fetched.
-template <int ES, int BM, int A_IT, int B_IT>
-__device__ __forceinline__ void igemm_issue_stage(const IgemmArgs& a, unsigned char* As, bool live, int ktc, int wave,
-                                                  const int (&a_base)[A_IT], const int (&a_h0)[A_IT],
-                                                  const int (&a_w0)[A_IT], const unsigned (&b_off)[B_IT])
-{
-#if __HIP_DEVICE_COMPILE__  // the buffer-resource builtins exist in the device pass only
-    typedef __attribute__((address_space(3))) void* lds_ptr_t;
-    constexpr int KT = 128 / ES;
-    const __amdgpu_buffer_rsrc_t x_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.x, 0, live ? (int)a.x_bytes : 0, 0x00020000);
-    const __amdgpu_buffer_rsrc_t w_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, live ? (int)a.w_bytes : 0, 0x00020000);
-    const int tap = ktc / a.cin_tiles;
-    const int c0 = (ktc - tap * a.cin_tiles) * KT;
-    const int r = tap / a.S, s = tap - r * a.S;
-    const int tap_off = (r * a.W + s) * a.Cin + c0;
-#pragma unroll
-    for (int i = 0; i < A_IT; ++i) {
-        const int ih = a_h0[i] + r, iw = a_w0[i] + s;
-        const bool ok = (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
-        const unsigned voff = ok ? (unsigned)(a_base[i] + tap_off) * ES : 0x80000000u;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rs, (lds_ptr_t)(As + (i * 32 + wave * 8) * 128), 16, voff, 0, 0, 0);
-    }
-#pragma unroll
-    for (int i = 0; i < B_IT; ++i)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rs, (lds_ptr_t)(As + (BM + i * 32 + wave * 8) * 128), 16, b_off[i],
-                                                 ktc * 128, 0, 0);
-#endif
-}
-
 // One BM x BN output tile: tile column bx, channel block by, split-K slice bz.
 //
 // The k-tiles move global -> LDS directly (buffer loads with the LDS bit; one
@@ -128,40 +97,75 @@ __device__ __forceinline__ void igemm_tile(const IgemmArgs& a, int bx, int by, i
 
     extern __shared__ __align__(16) unsigned char smem[];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: LDS destinations stay in scalar registers
     const int wm = wave / WN, wn = wave % WN;
     const int m0 = bx * BM, n0 = by * BN;
     const int kt_begin = bz * a.kt_per_split;
     const int kt_end = min(kt_begin + a.kt_per_split, a.ktiles);
     const int K = a.ktiles * KT;
+    const int R = a.ktiles / (a.S * a.cin_tiles);
 
     // ---- loader bookkeeping: instruction i of this wavefront fills rows
     // i*32 + wave*8 .. +7 of a stage; this lane's LDS slot (lane & 7) of row
     // lane >> 3 holds global chunk (lane & 7) ^ (lane >> 3) (the swizzle).
+    // Per row: the byte offset of tap (0, 0) and which filter rows (bits 0..)
+    // and columns (bits 16..) fall inside the image.
     const int lrow = wave * 8 + (lane >> 3), gchunk = (lane & 7) ^ (lane >> 3);
-    int a_base[A_IT], a_h0[A_IT], a_w0[A_IT];
+    int a_base[A_IT];
+    unsigned a_in[A_IT];
 #pragma unroll
     for (int i = 0; i < A_IT; ++i) {
         const int m = m0 + lrow + 32 * i;
+        a_base[i] = 0;
+        a_in[i] = 0;  // rows past M: every tap falls outside
         if (m < a.M) {
             const int n = m / a.PQ, rem = m - n * a.PQ;
             const int p = rem / a.Q, q = rem - p * a.Q;
-            a_h0[i] = p * a.stride - a.pad;
-            a_w0[i] = q * a.stride - a.pad;
-            a_base[i] = ((n * a.H + a_h0[i]) * a.W + a_w0[i]) * a.Cin + gchunk * CH;
-        } else {
-            a_h0[i] = -(1 << 20);  // every tap falls outside the image
-            a_w0[i] = 0;
-            a_base[i] = 0;
+            const int h0 = p * a.stride - a.pad, w0 = q * a.stride - a.pad;
+            a_base[i] = (((n * a.H + h0) * a.W + w0) * a.Cin + gchunk * CH) * ES;
+            for (int r = 0; r < R; ++r) a_in[i] |= (unsigned)((unsigned)(h0 + r) < (unsigned)a.H) << r;
+            for (int c = 0; c < a.S; ++c) a_in[i] |= (unsigned)((unsigned)(w0 + c) < (unsigned)a.W) << (16 + c);
         }
     }
     unsigned b_off[B_IT];
 #pragma unroll
     for (int i = 0; i < B_IT; ++i) b_off[i] = (unsigned)((n0 + lrow + 32 * i) * K + gchunk * CH) * ES;
 
+    // The issue cursor walks the k-tiles in order: channel tile ic of tap (ir, is).  The lanes'
+    // offsets change only when the tap does; the channel tile goes into the scalar offset.
+    int ic = kt_begin % a.cin_tiles, ir = (kt_begin / a.cin_tiles) / a.S, is = (kt_begin / a.cin_tiles) % a.S;
+    unsigned a_voff[A_IT];
+    auto enter_tap = [&]() {
+        const int tap_off = (ir * a.W + is) * a.Cin * ES;
+        const unsigned need = (1u << ir) | (0x10000u << is);
+#pragma unroll
+        for (int i = 0; i < A_IT; ++i)
+            a_voff[i] = (a_in[i] & need) == need ? (unsigned)(a_base[i] + tap_off) : 0x80000000u;
+    };
+    enter_tap();
+    // Loads of k-tile kt straight into LDS stage `stage`: A_IT instructions for the input rows,
+    // B_IT for the weight rows.  Past kt_end the descriptors have size 0 and nothing is fetched.
     auto issue_stage = [&](int kt, int stage) {
-        igemm_issue_stage<ES, BM, A_IT, B_IT>(a, smem + stage * STAGE, kt < kt_end, kt < kt_end ? kt : kt_begin, wave, a_base,
-                                              a_h0, a_w0, b_off);
+#if __HIP_DEVICE_COMPILE__  // the buffer-resource builtins exist in the device pass only
+        typedef __attribute__((address_space(3))) void* lds_ptr_t;
+        const bool live = kt < kt_end;
+        const __amdgpu_buffer_rsrc_t x_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.x, 0, live ? (int)a.x_bytes : 0, 0x00020000);
+        const __amdgpu_buffer_rsrc_t w_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, live ? (int)a.w_bytes : 0, 0x00020000);
+        unsigned char* As = smem + stage * STAGE;
+#pragma unroll
+        for (int i = 0; i < A_IT; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rs, (lds_ptr_t)(As + (i * 32 + wave * 8) * 128), 16, a_voff[i], ic * 128, 0, 0);
+#pragma unroll
+        for (int i = 0; i < B_IT; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rs, (lds_ptr_t)(As + (BM + i * 32 + wave * 8) * 128), 16, b_off[i],
+                                                     (live ? kt : 0) * 128, 0, 0);
+        if (++ic == a.cin_tiles) {
+            ic = 0;
+            if (++is == a.S) { is = 0; ++ir; }
+            enter_tap();
+        }
+#endif
     };
 
     f32x16_t acc[TM][TN];
@@ -173,30 +177,24 @@ __device__ __forceinline__ void igemm_tile(const IgemmArgs& a, int bx, int by, i
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
     const int frow = lane & 31, fhalf = lane >> 5;
-    // fragment addresses inside a stage for k-step 0; k-step ks flips bits 5-6
-    unsigned fa_off[TM], fb_off[TN];
+    // fragment addresses inside a stage, one per k-step (k-step ks flips bits 5-6); the
+    // 32-row tiles below and the stage are constant offsets from them
+    unsigned fa_off[4], fb_off[4];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) fa_off[i] = swz(wm * WTM + i * 32 + frow, fhalf);
-#pragma unroll
-    for (int j = 0; j < TN; ++j) fb_off[j] = BM * 128 + swz(wn * WTN + j * 32 + frow, fhalf);
+    for (int ks = 0; ks < 4; ++ks) {
+        fa_off[ks] = swz(wm * WTM + frow, fhalf) ^ (ks << 5);
+        fb_off[ks] = BM * 128 + (swz(wn * WTN + frow, fhalf) ^ (ks << 5));
+    }
 
-#pragma unroll
-    for (int q = 0; q < NS - 1; ++q) issue_stage(kt_begin + q, q);
-    int stage = 0;
-    for (int kt = kt_begin; kt < kt_end; ++kt) {
-        // k-tile kt has landed once at most the NS-2 younger stages are outstanding
-        __builtin_amdgcn_s_waitcnt(((NS - 2) * LPS & 15) | (((NS - 2) * LPS >> 4) << 14) | 0x0F70);
-        __syncthreads();  // ... for every thread; and the stage read last iteration is free
-        const int free_stage = stage == 0 ? NS - 1 : stage - 1;
-        issue_stage(kt + NS - 1, free_stage);
+    auto compute_stage = [&](int stage) {
         const unsigned char* St = smem + stage * STAGE;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             u32x4_t af[TM], bf[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) af[i] = *(const u32x4_t*)(St + (fa_off[i] ^ (ks << 5)));
+            for (int i = 0; i < TM; ++i) af[i] = *(const u32x4_t*)(St + fa_off[ks] + i * 32 * 128);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bf[j] = *(const u32x4_t*)(St + (fb_off[j] ^ (ks << 5)));
+            for (int j = 0; j < TN; ++j) bf[j] = *(const u32x4_t*)(St + fb_off[ks] + j * 32 * 128);
             if constexpr (DT == SGPRS_BF16) {
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
@@ -216,8 +214,26 @@ __device__ __forceinline__ void igemm_tile(const IgemmArgs& a, int bx, int by, i
                                 __uint_as_float(af[i][u]), __uint_as_float(bf[j][u]), acc[i][j], 0, 0, 0);
             }
         }
-        stage = stage == NS - 1 ? 0 : stage + 1;
+    };
+
+#pragma unroll
+    for (int q = 0; q < NS - 1; ++q) issue_stage(kt_begin + q, q);
+    // NS k-tiles per trip, so that every stage index below is a constant
+    auto k_tile = [&](int kt, int st) {
+        // k-tile kt has landed once at most the NS-2 younger stages are outstanding
+        __builtin_amdgcn_s_waitcnt(((NS - 2) * LPS & 15) | (((NS - 2) * LPS >> 4) << 14) | 0x0F70);
+        __syncthreads();  // ... for every thread; and the stage read last iteration is free
+        issue_stage(kt + NS - 1, (st + NS - 1) % NS);
+        compute_stage(st);
+    };
+    int kt = kt_begin;
+    for (; kt + NS <= kt_end; kt += NS) {
+#pragma unroll
+        for (int st = 0; st < NS; ++st) k_tile(kt + st, st);
     }
+#pragma unroll
+    for (int st = 0; st < NS - 1; ++st)
+        if (kt + st < kt_end) k_tile(kt + st, st);
     // drain the (empty) loads still in flight before the staging area becomes scratch
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
@@ -323,14 +339,22 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const IgemmArgs a)
 // rest the second.  Neither depends on the other, so the short second problem
 // fills the tail of the first instead of paying a launch of its own.
 template <int DT, int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(256) void conv_igemm_pair_kernel(const IgemmArgs a0, const IgemmArgs a1, int grid_m0,
-                                                              int tiles0, int grid_m1)
+__global__ __launch_bounds__(256) void conv_igemm_pair_kernel(const IgemmArgs a0, const IgemmArgs a1, int grid_n0,
+                                                              int tiles0, int slots0, int grid_n1, int tiles1)
 {
-    const int b = blockIdx.x;
-    if (b < tiles0)
-        igemm_tile<DT, BM, BN, WM, WN, false>(a0, b % grid_m0, b / grid_m0, 0);
-    else
-        igemm_tile<DT, BM, BN, WM, WN, false>(a1, (b - tiles0) % grid_m1, (b - tiles0) / grid_m1, 0);
+    // Workgroup b runs on die b % 8.  Each die takes a contiguous range of row tiles with all
+    // their channel blocks (of both problems), so that a die's L2 fetches its input rows once and
+    // workgroups launched back to back share them; slots0 and the grid are multiples of 8, the
+    // surplus workgroups leave at once.
+    const int b = blockIdx.x, die = b & 7;
+    if (b < slots0) {
+        const int t = die * (slots0 >> 3) + (b >> 3);
+        if (t < tiles0) igemm_tile<DT, BM, BN, WM, WN, false>(a0, t / grid_n0, t % grid_n0, 0);
+    } else {
+        const int slots1 = gridDim.x - slots0;
+        const int t = die * (slots1 >> 3) + ((b - slots0) >> 3);
+        if (t < tiles1) igemm_tile<DT, BM, BN, WM, WN, false>(a1, t / grid_n1, t % grid_n1, 0);
+    }
 }
 
 // Second pass of split-K: sums the slices in index order, then scale/shift,
@@ -407,7 +431,9 @@ static int launch_pair_variant(const IgemmArgs& a0, const ConvPlan& p0, const Ig
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         raised = true;
     }
-    SGPRS_LAUNCH((conv_igemm_pair_kernel<DT, BM, BN, WM, WN>), dim3(tiles0 + tiles1), dim3(256), lds, stream, a0, a1, p0.grid_m, tiles0, p1.grid_m);
+    const int slots0 = (tiles0 + 7) / 8 * 8, slots1 = (tiles1 + 7) / 8 * 8;
+    SGPRS_LAUNCH((conv_igemm_pair_kernel<DT, BM, BN, WM, WN>), dim3(slots0 + slots1), dim3(256), lds, stream, a0, a1, p0.grid_n, tiles0, slots0,
+                 p1.grid_n, tiles1);
     SGPRS_HIP(hipGetLastError());
     return SGPRS_OK;
 }
