@@ -34,8 +34,10 @@ struct IgemmArgs {
     const float* shift;
     const unsigned char* res;
     float* partial;
-    int H, W, Cin, Cout, P, Q, S, stride, pad;
+    int H, W, Cin, Cout, P, Q, R, S, stride, pad;
     int M, PQ;
+    unsigned pq_mul, q_mul;  // m / PQ and rem / Q as multiply-high and shift (shift -1: divisor 1)
+    int pq_sh, q_sh;
     int ktiles, kt_per_split, cin_tiles;
     int relu;
     unsigned x_bytes, w_bytes;  // buffer-descriptor bounds of x and w
@@ -63,6 +65,12 @@ template <> struct Store<SGPRS_BF16> {
         ((unsigned short*)p)[i] = f32_to_bf16(v);
     }
 };
+
+// m / d for 0 <= m < 2^31 with the constants of fast_div_constants().
+__device__ __forceinline__ int fast_div(int m, unsigned mul, int sh)
+{
+    return sh < 0 ? m : (int)(__umulhi((unsigned)m, mul) >> sh);
+}
 
 __device__ __forceinline__ int swz(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
 
@@ -104,7 +112,6 @@ __device__ __forceinline__ void igemm_tile(const IgemmArgs& a, int bx, int by, i
     const int kt_begin = bz * a.kt_per_split;
     const int kt_end = min(kt_begin + a.kt_per_split, a.ktiles);
     const int K = a.ktiles * KT;
-    const int R = a.ktiles / (a.S * a.cin_tiles);
 
     // ---- loader bookkeeping: instruction i of this wavefront fills rows
     // i*32 + wave*8 .. +7 of a stage; this lane's LDS slot (lane & 7) of row
@@ -120,12 +127,15 @@ __device__ __forceinline__ void igemm_tile(const IgemmArgs& a, int bx, int by, i
         a_base[i] = 0;
         a_in[i] = 0;  // rows past M: every tap falls outside
         if (m < a.M) {
-            const int n = m / a.PQ, rem = m - n * a.PQ;
-            const int p = rem / a.Q, q = rem - p * a.Q;
+            const int n = fast_div(m, a.pq_mul, a.pq_sh), rem = m - n * a.PQ;
+            const int p = fast_div(rem, a.q_mul, a.q_sh), q = rem - p * a.Q;
             const int h0 = p * a.stride - a.pad, w0 = q * a.stride - a.pad;
             a_base[i] = (((n * a.H + h0) * a.W + w0) * a.Cin + gchunk * CH) * ES;
-            for (int r = 0; r < R; ++r) a_in[i] |= (unsigned)((unsigned)(h0 + r) < (unsigned)a.H) << r;
-            for (int c = 0; c < a.S; ++c) a_in[i] |= (unsigned)((unsigned)(w0 + c) < (unsigned)a.W) << (16 + c);
+#pragma unroll
+            for (int t = 0; t < 3; ++t) {  // filters are at most 3x3 here
+                a_in[i] |= (unsigned)(t < a.R && (unsigned)(h0 + t) < (unsigned)a.H) << t;
+                a_in[i] |= (unsigned)(t < a.S && (unsigned)(w0 + t) < (unsigned)a.W) << (16 + t);
+            }
         }
     }
     unsigned b_off[B_IT];
@@ -134,7 +144,13 @@ __device__ __forceinline__ void igemm_tile(const IgemmArgs& a, int bx, int by, i
 
     // The issue cursor walks the k-tiles in order: channel tile ic of tap (ir, is).  The lanes'
     // offsets change only when the tap does; the channel tile goes into the scalar offset.
-    int ic = kt_begin % a.cin_tiles, ir = (kt_begin / a.cin_tiles) / a.S, is = (kt_begin / a.cin_tiles) % a.S;
+    int ic = 0, ir = 0, is = 0;
+    if (kt_begin) {  // split-K slices start somewhere inside the filter
+        const int tap = kt_begin / a.cin_tiles;
+        ic = kt_begin - tap * a.cin_tiles;
+        ir = tap / a.S;
+        is = tap - ir * a.S;
+    }
     unsigned a_voff[A_IT];
     auto enter_tap = [&]() {
         const int tap_off = (ir * a.W + is) * a.Cin * ES;
@@ -494,6 +510,17 @@ int launch_splitk_reduce(int dtype, const float* partial, int splits, size_t tot
 
 // Kernel arguments for plan p; false if the plan does not match the shape
 // (the host-side checks the kernel relies on).
+// Constants for fast_div: with L = ceil(log2 d) and mul = ceil(2^(31+L) / d) < 2^32,
+// floor(m / d) = (m * mul) >> (31 + L) for every 0 <= m < 2^31.
+static void fast_div_constants(int d, unsigned* mul, int* sh)
+{
+    if (d <= 1) { *mul = 0; *sh = -1; return; }
+    int L = 1;
+    while ((1ll << L) < d) ++L;
+    *mul = (unsigned)(((1ull << (31 + L)) + (unsigned)d - 1) / (unsigned)d);
+    *sh = L - 1;
+}
+
 static bool fill_igemm_args(const sgprs_conv_desc_t& d, const ConvPlan& p, const void* x, const void* w,
                             const float* scale, const float* shift, const void* residual, void* y, void* ws,
                             IgemmArgs* out)
@@ -504,8 +531,11 @@ static bool fill_igemm_args(const sgprs_conv_desc_t& d, const ConvPlan& p, const
     a.scale = scale; a.shift = shift; a.res = (const unsigned char*)residual; a.partial = (float*)ws;
     a.H = d.h; a.W = d.w; a.Cin = d.cin; a.Cout = d.cout;
     a.P = out_dim(d.h, d.r, d.stride, d.pad); a.Q = out_dim(d.w, d.s, d.stride, d.pad);
-    a.S = d.s; a.stride = d.stride; a.pad = d.pad;
+    a.R = d.r; a.S = d.s; a.stride = d.stride; a.pad = d.pad;
     a.PQ = a.P * a.Q; a.M = d.n * a.PQ;
+    fast_div_constants(a.PQ, &a.pq_mul, &a.pq_sh);
+    fast_div_constants(a.Q, &a.q_mul, &a.q_sh);
+    if (d.r > 3 || d.s > 3) return false;  // the tap masks of the loader hold 3 rows and 3 columns
     a.ktiles = p.ktiles; a.kt_per_split = (p.ktiles + p.splits - 1) / p.splits;
     a.cin_tiles = d.cin / kt_el; a.relu = d.relu;
     // x and w are addressed through 31-bit buffer offsets
