@@ -259,6 +259,11 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
         }
         // tile row -> output pixel of this item, or -1 past the item's rows
         auto tile_pixel = [&](int tt) { return tt < m_lim ? tt : -1; };
+        // y and the residual go through buffer descriptors: 32-bit offsets, rows past the item get an
+        // offset beyond the bound (loads return 0, stores are dropped), no residual = a bound of 0
+        const __amdgpu_buffer_rsrc_t y_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.y, 0, (int)a.y_bytes, 0x00020000);
+        const __amdgpu_buffer_rsrc_t res_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.res, 0, a.res ? (int)a.y_bytes : 0, 0x00020000);
+        auto out_off = [&](int px) { return px >= 0 ? (unsigned)((g0 * a.W + px) * a.Cout + nbase) * 2u : 0x80000000u; };
         f32x16_t acc[TM][TN];
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -345,11 +350,8 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int pass = 0; pass < NPASS; ++pass) {
-                        const int px = tile_pixel(wm * WTM + i * 32 + pass * RPP + rsub);
-                        u32x4_t rv = {0u, 0u, 0u, 0u};
-                        if (a.res && px >= 0)
-                            rv = *(const u32x4_t*)(a.res + (((size_t)g0 * a.W + px) * a.Cout + nbase) * 2);
-                        rres[i][pass] = rv;
+                        rres[i][pass] = __builtin_amdgcn_raw_buffer_load_b128(
+                            res_rs, out_off(tile_pixel(wm * WTM + i * 32 + pass * RPP + rsub)), 0, 0);
                     }
             }
             // MFMA loop: 9 * KS k-steps, fragments fetched two k-steps ahead, one load slot per k-step
@@ -400,11 +402,8 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int pass = 0; pass < NPASS; ++pass) {
-                        const int px = tile_pixel(wm * WTM + i * 32 + pass * RPP + rsub);
-                        u32x4_t rv = {0u, 0u, 0u, 0u};
-                        if (a.res && px >= 0)
-                            rv = *(const u32x4_t*)(a.res + (((size_t)g0 * a.W + px) * a.Cout + nbase) * 2);
-                        rres[i][pass] = rv;
+                        rres[i][pass] = __builtin_amdgcn_raw_buffer_load_b128(
+                            res_rs, out_off(tile_pixel(wm * WTM + i * 32 + pass * RPP + rsub)), 0, 0);
                     }
             }
 #pragma unroll
@@ -424,14 +423,14 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
                     const int px = tile_pixel(wm * WTM + i * 32 + pass * RPP + rsub);
                     f32x4_t v0 = *(const f32x4_t*)(scr + rr * SROW + c8);
                     f32x4_t v1 = *(const f32x4_t*)(scr + rr * SROW + c8 + 4);
-                    if (px >= 0) {
-                        const size_t m = (size_t)g0 * a.W + px;
-                        if constexpr (SPLIT) {  // fp32 partial sums; scale, shift, residual and ReLU happen in the reduction
+                    if constexpr (SPLIT) {  // fp32 partial sums; scale, shift, residual and ReLU happen in the reduction
+                        if (px >= 0) {
+                            const size_t m = (size_t)g0 * a.W + px;
                             float* dst = a.partial + ((size_t)cur.split * a.NH * a.W + m) * a.Cout + nbase;
                             *(f32x4_t*)dst = v0;
                             *(f32x4_t*)(dst + 4) = v1;
-                            continue;
                         }
+                    } else {
                         const u32x4_t rv = rres[i][pass];
                         v0 = v0 * sc0 + sh0;
                         v1 = v1 * sc1 + sh1;
@@ -446,7 +445,7 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
                             ov[u] = (unsigned)__builtin_bit_cast(unsigned short, l16) |
                                     ((unsigned)__builtin_bit_cast(unsigned short, h16) << 16);
                         }
-                        *(u32x4_t*)(a.y + (m * a.Cout + nbase) * 2) = ov;
+                        __builtin_amdgcn_raw_buffer_store_b128(ov, y_rs, out_off(px), 0, 0);  // rows past the item: dropped
                     }
                 }
             }
