@@ -246,6 +246,7 @@ def main():
         rnd = out["roofline"]["sustained_mfma"]["random_data"]["tflops"]
         out["roofline"]["frac_of_sustained_random_data"] = round(roofline["achieved"] / rnd, 4)
         out["conv_all"]["frac_of_sustained_random_data"] = round(conv_all["tflops"] / rnd, 4)
+        out["roofline"]["sustained_load_to_lds"] = leg_load_probe(S, hip, torch, pool, stream, total_cus)
         out["batch1_fp32"] = leg_batch1(S, hip, pool, stream, nhwc, torch, total_cus)
         out["cu_sweep"] = leg_sweep(S, hip, torch, total_cus, nhwc, with_cpu=not args.no_cpu)
         out["multi_tenant"] = leg_multi_tenant(S, hip, torch, total_cus, nhwc)
@@ -425,6 +426,32 @@ def leg_mfma_probe(S, hip, torch, pool, stream, total_cus, steps=4000, reps=5):
                          mfma_pipe_busy=round(mfmas_per_simd * 32 / clocks, 3),
                          frac_of_published_peak=round(flops / sec / PEAK_BF16, 4))
         log("mfma_probe", name, json.dumps(res[name]))
+    return res
+
+
+def leg_load_probe(S, hip, torch, pool, stream, total_cus, iters=2048, reps=3):
+    """What the load path of the convolution kernels sustains (16-byte buffer loads straight into
+    LDS, 8 wavefronts per CU, 64 KiB in flight per CU): every workgroup cycles through its own region;
+    the regions together fit the L2s (16 MiB), the memory-side cache (64 MiB) or neither (1 GiB)."""
+    buf = torch.ones(256 << 20, dtype=torch.int32, device="cuda")  # 1 GiB
+    out = torch.zeros(total_cus, dtype=torch.int32, device="cuda")
+    res = {}
+    for name, region in (("l2_resident_64KiB_regions", 64 << 10), ("beyond_l2_256KiB_regions", 256 << 10),
+                         ("beyond_caches_4MiB_regions", 4 << 20)):
+        nbytes = min(buf.numel() * 4, region * total_cus)
+        pool.load_probe(0, buf.data_ptr(), nbytes, region, 64, out.data_ptr())
+        pool.sync()
+        e0, e1 = hip.event(), hip.event()
+        hip.record(e0, stream)
+        for _ in range(reps):
+            pool.load_probe(0, buf.data_ptr(), nbytes, region, iters, out.data_ptr())
+        hip.record(e1, stream)
+        pool.sync()
+        sec = hip.elapsed_ms(e0, e1) * 1e-3 / reps
+        moved = float(total_cus) * iters * 65536
+        assert int(out.min()) == 16384 and int(out.max()) == 16384
+        res[name] = dict(tb_per_s=round(moved / sec / 1e12, 2), gb_per_s_per_cu=round(moved / sec / 1e9 / total_cus, 1))
+        log("load_probe", name, json.dumps(res[name]))
     return res
 
 

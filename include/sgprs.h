@@ -133,6 +133,18 @@ int sgprs_partition_probe_graph(sgprs_pool_t *pool, int partition, int n_blocks,
  * shader clocks, a checksum.  Time the launch with events on the partition's
  * stream for the aggregate rate. */
 int sgprs_mfma_probe(sgprs_pool_t *pool, int partition, int random_data, int steps, uint64_t *out);
+/* Diagnostic: the sustained rate of the load path the convolution kernels use
+ * (16-byte buffer loads straight into LDS).  One 512-thread workgroup per CU
+ * reads 64 KiB per iteration, `iters` (1..1e6) times, cycling through its own
+ * region of region_bytes (a power of two, 16 KiB..1 GiB) of buf: workgroup b
+ * uses buf + (b * region_bytes) % buf_bytes (buf DEVICE, 16-byte aligned,
+ * buf_bytes a multiple of region_bytes).  With all regions together inside the
+ * L2s this measures L2 -> LDS, with more it measures what lies behind them.
+ * out: DEVICE uint32[CUs of the partition]; workgroup b writes the sum of the
+ * 16384 32-bit words its last iteration left in LDS.  Moves CUs * iters *
+ * 65536 bytes; time the launch with events on the partition's stream. */
+int sgprs_load_probe(sgprs_pool_t *pool, int partition, const void *buf, size_t buf_bytes,
+                     size_t region_bytes, int iters, uint32_t *out);
 
 /* -------------------------------------------------------- per-operator ----
  * The operators of the paper's "GPU Speedup Analysis": convolution, max

@@ -80,6 +80,7 @@ def lib():
         "sgprs_pool_sync": (c_int, [vp]),
         "sgprs_partition_probe": (c_int, [vp, c_int, c_int, c_int, vp]),
         "sgprs_mfma_probe": (c_int, [vp, c_int, c_int, c_int, vp]),
+        "sgprs_load_probe": (c_int, [vp, c_int, vp, c_size_t, c_size_t, c_int, vp]),
         "sgprs_partition_probe_graph": (c_int, [vp, c_int, c_int, c_int, vp]),
         "sgprs_fold_bn": (c_int, [fp, fp, fp, fp, c_float, c_int, fp, fp]),
         "sgprs_conv_packed_weight_bytes": (c_int, [POINTER(ConvDesc), POINTER(c_size_t)]),
@@ -233,6 +234,9 @@ class Pool:
 
     def mfma_probe(self, p: int, random_data: bool, steps: int, out_ptr: int) -> None:
         _check(lib().sgprs_mfma_probe(self.handle, p, int(bool(random_data)), steps, out_ptr))
+
+    def load_probe(self, p: int, buf_ptr: int, buf_bytes: int, region_bytes: int, iters: int, out_ptr: int) -> None:
+        _check(lib().sgprs_load_probe(self.handle, p, buf_ptr, buf_bytes, region_bytes, iters, out_ptr))
 
     def destroy(self) -> None:
         if self.handle:

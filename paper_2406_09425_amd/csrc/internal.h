@@ -181,6 +181,7 @@ int launch_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void* x
                       Profiler* prof);
 int launch_probe(int n_blocks, int spin_cycles, uint32_t* out, hipStream_t stream);
 int launch_mfma_probe(int cus, int steps, int random_data, unsigned long long* out, hipStream_t stream);
+int launch_load_probe(int cus, const void* buf, size_t buf_bytes, unsigned region, int iters, unsigned* out, hipStream_t stream);
 // stage 0 fused: conv7x7/2 + BN + ReLU + max-pool 3x3/2
 bool stem_pool_applicable(int dtype, int n, int h, int w, int cus);
 int launch_stem_pool(int dtype, int n, int h, int w, const void* x, const void* wts, const float* scale,

@@ -320,4 +320,20 @@ int sgprs_mfma_probe(sgprs_pool_t* pool, int partition, int random_data, int ste
     return launch_mfma_probe(c, steps, random_data != 0, (unsigned long long*)out, s);
 }
 
+int sgprs_load_probe(sgprs_pool_t* pool, int partition, const void* buf, size_t buf_bytes, size_t region_bytes, int iters,
+                     uint32_t* out)
+{
+    hipStream_t s;
+    int c = 0;
+    int rc = resolve(pool, partition, &s, &c);
+    if (rc) return rc;
+    if (!buf || !out || ((uintptr_t)buf & 15)) return fail(SGPRS_ERR_INVALID_ARG, "buf must be 16-byte aligned, buf and out non-NULL");
+    if (region_bytes < (16u << 10) || region_bytes > (1u << 30) || (region_bytes & (region_bytes - 1)))
+        return fail(SGPRS_ERR_INVALID_ARG, "region_bytes %zu is not a power of two in [16 KiB, 1 GiB]", region_bytes);
+    if (buf_bytes < region_bytes || buf_bytes % region_bytes)
+        return fail(SGPRS_ERR_INVALID_ARG, "buf_bytes %zu is not a positive multiple of region_bytes %zu", buf_bytes, region_bytes);
+    if (iters <= 0 || iters > 1000000) return fail(SGPRS_ERR_INVALID_ARG, "iters %d outside [1,1e6]", iters);
+    return launch_load_probe(c, buf, buf_bytes, (unsigned)region_bytes, iters, out, s);
+}
+
 }  // extern "C"

@@ -114,6 +114,28 @@ def test_mfma_probe_checksum_and_errors():
     pool.destroy()
 
 
+def test_load_probe_checksum_and_errors():
+    """The load probe really moves its data: the buffer holds ones, so every workgroup finds
+    16384 of them in LDS after its last iteration, whatever the region size."""
+    pool = S.Pool(2, 32)
+    cus = pool.partition_cus(1)
+    buf = torch.ones(4 << 20, dtype=torch.int32, device="cuda")  # 16 MiB
+    for region in (16 << 10, 64 << 10, 1 << 20):
+        out = torch.zeros(cus, dtype=torch.int32, device="cuda")
+        pool.load_probe(1, buf.data_ptr(), buf.numel() * 4, region, 5, out.data_ptr())
+        pool.sync()
+        assert out.cpu().tolist() == [16384] * cus
+    out = torch.zeros(cus, dtype=torch.int32, device="cuda")
+    for bad in (dict(region=48 << 10), dict(region=8 << 10), dict(nbytes=(64 << 10) + 16), dict(iters=0), dict(buf=0),
+                dict(buf=buf.data_ptr() + 4), dict(out=0)):
+        kw = dict(buf=buf.data_ptr(), nbytes=1 << 20, region=64 << 10, iters=1, out=out.data_ptr())
+        kw.update(bad)
+        with pytest.raises(S.SgprsError):
+            pool.load_probe(1, kw["buf"], kw["nbytes"], kw["region"], kw["iters"], kw["out"])
+    pool.sync()
+    pool.destroy()
+
+
 def test_graph_launch_keeps_to_the_partition():
     """A kernel recorded by stream capture and launched as a HIP graph on a partition's stream
     runs on that partition's CUs only (sgprs_task_run replays captured tasks this way)."""
