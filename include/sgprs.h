@@ -8,7 +8,8 @@
  * partitions execute: the pool itself (CU-masked HIP streams) and the six
  * stages of the paper's benchmark task, ResNet18 on a 224x224 input
  * ("Simulation Results"), as hand-written HIP kernels.  The scheduler that
- * decides which stage goes to which partition is not part of this library.
+ * decides which stage goes to which partition is host logic at the end of this
+ * header (sgprs_sched_*); it launches nothing by itself.
  *
  * Conventions
  *  - Every call returns an int status: SGPRS_OK (0) or a negative SGPRS_ERR_*.
@@ -287,6 +288,63 @@ int sgprs_task_kernel_times(sgprs_task_t *task, int stage, int *count, int *kind
  * profiler rows; points into a small ring of static buffers (copy it before
  * asking for more than eight names). */
 const char *sgprs_kernel_name(int kind, int variant);
+
+/* ------------------------------------------------------------ scheduler --
+ * The paper's scheduler ("Real-Time Scheduler Design"), host logic only: it
+ * launches nothing and reads no clock; the caller reports releases and
+ * completions with their times (seconds, any origin) and asks which stage may
+ * start.  Not thread-safe: one thread drives one scheduler.
+ *
+ * Offline phase, at sgprs_sched_add_task ("Two Level Priority Assignment",
+ * "WCET and Virtual Deadline Assignment"): the last stage of a task is high
+ * priority, the others low; stage j's relative deadline is
+ * D * C^j / sum_k C^k (C = wcet, D = rel_deadline).
+ * Online phase ("Absolute Deadline Assignment", "Context Assignment", "Stage
+ * Queuing"): stage j of a job released at r has the absolute deadline
+ * r + D^0 + .. + D^j.  On release a stage is assigned to a context: one with an
+ * empty queue (waiting or running stages) first; else, among the contexts
+ * where now + backlog + C^j <= deadline (backlog = WCETs waiting plus what is
+ * left of the running ones), the one with the fewest stages queued; else the
+ * one with the smallest backlog; ties to the lowest index.  A context runs up
+ * to lanes_per_context stages at once (the paper: 4), the first lanes/2 lanes
+ * for high-priority stages, the rest for medium and low ones (one lane: shared
+ * by all).  A low-priority stage whose predecessor completed after its
+ * deadline is medium.  A free lane takes, of the waiting stages of its class,
+ * the highest level, then the earliest deadline, then the earliest release. */
+typedef struct sgprs_sched sgprs_sched_t;
+typedef struct {
+    int task, job, stage;   /* what to run */
+    int context, lane;      /* where: lane < lanes_per_context */
+    int level;              /* 0 high, 1 medium, 2 low */
+    double deadline;        /* absolute */
+    double wcet;
+} sgprs_dispatch_t;
+typedef struct {
+    long long jobs_released, jobs_completed, jobs_missed; /* missed: last stage completed after r + D */
+    long long stages_completed, stages_missed;
+} sgprs_sched_stats_t;
+
+/* n_contexts in [1,64], lanes_per_context in [1,8]. */
+int sgprs_sched_create(int n_contexts, int lanes_per_context, sgprs_sched_t **out);
+void sgprs_sched_destroy(sgprs_sched_t *sched);
+/* wcet: HOST double[n_stages], all > 0 (seconds); period, rel_deadline > 0.
+ * *task_id receives the task's index (0, 1, ...). */
+int sgprs_sched_add_task(sgprs_sched_t *sched, int n_stages, const double *wcet, double period,
+                         double rel_deadline, int *task_id);
+/* The task's relative virtual deadlines: HOST double[capacity >= n_stages]. */
+int sgprs_sched_virtual_deadlines(const sgprs_sched_t *sched, int task, int capacity, double *out);
+/* A job of `task` is released at `now`: its first stage is queued.  *job_id
+ * (may be NULL) receives the job's number (0, 1, ... per task). */
+int sgprs_sched_release(sgprs_sched_t *sched, int task, double now, int *job_id);
+/* Returns 1 and fills *out if a waiting stage may start at `now` (its lane is
+ * then busy until sgprs_sched_complete), 0 if none can, < 0 on error.  Call it
+ * until it returns 0.  Contexts and lanes are scanned in index order. */
+int sgprs_sched_next(sgprs_sched_t *sched, double now, sgprs_dispatch_t *out);
+/* The running stage (task, job, stage) completed at `now`: its lane is free,
+ * the deadline is checked (*missed, may be NULL: 1 if now > deadline), and the
+ * job's next stage, if any, is released at `now`.  Error if it is not running. */
+int sgprs_sched_complete(sgprs_sched_t *sched, int task, int job, int stage, double now, int *missed);
+int sgprs_sched_get_stats(const sgprs_sched_t *sched, sgprs_sched_stats_t *out);
 
 #ifdef __cplusplus
 }

@@ -15,7 +15,7 @@ import numpy as np
 
 __all__ = [
     "SgprsError", "SGPRS_F32", "SGPRS_BF16", "SGPRS_POOL_OVERSUBSCRIBE", "SGPRS_POOL_BLOCKED_LAYOUT",
-    "ConvDesc", "lib", "lib_path", "Pool", "Task",
+    "ConvDesc", "lib", "lib_path", "Pool", "Task", "Sched", "Dispatch", "SchedStats",
     "sgprs_version", "sgprs_status_string", "sgprs_last_error", "sgprs_build_cu_mask",
     "sgprs_fold_bn", "sgprs_conv_packed_weight_bytes", "sgprs_pack_conv_weights",
     "sgprs_unpack_conv_weights", "sgprs_conv2d_workspace", "sgprs_conv2d", "sgprs_maxpool2d",
@@ -51,6 +51,16 @@ def lib_path() -> str:
 
 
 _lib = None
+
+
+class Dispatch(ctypes.Structure):
+    _fields_ = [("task", c_int), ("job", c_int), ("stage", c_int), ("context", c_int), ("lane", c_int),
+                ("level", c_int), ("deadline", c_double), ("wcet", c_double)]
+
+
+class SchedStats(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_longlong) for n in ("jobs_released", "jobs_completed", "jobs_missed",
+                                                 "stages_completed", "stages_missed")]
 
 
 def lib():
@@ -104,6 +114,14 @@ def lib():
         "sgprs_task_set_graph_replay": (c_int, [vp, c_int]),
         "sgprs_task_kernel_times": (c_int, [vp, c_int, ip, ip, ip, fp, POINTER(c_double), POINTER(c_double)]),
         "sgprs_kernel_name": (c_char_p, [c_int, c_int]),
+        "sgprs_sched_create": (c_int, [c_int, c_int, POINTER(vp)]),
+        "sgprs_sched_destroy": (None, [vp]),
+        "sgprs_sched_add_task": (c_int, [vp, c_int, POINTER(c_double), c_double, c_double, ip]),
+        "sgprs_sched_virtual_deadlines": (c_int, [vp, c_int, c_int, POINTER(c_double)]),
+        "sgprs_sched_release": (c_int, [vp, c_int, c_double, ip]),
+        "sgprs_sched_next": (c_int, [vp, c_double, POINTER(Dispatch)]),
+        "sgprs_sched_complete": (c_int, [vp, c_int, c_int, c_int, c_double, ip]),
+        "sgprs_sched_get_stats": (c_int, [vp, POINTER(SchedStats)]),
     }
     for name, (res, args) in sig.items():
         f = getattr(L, name)
@@ -351,6 +369,56 @@ class Task:
         if self.handle:
             h, self.handle = self.handle, None
             _check(lib().sgprs_task_destroy(h))
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+class Sched:
+    """sgprs_sched_*: the scheduler core (host logic; the caller supplies the clock)."""
+
+    def __init__(self, n_contexts: int, lanes_per_context: int):
+        h = c_void_p()
+        _check(lib().sgprs_sched_create(n_contexts, lanes_per_context, ctypes.byref(h)))
+        self.handle = h
+
+    def add_task(self, wcet, period: float, rel_deadline: float) -> int:
+        w = (c_double * len(wcet))(*[float(v) for v in wcet])
+        tid = c_int()
+        _check(lib().sgprs_sched_add_task(self.handle, len(wcet), w, period, rel_deadline, ctypes.byref(tid)))
+        return tid.value
+
+    def virtual_deadlines(self, task: int, n_stages: int):
+        out = (c_double * n_stages)()
+        _check(lib().sgprs_sched_virtual_deadlines(self.handle, task, n_stages, out))
+        return list(out)
+
+    def release(self, task: int, now: float) -> int:
+        job = c_int()
+        _check(lib().sgprs_sched_release(self.handle, task, now, ctypes.byref(job)))
+        return job.value
+
+    def next(self, now: float):
+        d = Dispatch()
+        return d if _check(lib().sgprs_sched_next(self.handle, now, ctypes.byref(d))) == 1 else None
+
+    def complete(self, task: int, job: int, stage: int, now: float) -> bool:
+        m = c_int()
+        _check(lib().sgprs_sched_complete(self.handle, task, job, stage, now, ctypes.byref(m)))
+        return bool(m.value)
+
+    def stats(self) -> dict:
+        st = SchedStats()
+        _check(lib().sgprs_sched_get_stats(self.handle, ctypes.byref(st)))
+        return {n: int(getattr(st, n)) for n, _ in SchedStats._fields_}
+
+    def destroy(self) -> None:
+        if self.handle:
+            h, self.handle = self.handle, None
+            lib().sgprs_sched_destroy(h)
 
     def __del__(self):
         try:

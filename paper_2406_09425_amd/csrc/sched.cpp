@@ -1,0 +1,242 @@
+// The SGPRS scheduler core: host-side decisions only, no GPU call and no clock of its own
+// (the caller passes the time, so the same code serves a real run and a simulated one).
+//
+// Offline phase ("Two Level Priority Assignment", "WCET and Virtual Deadline Assignment"):
+// a task's last stage is high priority, the others low; stage j gets the share
+// D * C^j / sum_k C^k of the task's relative deadline.
+// Online phase ("Absolute Deadline Assignment", "Context Assignment", "Stage Queuing"):
+// a released stage gets the absolute deadline r + D^0 + .. + D^j (r = its job's release), is
+// assigned to a context (an empty queue first, else the shortest queue among the contexts on
+// which it would still meet its deadline, else the earliest finish), and waits there.  A
+// context runs up to `lanes` stages at once, the first lanes / 2 lanes for high-priority
+// stages, the others for medium and low ones; a low-priority stage whose predecessor missed
+// its deadline is medium; inside a level the earliest deadline goes first.
+#include <algorithm>
+#include <cstdint>
+#include <new>
+#include <unordered_map>
+#include <vector>
+
+#include "internal.h"
+
+namespace {
+
+enum { kHigh = 0, kMedium = 1, kLow = 2 };
+
+struct SchedTask {
+    std::vector<double> wcet, vdl;
+    double period = 0, deadline = 0;
+    int next_job = 0;
+};
+
+struct StageRec {
+    int task = 0, job = 0, stage = 0, level = kLow, context = 0, lane = -1;
+    double wcet = 0, deadline = 0, start = 0;
+    long long seq = 0;
+};
+
+struct JobRec {
+    double release = 0;
+    bool prev_missed = false;
+};
+
+struct SchedContext {
+    std::vector<StageRec> waiting;
+    std::vector<StageRec> running;  // one slot per lane
+    std::vector<char> busy;
+};
+
+inline long long job_key(int task, int job) { return ((long long)task << 32) | (unsigned)job; }
+
+}  // namespace
+
+struct sgprs_sched {
+    int n_contexts = 0, lanes = 0, n_high = 0;
+    std::vector<SchedTask> tasks;
+    std::vector<SchedContext> ctx;
+    std::unordered_map<long long, JobRec> jobs;
+    long long seq = 0;
+    sgprs_sched_stats_t stats{};
+
+    double backlog(int c, double now) const
+    {
+        double b = 0.0;
+        for (const StageRec& s : ctx[c].waiting) b += s.wcet;
+        for (int l = 0; l < lanes; ++l)
+            if (ctx[c].busy[l]) b += std::max(0.0, ctx[c].running[l].wcet - (now - ctx[c].running[l].start));
+        return b;
+    }
+    int queue_len(int c) const
+    {
+        int n = (int)ctx[c].waiting.size();
+        for (int l = 0; l < lanes; ++l) n += ctx[c].busy[l] ? 1 : 0;
+        return n;
+    }
+    int assign_context(double now, double wcet, double deadline) const
+    {
+        for (int c = 0; c < n_contexts; ++c)
+            if (queue_len(c) == 0) return c;
+        int best = -1;
+        for (int c = 0; c < n_contexts; ++c)
+            if (now + backlog(c, now) + wcet <= deadline && (best < 0 || queue_len(c) < queue_len(best))) best = c;
+        if (best >= 0) return best;
+        for (int c = 0; c < n_contexts; ++c)
+            if (best < 0 || now + backlog(c, now) < now + backlog(best, now)) best = c;
+        return best;
+    }
+    void release_stage(int task, int job, int stage, double now)
+    {
+        const SchedTask& t = tasks[task];
+        const JobRec& j = jobs[job_key(task, job)];
+        StageRec s;
+        s.task = task; s.job = job; s.stage = stage;
+        s.level = stage == (int)t.wcet.size() - 1 ? kHigh : (j.prev_missed ? kMedium : kLow);
+        s.wcet = t.wcet[stage];
+        double d = j.release;
+        for (int k = 0; k <= stage; ++k) d += t.vdl[k];
+        s.deadline = d;
+        s.seq = seq++;
+        s.context = assign_context(now, s.wcet, s.deadline);
+        ctx[s.context].waiting.push_back(s);
+    }
+};
+
+using namespace sgprs;
+
+extern "C" {
+
+int sgprs_sched_create(int n_contexts, int lanes_per_context, sgprs_sched_t** out)
+{
+    if (!out) return fail(SGPRS_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (n_contexts < 1 || n_contexts > 64) return fail(SGPRS_ERR_INVALID_ARG, "n_contexts %d outside [1,64]", n_contexts);
+    if (lanes_per_context < 1 || lanes_per_context > 8)
+        return fail(SGPRS_ERR_INVALID_ARG, "lanes_per_context %d outside [1,8]", lanes_per_context);
+    sgprs_sched* s = new (std::nothrow) sgprs_sched;
+    if (!s) return fail(SGPRS_ERR_OOM, "scheduler allocation failed");
+    s->n_contexts = n_contexts;
+    s->lanes = lanes_per_context;
+    s->n_high = lanes_per_context / 2;
+    s->ctx.resize(n_contexts);
+    for (SchedContext& c : s->ctx) {
+        c.running.resize(lanes_per_context);
+        c.busy.assign(lanes_per_context, 0);
+    }
+    *out = s;
+    return SGPRS_OK;
+}
+
+void sgprs_sched_destroy(sgprs_sched_t* s) { delete s; }
+
+int sgprs_sched_add_task(sgprs_sched_t* s, int n_stages, const double* wcet, double period, double rel_deadline, int* task_id)
+{
+    if (!s || !wcet || !task_id) return fail(SGPRS_ERR_INVALID_ARG, "NULL argument");
+    if (n_stages < 1 || n_stages > 4096) return fail(SGPRS_ERR_INVALID_ARG, "n_stages %d outside [1,4096]", n_stages);
+    if (!(period > 0) || !(rel_deadline > 0)) return fail(SGPRS_ERR_INVALID_ARG, "period and deadline must be positive");
+    double total = 0.0;
+    for (int j = 0; j < n_stages; ++j) {
+        if (!(wcet[j] > 0)) return fail(SGPRS_ERR_INVALID_ARG, "wcet[%d] must be positive", j);
+        total += wcet[j];
+    }
+    SchedTask t;
+    t.wcet.assign(wcet, wcet + n_stages);
+    t.vdl.resize(n_stages);
+    for (int j = 0; j < n_stages; ++j) t.vdl[j] = rel_deadline * wcet[j] / total;
+    t.period = period;
+    t.deadline = rel_deadline;
+    s->tasks.push_back(t);
+    *task_id = (int)s->tasks.size() - 1;
+    return SGPRS_OK;
+}
+
+int sgprs_sched_virtual_deadlines(const sgprs_sched_t* s, int task, int capacity, double* out)
+{
+    if (!s || !out) return fail(SGPRS_ERR_INVALID_ARG, "NULL argument");
+    if (task < 0 || task >= (int)s->tasks.size()) return fail(SGPRS_ERR_INVALID_ARG, "task %d does not exist", task);
+    const SchedTask& t = s->tasks[task];
+    if (capacity < (int)t.vdl.size()) return fail(SGPRS_ERR_INVALID_ARG, "capacity %d below %zu stages", capacity, t.vdl.size());
+    std::copy(t.vdl.begin(), t.vdl.end(), out);
+    return SGPRS_OK;
+}
+
+int sgprs_sched_release(sgprs_sched_t* s, int task, double now, int* job_id)
+{
+    if (!s) return fail(SGPRS_ERR_INVALID_ARG, "sched is NULL");
+    if (task < 0 || task >= (int)s->tasks.size()) return fail(SGPRS_ERR_INVALID_ARG, "task %d does not exist", task);
+    const int job = s->tasks[task].next_job++;
+    JobRec j;
+    j.release = now;
+    s->jobs[job_key(task, job)] = j;
+    ++s->stats.jobs_released;
+    s->release_stage(task, job, 0, now);
+    if (job_id) *job_id = job;
+    return SGPRS_OK;
+}
+
+int sgprs_sched_next(sgprs_sched_t* s, double now, sgprs_dispatch_t* out)
+{
+    if (!s || !out) return fail(SGPRS_ERR_INVALID_ARG, "NULL argument");
+    for (int c = 0; c < s->n_contexts; ++c) {
+        SchedContext& cx = s->ctx[c];
+        if (cx.waiting.empty()) continue;
+        for (int lane = 0; lane < s->lanes; ++lane) {
+            if (cx.busy[lane]) continue;
+            int best = -1;
+            for (int i = 0; i < (int)cx.waiting.size(); ++i) {
+                const StageRec& w = cx.waiting[i];
+                if (s->lanes > 1 && (lane < s->n_high) != (w.level == kHigh)) continue;  // lane classes
+                if (best < 0) { best = i; continue; }
+                const StageRec& b = cx.waiting[best];
+                if (w.level != b.level ? w.level < b.level : w.deadline != b.deadline ? w.deadline < b.deadline : w.seq < b.seq)
+                    best = i;
+            }
+            if (best < 0) continue;
+            StageRec r = cx.waiting[best];
+            cx.waiting.erase(cx.waiting.begin() + best);
+            r.lane = lane;
+            r.start = now;
+            cx.running[lane] = r;
+            cx.busy[lane] = 1;
+            out->task = r.task; out->job = r.job; out->stage = r.stage; out->context = c; out->lane = lane;
+            out->level = r.level; out->deadline = r.deadline; out->wcet = r.wcet;
+            return 1;
+        }
+    }
+    return 0;
+}
+
+int sgprs_sched_complete(sgprs_sched_t* s, int task, int job, int stage, double now, int* missed_out)
+{
+    if (!s) return fail(SGPRS_ERR_INVALID_ARG, "sched is NULL");
+    for (int c = 0; c < s->n_contexts; ++c)
+        for (int lane = 0; lane < s->lanes; ++lane) {
+            SchedContext& cx = s->ctx[c];
+            if (!cx.busy[lane]) continue;
+            const StageRec r = cx.running[lane];
+            if (r.task != task || r.job != job || r.stage != stage) continue;
+            cx.busy[lane] = 0;
+            const bool missed = now > r.deadline;
+            ++s->stats.stages_completed;
+            s->stats.stages_missed += missed ? 1 : 0;
+            if (stage + 1 < (int)s->tasks[task].wcet.size()) {
+                s->jobs[job_key(task, job)].prev_missed = missed;
+                s->release_stage(task, job, stage + 1, now);
+            } else {
+                ++s->stats.jobs_completed;
+                s->stats.jobs_missed += missed ? 1 : 0;
+                s->jobs.erase(job_key(task, job));
+            }
+            if (missed_out) *missed_out = missed ? 1 : 0;
+            return SGPRS_OK;
+        }
+    return fail(SGPRS_ERR_INVALID_ARG, "stage %d of job %d of task %d is not running", stage, job, task);
+}
+
+int sgprs_sched_get_stats(const sgprs_sched_t* s, sgprs_sched_stats_t* out)
+{
+    if (!s || !out) return fail(SGPRS_ERR_INVALID_ARG, "NULL argument");
+    *out = s->stats;
+    return SGPRS_OK;
+}
+
+}  // extern "C"
