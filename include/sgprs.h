@@ -346,6 +346,34 @@ int sgprs_sched_next(sgprs_sched_t *sched, double now, sgprs_dispatch_t *out);
 int sgprs_sched_complete(sgprs_sched_t *sched, int task, int job, int stage, double now, int *missed);
 int sgprs_sched_get_stats(const sgprs_sched_t *sched, sgprs_sched_stats_t *out);
 
+/* The periodic-release experiment of "Simulation Results" on the real pool.
+ * tasks[i] (HOST array of n_tasks handles, n_tasks = the scheduler's task
+ * count, stage counts equal) is the DNN behind the scheduler's task i;
+ * inputs[i] / logits[i] are its DEVICE input and fp32 logits buffers for
+ * `batch` images.  Lane l of context c is partition c * lanes + l of `pool`,
+ * which must have at least n_contexts * lanes partitions (give the lanes of a
+ * context the same CU mask; contexts may overlap: an over-subscribed pool).
+ * Job k of task i is released at offsets[i] + k * period_i (offsets HOST
+ * double[n_tasks] or NULL = 0) while that is < duration_s seconds on the host's
+ * steady clock; the calling thread releases, dispatches (sgprs_stage_run) and
+ * polls one event per lane for completions until every job has finished.  A
+ * job released while the task's previous job is still in flight is dropped
+ * (a task holds one job's activations) and counts as a miss.
+ * report: elapsed_s = max(duration_s, time of the last completion), fps =
+ * completed jobs / elapsed_s, dmr = (missed + dropped) / releases, response
+ * times from release to completion of the last stage.  Blocking; the
+ * scheduler must have no job in flight when called. */
+typedef struct {
+    double elapsed_s;
+    long long releases, dropped;
+    sgprs_sched_stats_t sched; /* of this run only */
+    double fps, dmr;
+    double mean_response_s, max_response_s;
+} sgprs_run_report_t;
+int sgprs_sched_run_periodic(sgprs_sched_t *sched, sgprs_pool_t *pool, sgprs_task_t *const *tasks,
+                             int n_tasks, const void *const *inputs, float *const *logits, int batch,
+                             const double *offsets, double duration_s, sgprs_run_report_t *report);
+
 #ifdef __cplusplus
 }
 #endif

@@ -15,7 +15,7 @@ import numpy as np
 
 __all__ = [
     "SgprsError", "SGPRS_F32", "SGPRS_BF16", "SGPRS_POOL_OVERSUBSCRIBE", "SGPRS_POOL_BLOCKED_LAYOUT",
-    "ConvDesc", "lib", "lib_path", "Pool", "Task", "Sched", "Dispatch", "SchedStats",
+    "ConvDesc", "lib", "lib_path", "Pool", "Task", "Sched", "Dispatch", "SchedStats", "RunReport",
     "sgprs_version", "sgprs_status_string", "sgprs_last_error", "sgprs_build_cu_mask",
     "sgprs_fold_bn", "sgprs_conv_packed_weight_bytes", "sgprs_pack_conv_weights",
     "sgprs_unpack_conv_weights", "sgprs_conv2d_workspace", "sgprs_conv2d", "sgprs_maxpool2d",
@@ -61,6 +61,12 @@ class Dispatch(ctypes.Structure):
 class SchedStats(ctypes.Structure):
     _fields_ = [(n, ctypes.c_longlong) for n in ("jobs_released", "jobs_completed", "jobs_missed",
                                                  "stages_completed", "stages_missed")]
+
+
+class RunReport(ctypes.Structure):
+    _fields_ = [("elapsed_s", c_double), ("releases", ctypes.c_longlong), ("dropped", ctypes.c_longlong),
+                ("sched", SchedStats), ("fps", c_double), ("dmr", c_double), ("mean_response_s", c_double),
+                ("max_response_s", c_double)]
 
 
 def lib():
@@ -122,6 +128,8 @@ def lib():
         "sgprs_sched_next": (c_int, [vp, c_double, POINTER(Dispatch)]),
         "sgprs_sched_complete": (c_int, [vp, c_int, c_int, c_int, c_double, ip]),
         "sgprs_sched_get_stats": (c_int, [vp, POINTER(SchedStats)]),
+        "sgprs_sched_run_periodic": (c_int, [vp, vp, POINTER(vp), c_int, POINTER(vp), POINTER(vp), c_int, POINTER(c_double), c_double,
+                                             POINTER(RunReport)]),
     }
     for name, (res, args) in sig.items():
         f = getattr(L, name)
@@ -409,6 +417,18 @@ class Sched:
         m = c_int()
         _check(lib().sgprs_sched_complete(self.handle, task, job, stage, now, ctypes.byref(m)))
         return bool(m.value)
+
+    def run_periodic(self, pool, tasks, input_ptrs, logits_ptrs, batch: int, duration_s: float, offsets=None) -> dict:
+        n = len(tasks)
+        th = (c_void_p * n)(*[getattr(t.handle, "value", t.handle) for t in tasks])
+        ins = (c_void_p * n)(*input_ptrs)
+        outs = (c_void_p * n)(*logits_ptrs)
+        off = (c_double * n)(*[float(v) for v in offsets]) if offsets is not None else None
+        rep = RunReport()
+        _check(lib().sgprs_sched_run_periodic(self.handle, _h(pool), th, n, ins, outs, batch, off, duration_s, ctypes.byref(rep)))
+        out = {k: getattr(rep, k) for k in ("elapsed_s", "releases", "dropped", "fps", "dmr", "mean_response_s", "max_response_s")}
+        out.update({k: int(getattr(rep.sched, k)) for k, _ in SchedStats._fields_})
+        return out
 
     def stats(self) -> dict:
         st = SchedStats()

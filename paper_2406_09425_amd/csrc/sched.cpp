@@ -12,6 +12,7 @@
 // stages, the others for medium and low ones; a low-priority stage whose predecessor missed
 // its deadline is medium; inside a level the earliest deadline goes first.
 #include <algorithm>
+#include <chrono>
 #include <cstdint>
 #include <new>
 #include <unordered_map>
@@ -236,6 +237,124 @@ int sgprs_sched_get_stats(const sgprs_sched_t* s, sgprs_sched_stats_t* out)
 {
     if (!s || !out) return fail(SGPRS_ERR_INVALID_ARG, "NULL argument");
     *out = s->stats;
+    return SGPRS_OK;
+}
+
+// The periodic-release experiment of "Simulation Results" on the real pool: one host thread
+// releases the jobs, asks the scheduler what may start, enqueues those stages on the lane's
+// partition and polls one event per lane for completions.
+int sgprs_sched_run_periodic(sgprs_sched_t* s, sgprs_pool_t* pool, sgprs_task_t* const* tasks, int n_tasks,
+                             const void* const* inputs, float* const* logits, int batch, const double* offsets,
+                             double duration_s, sgprs_run_report_t* report)
+{
+    if (!s || !pool || !tasks || !inputs || !logits || !report) return fail(SGPRS_ERR_INVALID_ARG, "NULL argument");
+    if (n_tasks != (int)s->tasks.size()) return fail(SGPRS_ERR_INVALID_ARG, "%d tasks given, the scheduler knows %zu", n_tasks, s->tasks.size());
+    if (!(duration_s > 0) || duration_s > 600) return fail(SGPRS_ERR_INVALID_ARG, "duration_s outside (0,600]");
+    if (!s->jobs.empty()) return fail(SGPRS_ERR_INVALID_ARG, "the scheduler still has jobs in flight");
+    int n_p = 0, cpp = 0, total = 0, nx = 0, rc;
+    if ((rc = sgprs_pool_info(pool, &n_p, &cpp, &total, &nx))) return rc;
+    if (n_p < s->n_contexts * s->lanes)
+        return fail(SGPRS_ERR_INVALID_ARG, "the pool has %d partitions, %d contexts x %d lanes need %d", n_p, s->n_contexts, s->lanes,
+                    s->n_contexts * s->lanes);
+    for (int i = 0; i < n_tasks; ++i) {
+        if (!tasks[i] || !inputs[i] || !logits[i]) return fail(SGPRS_ERR_INVALID_ARG, "task %d: NULL handle or buffer", i);
+        if (sgprs_task_num_stages(tasks[i]) != (int)s->tasks[i].wcet.size())
+            return fail(SGPRS_ERR_INVALID_ARG, "task %d has %d stages, the scheduler knows %zu", i, sgprs_task_num_stages(tasks[i]),
+                        s->tasks[i].wcet.size());
+    }
+    struct Slot { bool busy = false; int task = 0, job = 0, stage = 0; hipEvent_t ev = nullptr; hipStream_t stream = nullptr; };
+    std::vector<Slot> slots((size_t)s->n_contexts * s->lanes);
+    auto cleanup = [&]() { for (Slot& sl : slots) if (sl.ev) (void)hipEventDestroy(sl.ev); };
+    for (size_t p = 0; p < slots.size(); ++p) {
+        slots[p].stream = (hipStream_t)sgprs_pool_stream(pool, (int)p);
+        if (hipEventCreateWithFlags(&slots[p].ev, hipEventDisableTiming) != hipSuccess) {
+            cleanup();
+            return fail(SGPRS_ERR_HIP, "hipEventCreateWithFlags failed");
+        }
+    }
+    std::vector<long long> released(n_tasks, 0);
+    std::vector<char> active(n_tasks, 0);
+    std::vector<double> job_release(n_tasks, 0.0);
+    const sgprs_sched_stats_t before = s->stats;
+    long long releases = 0, dropped = 0, in_flight = 0;
+    double resp_sum = 0.0, resp_max = 0.0, last_done = 0.0;
+    const auto t0 = std::chrono::steady_clock::now();
+    auto clock_s = [&]() { return std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count(); };
+    int status = SGPRS_OK;
+    for (;;) {
+        const double now = clock_s();
+        // completions
+        for (Slot& sl : slots) {
+            if (!sl.busy) continue;
+            const hipError_t q = hipEventQuery(sl.ev);
+            if (q == hipErrorNotReady) continue;
+            if (q != hipSuccess) { status = fail(SGPRS_ERR_HIP, "hipEventQuery: %s", hipGetErrorString(q)); break; }
+            sl.busy = false;
+            if ((status = sgprs_sched_complete(s, sl.task, sl.job, sl.stage, now, nullptr))) break;
+            if (sl.stage + 1 == (int)s->tasks[sl.task].wcet.size()) {
+                active[sl.task] = 0;
+                --in_flight;
+                const double r = now - job_release[sl.task];
+                resp_sum += r;
+                resp_max = std::max(resp_max, r);
+                last_done = now;
+            }
+        }
+        if (status) break;
+        // releases: job k of task i at offsets[i] + k * period; a job whose predecessor is still in
+        // flight is dropped (the task's buffers hold one job at a time) and counted as a miss
+        bool more_releases = false;
+        for (int i = 0; i < n_tasks; ++i) {
+            for (;;) {
+                const double r = (offsets ? offsets[i] : 0.0) + (double)released[i] * s->tasks[i].period;
+                if (r >= duration_s) break;
+                more_releases = true;
+                if (r > now) break;
+                ++released[i];
+                ++releases;
+                if (active[i]) { ++dropped; continue; }
+                if ((status = sgprs_sched_release(s, i, r, nullptr))) break;
+                active[i] = 1;
+                job_release[i] = r;
+                ++in_flight;
+            }
+            if (status) break;
+        }
+        if (status) break;
+        // dispatches
+        sgprs_dispatch_t d;
+        int got;
+        while ((got = sgprs_sched_next(s, now, &d)) == 1) {
+            Slot& sl = slots[(size_t)d.context * s->lanes + d.lane];
+            const int last = (int)s->tasks[d.task].wcet.size() - 1;
+            const void* in = d.stage == 0 ? inputs[d.task] : sgprs_task_stage_output(tasks[d.task], d.stage - 1);
+            void* out = d.stage == last ? (void*)logits[d.task] : (void*)sgprs_task_stage_output(tasks[d.task], d.stage);
+            if ((status = sgprs_stage_run(tasks[d.task], d.stage, batch, in, out, pool, d.context * s->lanes + d.lane))) break;
+            if (hipEventRecord(sl.ev, sl.stream) != hipSuccess) { status = fail(SGPRS_ERR_HIP, "hipEventRecord failed"); break; }
+            sl.busy = true; sl.task = d.task; sl.job = d.job; sl.stage = d.stage;
+        }
+        if (got < 0) status = got;
+        if (status) break;
+        if (!more_releases && in_flight == 0) break;
+        if (now > duration_s + 30.0) { status = fail(SGPRS_ERR_HIP, "jobs still in flight 30 s after the last release"); break; }
+    }
+    // whatever happened, nothing of ours stays queued behind the caller's back
+    for (Slot& sl : slots)
+        if (sl.busy) (void)hipEventSynchronize(sl.ev);
+    cleanup();
+    if (status) return status;
+    report->elapsed_s = std::max(last_done, duration_s);
+    report->releases = releases;
+    report->dropped = dropped;
+    report->sched.jobs_released = s->stats.jobs_released - before.jobs_released;
+    report->sched.jobs_completed = s->stats.jobs_completed - before.jobs_completed;
+    report->sched.jobs_missed = s->stats.jobs_missed - before.jobs_missed;
+    report->sched.stages_completed = s->stats.stages_completed - before.stages_completed;
+    report->sched.stages_missed = s->stats.stages_missed - before.stages_missed;
+    report->fps = (double)report->sched.jobs_completed / report->elapsed_s;
+    report->dmr = releases ? (double)(report->sched.jobs_missed + dropped) / (double)releases : 0.0;
+    report->mean_response_s = report->sched.jobs_completed ? resp_sum / (double)report->sched.jobs_completed : 0.0;
+    report->max_response_s = resp_max;
     return SGPRS_OK;
 }
 
