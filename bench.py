@@ -68,13 +68,14 @@ class Hip:
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--no-extras", action="store_true", help="skip batch-1, CU sweep and multi-tenant legs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle CPU baseline")
     ap.add_argument("--cpu-sample", type=int, default=24, help="images of the batch the oracle is timed on")
     ap.add_argument("--periodic-only", action="store_true", help="only the periodic-task scheduler experiment")
+    ap.add_argument("--probes-only", action="store_true", help="only the sustained MFMA and load-path probes")
     ap.add_argument("--membound-only", action="store_true",
                     help="run only the memory-bound operator leg (for profiling it); prints its own JSON line")
     ap.add_argument("--copy-calib", action="store_true",
@@ -109,6 +110,12 @@ def main():
         S.sgprs_bn_relu(S.SGPRS_BF16, nel // 64, 64, src.data_ptr(), one.data_ptr(), zero.data_ptr(), dst.data_ptr(),
                         pool, 0)
         pool.sync()
+
+    if args.probes_only:
+        print(json.dumps(dict(sustained_mfma=leg_mfma_probe(S, hip, torch, pool, stream, total_cus),
+                              sustained_load_to_lds=leg_load_probe(S, hip, torch, pool, stream, total_cus))), flush=True)
+        pool.destroy()
+        return
 
     if args.periodic_only:
         print(json.dumps(dict(periodic_tasks=leg_periodic(S, hip, torch, total_cus, nhwc))), flush=True)
@@ -156,7 +163,7 @@ def main():
     task.set_profiling(True)
     agg = {}      # kernel name -> [time_s, flops, bytes, launches]
     stages = []
-    prof_steps = min(args.steps, 20)
+    prof_steps = min(args.steps, 100)
     per_stage = [dict(ms=0.0, flops=0.0, bytes=0.0, roof_s=0.0) for _ in range(6)]
     for _ in range(prof_steps):
         step()
@@ -462,7 +469,7 @@ def leg_load_probe(S, hip, torch, pool, stream, total_cus, iters=2048, reps=3):
     return res
 
 
-def leg_membound(S, hip, torch, pool, stream, reps=20):
+def leg_membound(S, hip, torch, pool, stream, reps=100):
     """Bandwidth kernels at batch-64 sizes, bf16, on the full-GPU partition.  Each launch works on its
     own buffers out of a rotating set larger than the 256 MB last-level cache, so the bytes really
     come from and go to HBM.  GB/s = algorithmic bytes / time."""
@@ -471,7 +478,7 @@ def leg_membound(S, hip, torch, pool, stream, reps=20):
 
     def timed(name, nbytes, make, run):
         sets = [make() for _ in range(max(2, int(700e6 // nbytes) + 1))]
-        for k in range(2):
+        for k in range(min(reps, 30)):  # long enough for the chip to settle in its loaded state
             run(sets[k % len(sets)])
         pool.sync()
         e0, e1 = hip.event(), hip.event()
@@ -501,7 +508,7 @@ def leg_membound(S, hip, torch, pool, stream, reps=20):
     return res
 
 
-def leg_oversubscribed(S, torch, total_cus, nhwc, headline_ips, rounds=30):
+def leg_oversubscribed(S, torch, total_cus, nhwc, headline_ips, rounds=300):
     """Two bf16 instances on a pool of two partitions that BOTH span all CUs (an
     over-subscribed context pool): the tails, prologues and idle CUs of one
     instance's kernels are filled by the other's workgroups.  Measured with two
@@ -527,7 +534,7 @@ def leg_oversubscribed(S, torch, total_cus, nhwc, headline_ips, rounds=30):
                     dst = lgs[i].data_ptr() if j == 5 else tasks[i].stage_output(j)
                     tasks[i].stage_run(j, n, src, dst, pool, i)
 
-        for _ in range(5):
+        for _ in range(50):
             issue_all()
         pool.sync()
         t0 = time.perf_counter()
@@ -605,7 +612,7 @@ def leg_periodic(S, hip, torch, total_cus, nhwc, n_list=(64, 128, 192, 256, 320,
     return dict(contexts=n_ctx, lanes_per_context=lanes, task_fps=fps, duration_s=duration, results=res)
 
 
-def leg_pool_scaling(S, torch, total_cus, nhwc, instances=8, rounds=40):
+def leg_pool_scaling(S, torch, total_cus, nhwc, instances=8, rounds=150):
     """Eight bf16 batch-1 instances spread round-robin over pools of 1, 2, 3, 4 and 8 equal
     partitions (the paper's question: how does throughput grow with the number of contexts?).
     Every instance is issued with sgprs_task_run from one host thread, i.e. replayed as a HIP
@@ -625,7 +632,7 @@ def leg_pool_scaling(S, torch, total_cus, nhwc, instances=8, rounds=40):
             for i in range(instances):
                 tasks[i].run(1, xs[i].data_ptr(), lgs[i].data_ptr(), pool, i % n_p)
 
-        for _ in range(5):
+        for _ in range(20):
             issue()
         pool.sync()
         t0 = time.perf_counter()
@@ -643,7 +650,7 @@ def leg_pool_scaling(S, torch, total_cus, nhwc, instances=8, rounds=40):
     return res
 
 
-def leg_multi_tenant(S, hip, torch, total_cus, nhwc, n_p=8, rounds=30):
+def leg_multi_tenant(S, hip, torch, total_cus, nhwc, n_p=8, rounds=100):
     """Eight bf16 instances, each pinned to its own 32-CU partition (a static
     instance->partition assignment, i.e. pure spatial partitioning), stages of
     all instances issued round-robin from one host thread."""
