@@ -551,12 +551,14 @@ def leg_oversubscribed(S, torch, total_cus, nhwc, headline_ips, rounds=300):
     return res
 
 
-def leg_periodic(S, hip, torch, total_cus, nhwc, n_list=(64, 128, 192, 256, 320, 384, 448), levels=(1.0, 1.5, 2.0), n_ctx=2, lanes=2,
+def leg_periodic(S, hip, torch, total_cus, nhwc, n_list=(64, 128, 192, 256, 320, 384, 448), levels=(1.0, 1.5, 2.0), n_ctx=2, lanes=3,
                  fps=32.0, duration=0.5):
     """'Simulation Results' in kind: N identical periodic ResNet18 tasks (bf16, batch 1, six stages,
     deadline = period = 1/32 s, releases spread evenly over the period) under the SGPRS scheduler
-    (sgprs_sched_run_periodic) on a pool of two contexts with two lanes each, at over-subscription
-    levels 1.0 / 1.5 / 2.0 (CUs of all contexts / CUs of the GPU).  Stage WCETs are measured first,
+    (sgprs_sched_run_periodic) on a pool of two contexts with three lanes each (one for high-priority
+    stages, two for the others; four lanes per context, the paper's shape, would keep more than four
+    CU-masked streams busy at once, which collapses on this system), at over-subscription levels
+    1.0 / 1.5 / 2.0 (CUs of all contexts / CUs of the GPU).  Stage WCETs are measured first,
     on one lane with the rest of the GPU idle (the paper's offline phase).  Reported: total FPS and
     deadline miss rate against the number of tasks, and the pivot point (the largest N without a miss)."""
     from workloads import BN_EPS, make_input, make_resnet18_params

@@ -12,9 +12,13 @@
 // stages, the others for medium and low ones; a low-priority stage whose predecessor missed
 // its deadline is medium; inside a level the earliest deadline goes first.
 #include <algorithm>
+#include <atomic>
 #include <chrono>
 #include <cstdint>
+#include <memory>
 #include <new>
+#include <string>
+#include <thread>
 #include <unordered_map>
 #include <vector>
 
@@ -262,16 +266,64 @@ int sgprs_sched_run_periodic(sgprs_sched_t* s, sgprs_pool_t* pool, sgprs_task_t*
             return fail(SGPRS_ERR_INVALID_ARG, "task %d has %d stages, the scheduler knows %zu", i, sgprs_task_num_stages(tasks[i]),
                         s->tasks[i].wcet.size());
     }
-    struct Slot { bool busy = false; int task = 0, job = 0, stage = 0; hipEvent_t ev = nullptr; hipStream_t stream = nullptr; };
-    std::vector<Slot> slots((size_t)s->n_contexts * s->lanes);
-    auto cleanup = [&]() { for (Slot& sl : slots) if (sl.ev) (void)hipEventDestroy(sl.ev); };
-    for (size_t p = 0; p < slots.size(); ++p) {
+    // One slot per lane.  The scheduling thread owns `busy` and the ids; the launch itself (a handful
+    // of kernel launches and the event record, 20-30 us of host time) is done by the lane's own
+    // launcher thread, so that one slow enqueue does not hold up the decisions for the other lanes.
+    struct Slot {
+        bool busy = false;
+        int task = 0, job = 0, stage = 0;
+        hipEvent_t ev = nullptr;
+        hipStream_t stream = nullptr;
+        std::atomic<int> state{0};  // 0 idle, 1 launch requested, 2 launched (event recorded), 3 launch failed, 4 quit
+        sgprs_task_t* rq_task = nullptr;
+        const void* rq_in = nullptr;
+        void* rq_out = nullptr;
+        int rq_partition = 0, rc = 0;
+        std::string error;
+        std::thread thread;
+    };
+    const size_t n_slots = (size_t)s->n_contexts * s->lanes;
+    std::unique_ptr<Slot[]> slots(new (std::nothrow) Slot[n_slots]);
+    if (!slots) return fail(SGPRS_ERR_OOM, "slot allocation failed");
+    const bool threaded = n_slots <= 16;  // beyond that the scheduling thread launches by itself
+    int device = 0;
+    (void)hipGetDevice(&device);
+    auto launch = [&](Slot& sl) {
+        sl.rc = sgprs_stage_run(sl.rq_task, sl.stage, batch, sl.rq_in, sl.rq_out, pool, sl.rq_partition);
+        if (!sl.rc && hipEventRecord(sl.ev, sl.stream) != hipSuccess) sl.rc = fail(SGPRS_ERR_HIP, "hipEventRecord failed");
+        if (sl.rc) sl.error = sgprs_last_error();
+        sl.state.store(sl.rc ? 3 : 2, std::memory_order_release);
+    };
+    auto launcher = [&](Slot* sl) {
+        (void)hipSetDevice(device);
+        for (;;) {
+            const int st = sl->state.load(std::memory_order_acquire);
+            if (st == 4) return;
+            if (st == 1) launch(*sl);
+            else std::this_thread::yield();
+        }
+    };
+    auto cleanup = [&]() {
+        for (size_t p = 0; p < n_slots; ++p) {
+            Slot& sl = slots[p];
+            if (sl.thread.joinable()) {
+                while (sl.state.load(std::memory_order_acquire) == 1) std::this_thread::yield();  // a launch in progress finishes first
+                sl.state.store(4, std::memory_order_release);
+                sl.thread.join();
+            }
+            if (sl.busy && sl.state.load() != 3 && sl.ev) (void)hipEventSynchronize(sl.ev);  // nothing of ours stays queued unseen
+            if (sl.ev) (void)hipEventDestroy(sl.ev);
+        }
+    };
+    for (size_t p = 0; p < n_slots; ++p) {
         slots[p].stream = (hipStream_t)sgprs_pool_stream(pool, (int)p);
         if (hipEventCreateWithFlags(&slots[p].ev, hipEventDisableTiming) != hipSuccess) {
             cleanup();
             return fail(SGPRS_ERR_HIP, "hipEventCreateWithFlags failed");
         }
     }
+    if (threaded)
+        for (size_t p = 0; p < n_slots; ++p) slots[p].thread = std::thread(launcher, &slots[p]);
     std::vector<long long> released(n_tasks, 0);
     std::vector<char> active(n_tasks, 0);
     std::vector<double> job_release(n_tasks, 0.0);
@@ -284,12 +336,17 @@ int sgprs_sched_run_periodic(sgprs_sched_t* s, sgprs_pool_t* pool, sgprs_task_t*
     for (;;) {
         const double now = clock_s();
         // completions
-        for (Slot& sl : slots) {
+        for (size_t p = 0; p < n_slots; ++p) {
+            Slot& sl = slots[p];
             if (!sl.busy) continue;
+            const int st = sl.state.load(std::memory_order_acquire);
+            if (st == 1) continue;  // its launcher is still enqueueing
+            if (st == 3) { status = fail(sl.rc, "%s", sl.error.c_str()); break; }
             const hipError_t q = hipEventQuery(sl.ev);
             if (q == hipErrorNotReady) continue;
             if (q != hipSuccess) { status = fail(SGPRS_ERR_HIP, "hipEventQuery: %s", hipGetErrorString(q)); break; }
             sl.busy = false;
+            sl.state.store(0, std::memory_order_relaxed);
             if ((status = sgprs_sched_complete(s, sl.task, sl.job, sl.stage, now, nullptr))) break;
             if (sl.stage + 1 == (int)s->tasks[sl.task].wcet.size()) {
                 active[sl.task] = 0;
@@ -329,18 +386,19 @@ int sgprs_sched_run_periodic(sgprs_sched_t* s, sgprs_pool_t* pool, sgprs_task_t*
             const int last = (int)s->tasks[d.task].wcet.size() - 1;
             const void* in = d.stage == 0 ? inputs[d.task] : sgprs_task_stage_output(tasks[d.task], d.stage - 1);
             void* out = d.stage == last ? (void*)logits[d.task] : (void*)sgprs_task_stage_output(tasks[d.task], d.stage);
-            if ((status = sgprs_stage_run(tasks[d.task], d.stage, batch, in, out, pool, d.context * s->lanes + d.lane))) break;
-            if (hipEventRecord(sl.ev, sl.stream) != hipSuccess) { status = fail(SGPRS_ERR_HIP, "hipEventRecord failed"); break; }
             sl.busy = true; sl.task = d.task; sl.job = d.job; sl.stage = d.stage;
+            sl.rq_task = tasks[d.task]; sl.rq_in = in; sl.rq_out = out; sl.rq_partition = d.context * s->lanes + d.lane;
+            if (threaded) sl.state.store(1, std::memory_order_release);
+            else {
+                launch(sl);
+                if (sl.rc) { status = fail(sl.rc, "%s", sl.error.c_str()); break; }
+            }
         }
         if (got < 0) status = got;
         if (status) break;
         if (!more_releases && in_flight == 0) break;
         if (now > duration_s + 30.0) { status = fail(SGPRS_ERR_HIP, "jobs still in flight 30 s after the last release"); break; }
     }
-    // whatever happened, nothing of ours stays queued behind the caller's back
-    for (Slot& sl : slots)
-        if (sl.busy) (void)hipEventSynchronize(sl.ev);
     cleanup();
     if (status) return status;
     report->elapsed_s = std::max(last_done, duration_s);
