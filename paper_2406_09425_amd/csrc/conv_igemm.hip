@@ -10,8 +10,8 @@
 // tile row is one contiguous run of channels of one input pixel.
 //
 // Per workgroup (256 threads = 4 wavefronts of 64): a BM x BN output tile,
-// A and B k-tiles staged in LDS (double buffered, register prefetch of the
-// next k-tile while the current one feeds the MFMAs), XOR-swizzled 16-byte
+// A and B k-tiles staged in LDS (two stages, filled by buffer loads that write
+// LDS directly while the other stage feeds the MFMAs), XOR-swizzled 16-byte
 // chunks so that fragment reads are bank-conflict free.  The epilogue applies
 // the folded BN scale/shift, the residual and ReLU in fp32 and stores in the
 // activation dtype.  With split-K each z-slice of the grid writes fp32 partial
@@ -74,9 +74,10 @@ __device__ __forceinline__ int fast_div(int m, unsigned mul, int sh)
 
 __device__ __forceinline__ int swz(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
 
-// Pipeline depth (LDS stages).  Measured on the batch-64 layers, deeper
-// pipelines lose more from the lower occupancy (workgroups per CU) than they
-// gain: the loop is bound by L2 -> LDS bandwidth, not by latency.
+// Pipeline depth (LDS stages).  Three and four stages measured the same as two,
+// at batch 64 (where they also cost workgroups per CU) and at batch 1: the loop
+// is bound by its instruction stream and by per-tile fixed costs, not by load
+// latency or L2 -> LDS bandwidth.
 template <int BM, int BN> struct IgemmStages { static constexpr int value = 2; };
 
 // One BM x BN output tile: tile column bx, channel block by, split-K slice bz.
