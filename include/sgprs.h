@@ -355,8 +355,11 @@ int sgprs_sched_get_stats(const sgprs_sched_t *sched, sgprs_sched_stats_t *out);
  * context the same CU mask; contexts may overlap: an over-subscribed pool).
  * Job k of task i is released at offsets[i] + k * period_i (offsets HOST
  * double[n_tasks] or NULL = 0) while that is < duration_s seconds on the host's
- * steady clock; the calling thread releases, dispatches (sgprs_stage_run) and
- * polls one event per lane for completions until every job has finished.  A
+ * steady clock; the calling thread releases jobs, takes the scheduler's
+ * decisions and polls one event per lane for completions until every job has
+ * finished; the launches themselves (sgprs_stage_run and the event record) are
+ * made by one helper thread per lane (up to 16 lanes; beyond that by the calling
+ * thread), which the call creates and joins.  A
  * job released while the task's previous job is still in flight is dropped
  * (a task holds one job's activations) and counts as a miss.
  * report: elapsed_s = max(duration_s, time of the last completion), fps =
