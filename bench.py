@@ -551,16 +551,17 @@ def leg_oversubscribed(S, torch, total_cus, nhwc, headline_ips, rounds=300):
     return res
 
 
-def leg_periodic(S, hip, torch, total_cus, nhwc, n_list=(64, 128, 192, 256, 320, 384, 448), levels=(1.0, 1.5, 2.0), n_ctx=2, lanes=3,
-                 fps=32.0, duration=0.5):
+def leg_periodic(S, hip, torch, total_cus, nhwc, n_list=(128, 256, 320, 384, 448, 512, 576), levels=(1.0, 1.5, 2.0),
+                 shapes=((2, 3), (4, 1)), fps=32.0, duration=0.5):
     """'Simulation Results' in kind: N identical periodic ResNet18 tasks (bf16, batch 1, six stages,
     deadline = period = 1/32 s, releases spread evenly over the period) under the SGPRS scheduler
-    (sgprs_sched_run_periodic) on a pool of two contexts with three lanes each (one for high-priority
-    stages, two for the others; four lanes per context, the paper's shape, would keep more than four
-    CU-masked streams busy at once, which collapses on this system), at over-subscription levels
-    1.0 / 1.5 / 2.0 (CUs of all contexts / CUs of the GPU).  Stage WCETs are measured first,
-    on one lane with the rest of the GPU idle (the paper's offline phase).  Reported: total FPS and
-    deadline miss rate against the number of tasks, and the pivot point (the largest N without a miss)."""
+    (sgprs_sched_run_periodic), at over-subscription levels 1.0 / 1.5 / 2.0 (CUs of all contexts /
+    CUs of the GPU), on two pool shapes: two contexts with three lanes each (one for high-priority
+    stages, two for the others: the nearest to the paper's two-high-two-low that does not keep more
+    than four CU-masked streams busy at once, which collapses on this system), and four contexts
+    with one lane each.  Stage WCETs are measured first, on one lane with the rest of the GPU idle
+    (the paper's offline phase).  Reported: total FPS and deadline miss rate against the number of
+    tasks, and the pivot point (the largest N without a miss)."""
     from workloads import BN_EPS, make_input, make_resnet18_params
     period = 1.0 / fps
     n_max = max(n_list)
@@ -568,50 +569,54 @@ def leg_periodic(S, hip, torch, total_cus, nhwc, n_list=(64, 128, 192, 256, 320,
     tasks = [S.Task(params, S.SGPRS_BF16, 1, BN_EPS) for _ in range(n_max)]
     x = nhwc(make_input(3, 0, (1, 3, 224, 224), bf16=True), torch.bfloat16)
     lgs = [torch.empty((1, 1000), dtype=torch.float32, device="cuda") for _ in range(n_max)]
-    res = {}
-    for level in levels:
-        cus = min(total_cus, int(round(total_cus / n_ctx * level)) // 8 * 8)
-        base = S.Pool(n_ctx, cus, flags=S.SGPRS_POOL_OVERSUBSCRIBE if n_ctx * cus > total_cus else 0)
-        masks = np.stack([base.mask(c) for c in range(n_ctx) for _ in range(lanes)])
-        base.destroy()
-        pool = S.Pool(n_ctx * lanes, 0, masks=masks)
-        # offline phase: per-stage WCET on one lane, alone
-        stream = pool.stream(0)
-        ev = [hip.event() for _ in range(7)]
-        per = [[] for _ in range(6)]
-        for it in range(40):
-            for j in range(6):
-                hip.record(ev[j], stream)
-                src = x.data_ptr() if j == 0 else tasks[0].stage_output(j - 1)
-                dst = lgs[0].data_ptr() if j == 5 else tasks[0].stage_output(j)
-                tasks[0].stage_run(j, 1, src, dst, pool, 0)
-            hip.record(ev[6], stream)
-            pool.sync()
-            if it >= 10:
+    out = []
+    for (n_ctx, lanes) in shapes:
+        res = {}
+        for level in levels:
+            cus = min(total_cus, int(round(total_cus / n_ctx * level)) // 8 * 8)
+            base = S.Pool(n_ctx, cus, flags=S.SGPRS_POOL_OVERSUBSCRIBE if n_ctx * cus > total_cus else 0)
+            masks = np.stack([base.mask(c) for c in range(n_ctx) for _ in range(lanes)])
+            base.destroy()
+            pool = S.Pool(n_ctx * lanes, 0, masks=masks)
+            # offline phase: per-stage WCET on one lane, alone
+            stream = pool.stream(0)
+            ev = [hip.event() for _ in range(7)]
+            per = [[] for _ in range(6)]
+            for it in range(40):
                 for j in range(6):
-                    per[j].append(hip.elapsed_ms(ev[j], ev[j + 1]) * 1e-3)
-        wcet = [max(p) for p in per]
-        rows, pivot = [], 0
-        for n in n_list:
-            sch = S.Sched(n_ctx, lanes)
-            for _ in range(n):
-                sch.add_task(wcet, period, period)
-            rep = sch.run_periodic(pool, tasks[:n], [x.data_ptr()] * n, [l.data_ptr() for l in lgs[:n]], 1, duration,
-                                   offsets=[i * period / n for i in range(n)])
-            pool.sync()
-            sch.destroy()
-            rows.append(dict(n_tasks=n, total_fps=round(rep["fps"], 1), dmr=round(rep["dmr"], 4), dropped=rep["dropped"],
-                             jobs_missed=rep["jobs_missed"], releases=rep["releases"],
-                             mean_response_ms=round(rep["mean_response_s"] * 1e3, 3),
-                             max_response_ms=round(rep["max_response_s"] * 1e3, 3)))
-            if all(r["dmr"] == 0.0 for r in rows):
-                pivot = n
-            log("periodic", f"os={level}", json.dumps(rows[-1]))
-        res[f"SGPRS_{level}"] = dict(cus_per_context=cus, stage_wcet_us=[round(w * 1e6, 1) for w in wcet], pivot_tasks=pivot, points=rows)
-        pool.destroy()
+                    hip.record(ev[j], stream)
+                    src = x.data_ptr() if j == 0 else tasks[0].stage_output(j - 1)
+                    dst = lgs[0].data_ptr() if j == 5 else tasks[0].stage_output(j)
+                    tasks[0].stage_run(j, 1, src, dst, pool, 0)
+                hip.record(ev[6], stream)
+                pool.sync()
+                if it >= 10:
+                    for j in range(6):
+                        per[j].append(hip.elapsed_ms(ev[j], ev[j + 1]) * 1e-3)
+            wcet = [max(p) for p in per]
+            rows, pivot = [], 0
+            for n in n_list:
+                sch = S.Sched(n_ctx, lanes)
+                for _ in range(n):
+                    sch.add_task(wcet, period, period)
+                rep = sch.run_periodic(pool, tasks[:n], [x.data_ptr()] * n, [l.data_ptr() for l in lgs[:n]], 1, duration,
+                                       offsets=[i * period / n for i in range(n)])
+                pool.sync()
+                sch.destroy()
+                rows.append(dict(n_tasks=n, total_fps=round(rep["fps"], 1), dmr=round(rep["dmr"], 4), dropped=rep["dropped"],
+                                 jobs_missed=rep["jobs_missed"], releases=rep["releases"],
+                                 mean_response_ms=round(rep["mean_response_s"] * 1e3, 3),
+                                 max_response_ms=round(rep["max_response_s"] * 1e3, 3)))
+                if all(r["dmr"] == 0.0 for r in rows):
+                    pivot = n
+                log("periodic", f"{n_ctx}x{lanes} os={level}", json.dumps(rows[-1]))
+            res[f"SGPRS_{level}"] = dict(cus_per_context=cus, stage_wcet_us=[round(w * 1e6, 1) for w in wcet], pivot_tasks=pivot,
+                                         points=rows)
+            pool.destroy()
+        out.append(dict(contexts=n_ctx, lanes_per_context=lanes, results=res))
     for t in tasks:
         t.destroy()
-    return dict(contexts=n_ctx, lanes_per_context=lanes, task_fps=fps, duration_s=duration, results=res)
+    return dict(task_fps=fps, duration_s=duration, pools=out)
 
 
 def leg_pool_scaling(S, torch, total_cus, nhwc, instances=8, rounds=150):
