@@ -779,20 +779,19 @@ static bool patch_geometry(const sgprs_conv_desc_t& d, int v, int splits, PatchA
 {
     struct Key { sgprs_conv_desc_t d; int v, splits; };
     struct Val { bool ok; PatchArgs a; };
-    static thread_local PlanMemo<Key, Val, 512> memo;
+    static thread_local PlanMemo<Key, Val, 512> local;
+    static SharedPlanMemo<Key, Val, 512> memo;
     Key k;
     memset(&k, 0, sizeof(k));
     k.d = d; k.v = v; k.splits = splits;
-    const Val* hit = memo.find(k);
-    if (!hit) {
+    const Val hit = memo.get(local, k, [&]() {
         Val nv;
         memset(&nv, 0, sizeof(nv));
         nv.ok = patch_geometry_uncached(d, v, splits, &nv.a);
-        memo.put(k, nv);
-        hit = memo.find(k);
-    }
-    if (hit->ok) *a = hit->a;
-    return hit->ok;
+        return nv;
+    });
+    if (hit.ok) *a = hit.a;
+    return hit.ok;
 }
 static bool patch_geometry_uncached(const sgprs_conv_desc_t& d, int v, int splits, PatchArgs* a)
 {
@@ -992,20 +991,19 @@ static bool s2patch_geometry(const sgprs_conv_desc_t& d, int v, S2Args* a)
 {
     struct Key { sgprs_conv_desc_t d; int v; };
     struct Val { bool ok; S2Args a; };
-    static thread_local PlanMemo<Key, Val, 64> memo;
+    static thread_local PlanMemo<Key, Val, 64> local;
+    static SharedPlanMemo<Key, Val, 64> memo;
     Key k;
     memset(&k, 0, sizeof(k));
     k.d = d; k.v = v;
-    const Val* hit = memo.find(k);
-    if (!hit) {
+    const Val hit = memo.get(local, k, [&]() {
         Val nv;
         memset(&nv, 0, sizeof(nv));
         nv.ok = s2patch_geometry_uncached(d, v, &nv.a);
-        memo.put(k, nv);
-        hit = memo.find(k);
-    }
-    if (hit->ok) *a = hit->a;
-    return hit->ok;
+        return nv;
+    });
+    if (hit.ok) *a = hit.a;
+    return hit.ok;
 }
 static bool s2patch_geometry_uncached(const sgprs_conv_desc_t& d, int v, S2Args* a)
 {

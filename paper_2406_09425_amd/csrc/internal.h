@@ -11,6 +11,7 @@
 #include <string>
 #include <cstring>
 #include <utility>
+#include <mutex>
 #include <vector>
 
 #include "sgprs.h"
@@ -87,9 +88,9 @@ inline bool is_igemm(const sgprs_conv_desc_t& d)
 int check_conv_desc(const sgprs_conv_desc_t* d);
 inline int out_dim(int in, int k, int stride, int pad) { return (in + 2 * pad - k) / stride + 1; }
 
-// Small per-thread memo for launch planning: the same few shapes are planned again on every
-// launch, and the geometry searches behind a plan walk all row tiles.  Keys are plain structs
-// compared bytewise (fill them with memset first); the oldest entries are dropped.
+// Small memo for launch planning: the same few shapes are planned again on every launch, and the
+// geometry searches behind a plan walk all row tiles.  Keys are plain structs compared bytewise
+// (fill them with memset first); the oldest entries are dropped.
 template <class K, class V, int CAP = 128> struct PlanMemo {
     std::vector<std::pair<K, V>> items;
     const V* find(const K& k)
@@ -108,6 +109,28 @@ template <class K, class V, int CAP = 128> struct PlanMemo {
     {
         if ((int)items.size() >= CAP) items.erase(items.begin(), items.begin() + CAP / 2);
         items.emplace_back(k, v);
+    }
+};
+// Two levels: a memo per thread, read without a lock, in front of one per process behind a mutex,
+// so that a thread that has never planned (a launcher thread just created) copies what another
+// thread worked out instead of searching again.
+template <class K, class V, int CAP = 128> struct SharedPlanMemo {
+    std::mutex mu;
+    PlanMemo<K, V, CAP> shared;
+    template <class F> V get(PlanMemo<K, V, CAP>& local, const K& k, F compute)
+    {
+        if (const V* hit = local.find(k)) return *hit;
+        V v;
+        {
+            std::lock_guard<std::mutex> guard(mu);
+            if (const V* hit = shared.find(k)) v = *hit;
+            else {
+                v = compute();
+                shared.put(k, v);
+            }
+        }
+        local.put(k, v);
+        return v;
     }
 };
 extern int g_plan_generation;  // bumped whenever a tuning override changes what the planners return

@@ -63,14 +63,12 @@ static ConvPlan plan_conv_uncached(const sgprs_conv_desc_t& d, int cus, bool has
 ConvPlan plan_conv(const sgprs_conv_desc_t& d, int cus, bool has_residual)
 {
     struct Key { sgprs_conv_desc_t d; int cus, res, gen; };
-    static thread_local PlanMemo<Key, ConvPlan> memo;
+    static thread_local PlanMemo<Key, ConvPlan> local;
+    static SharedPlanMemo<Key, ConvPlan> memo;
     Key k;
     memset(&k, 0, sizeof(k));
     k.d = d; k.cus = cus; k.res = has_residual; k.gen = g_plan_generation;
-    if (const ConvPlan* hit = memo.find(k)) return *hit;
-    const ConvPlan p = plan_conv_uncached(d, cus, has_residual);
-    memo.put(k, p);
-    return p;
+    return memo.get(local, k, [&]() { return plan_conv_uncached(d, cus, has_residual); });
 }
 
 static ConvPlan plan_conv_uncached(const sgprs_conv_desc_t& d, int cus, bool has_residual)
