@@ -7,6 +7,11 @@
       dispatch), scaled by what the same counters read for the 256 MiB + 256 MiB
       calibration copy (bn_relu_kernel) in the same runs
 
+  python -m paper_2406_09425_amd.profile_summary sq <dir> [<dir> ...] -- <command...>
+      SQ counters per dispatch of every sgprs kernel (one rocprofv3 --pmc run per
+      directory, at most 8 SQ counters each), as fractions of the SIMD cycles of the
+      dispatch where that makes sense
+
 The command line that produced the data is echoed into the summary.
 """
 from __future__ import annotations
@@ -67,10 +72,53 @@ def pmc(fetch_dir: str, write_dir: str, cmd: str) -> str:
     return "\n".join(out) + "\n"
 
 
+def sq(dirs, cmd: str) -> str:
+    """Shares of a dispatch's SIMD cycles.  SQ_BUSY_CYCLES counts per shader engine (32 on this
+    part, 4 per die), the *_CYCLES / ACTIVE_INST / WAIT counters count in units of 4 cycles per
+    SIMD, SQ_VALU_MFMA_BUSY_CYCLES in cycles per SIMD."""
+    vals = collections.defaultdict(dict)
+    disp = collections.Counter()
+    for d in dirs:
+        names = set()
+        for f in _find(d, "*counter_collection.csv"):
+            for r in csv.DictReader(open(f)):
+                if "sgprs::" not in r["Kernel_Name"]:
+                    continue
+                k = r["Kernel_Name"]
+                vals[k][r["Counter_Name"]] = vals[k].get(r["Counter_Name"], 0.0) + float(r["Counter_Value"])
+                names.add(r["Counter_Name"])
+                disp[(k, r["Counter_Name"])] += 1
+    out = [f"command: {cmd}", "one run per group of at most 8 SQ counters; values are per dispatch", "",
+           f"{'kernel':<62}{'cycles':>8}{'waves':>7}{'MFMA busy':>10}{'VALU':>7}{'scalar':>7}{'LDS':>6}{'VMEM':>6}"
+           f"{'any inst':>9}{'waiting':>8}{'VALU/wave':>10}{'SALU/wave':>10}{'LDS/wave':>9}{'bank confl.':>12}"]
+    for k, v in sorted(vals.items(), key=lambda kv: -kv[1].get("SQ_BUSY_CYCLES", 0) / max(1, disp[(kv[0], "SQ_BUSY_CYCLES")])):
+        g = lambda n: v.get(n, 0.0) / max(1, disp[(k, n)])
+        cycles = g("SQ_BUSY_CYCLES") / 32.0
+        simd = cycles * 1024.0
+        if simd <= 0:
+            continue
+        waves = max(1.0, g("SQ_WAVES"))
+        pct = lambda x: f"{100.0 * x / simd:.1f}%"
+        lds_active = g("SQ_ACTIVE_INST_LDS") * 4
+        out.append(f"{k.replace('void sgprs::', '')[:60]:<62}{cycles:>8.0f}{waves:>7.0f}{pct(g('SQ_VALU_MFMA_BUSY_CYCLES')):>10}"
+                   f"{pct(g('SQ_ACTIVE_INST_VALU') * 4):>7}{pct(g('SQ_ACTIVE_INST_SCA') * 4):>7}{pct(lds_active):>6}"
+                   f"{pct(g('SQ_ACTIVE_INST_VMEM') * 4):>6}{pct(g('SQ_ACTIVE_INST_ANY') * 4):>9}{pct(g('SQ_WAIT_INST_ANY') * 4):>8}"
+                   f"{g('SQ_INSTS_VALU') / waves:>10.0f}{g('SQ_INSTS_SALU') / waves:>10.0f}{g('SQ_INSTS_LDS') / waves:>9.0f}"
+                   f"{(100.0 * g('SQ_LDS_BANK_CONFLICT') / max(1.0, g('SQ_LDS_IDX_ACTIVE'))):>11.1f}%")
+    out += ["", "MFMA busy: SQ_VALU_MFMA_BUSY_CYCLES / (SQ_BUSY_CYCLES / 32 * 1024 SIMDs).  VALU, scalar, LDS, VMEM, any inst:",
+            "SQ_ACTIVE_INST_* * 4 over the same SIMD cycles (issue activity; VALU includes the MFMA issue slots).  waiting:",
+            "SQ_WAIT_INST_ANY * 4 over the same (wave-cycles spent waiting, summed over the resident waves, so it can exceed",
+            "100 %).  bank confl.: SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE."]
+    return "\n".join(out) + "\n"
+
+
 if __name__ == "__main__":
     if len(sys.argv) >= 4 and sys.argv[1] == "stats":
         sys.stdout.write(stats(sys.argv[2], " ".join(sys.argv[3:])))
     elif len(sys.argv) >= 5 and sys.argv[1] == "pmc":
         sys.stdout.write(pmc(sys.argv[2], sys.argv[3], " ".join(sys.argv[4:])))
+    elif len(sys.argv) >= 5 and sys.argv[1] == "sq" and "--" in sys.argv:
+        i = sys.argv.index("--")
+        sys.stdout.write(sq(sys.argv[2:i], " ".join(sys.argv[i + 1:])))
     else:
         sys.exit(__doc__)
