@@ -121,7 +121,10 @@ __global__ __launch_bounds__(256) void maxpool3x3s2_kernel(const void* __restric
             const int iw = 2 * q - 1 + s;
             cok[s] = (unsigned)iw < (unsigned)W;
             const int iwc = min(max(iw, 0), W - 1);
-            v[r][s].load(x, ((size_t)(n * H + ihc) * W + iwc) * cv + c);
+            // the three middle rows belong to this thread's two outputs alone: streamed past the caches;
+            // the outer two are shared with the neighbouring output rows (other workgroups) and stay cached
+            if (r >= 1 && r <= 3) v[r][s].load_nt(x, ((size_t)(n * H + ihc) * W + iwc) * cv + c);
+            else v[r][s].load(x, ((size_t)(n * H + ihc) * W + iwc) * cv + c);
         }
     }
     Vec<DT> m0, m1;
