@@ -75,6 +75,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle CPU baseline")
     ap.add_argument("--cpu-sample", type=int, default=24, help="images of the batch the oracle is timed on")
     ap.add_argument("--periodic-only", action="store_true", help="only the periodic-task scheduler experiment")
+    ap.add_argument("--batch-sweep-only", action="store_true", help="only the bf16 throughput at batches 1..32")
     ap.add_argument("--probes-only", action="store_true", help="only the sustained MFMA and load-path probes")
     ap.add_argument("--membound-only", action="store_true",
                     help="run only the memory-bound operator leg (for profiling it); prints its own JSON line")
@@ -114,6 +115,11 @@ def main():
     if args.probes_only:
         print(json.dumps(dict(sustained_mfma=leg_mfma_probe(S, hip, torch, pool, stream, total_cus),
                               sustained_load_to_lds=leg_load_probe(S, hip, torch, pool, stream, total_cus))), flush=True)
+        pool.destroy()
+        return
+
+    if args.batch_sweep_only:
+        print(json.dumps(dict(batch_sweep_bf16=leg_batch_sweep(S, hip, torch, pool, stream, nhwc))), flush=True)
         pool.destroy()
         return
 
@@ -262,6 +268,7 @@ def main():
         out["roofline"]["sustained_load_to_lds"] = leg_load_probe(S, hip, torch, pool, stream, total_cus)
         out["periodic_tasks"] = leg_periodic(S, hip, torch, total_cus, nhwc)
         out["batch1_fp32"] = leg_batch1(S, hip, pool, stream, nhwc, torch, total_cus)
+        out["batch_sweep_bf16"] = leg_batch_sweep(S, hip, torch, pool, stream, nhwc)
         out["cu_sweep"] = leg_sweep(S, hip, torch, total_cus, nhwc, with_cpu=not args.no_cpu)
         out["multi_tenant"] = leg_multi_tenant(S, hip, torch, total_cus, nhwc)
         out["pool_scaling"] = leg_pool_scaling(S, torch, total_cus, nhwc)
@@ -309,6 +316,32 @@ def leg_batch1(S, hip, pool, stream, nhwc, torch, total_cus, runs=100):
                          net_ms_median=round(statistics.median(whole), 4), net_ms_max=round(max(whole), 4),
                          back_to_back_ms=round(thr_ms, 4), images_per_s=round(1e3 / thr_ms, 1))
         log("batch1", name, json.dumps(res[name]))
+        task.destroy()
+    return res
+
+
+def leg_batch_sweep(S, hip, torch, pool, stream, nhwc, batches=(1, 2, 4, 8, 16, 32), runs=200):
+    """bf16 whole-network throughput at batch sizes below the headline's, on the whole chip, through
+    sgprs_task_run (graph replay), back to back on one stream."""
+    from workloads import BN_EPS, make_input, make_resnet18_params
+    params = make_resnet18_params(4, 0, bf16=True)
+    res = {}
+    for n in batches:
+        task = S.Task(params, S.SGPRS_BF16, n, BN_EPS)
+        xd = nhwc(make_input(4, 0, (n, 3, 224, 224), bf16=True), torch.bfloat16)
+        lg = torch.empty((n, 1000), dtype=torch.float32, device="cuda")
+        for _ in range(20):
+            task.run(n, xd.data_ptr(), lg.data_ptr(), pool, 0)
+        e0, e1 = hip.event(), hip.event()
+        hip.record(e0, stream)
+        for _ in range(runs):
+            task.run(n, xd.data_ptr(), lg.data_ptr(), pool, 0)
+        hip.record(e1, stream)
+        pool.sync()
+        ms = hip.elapsed_ms(e0, e1) / runs
+        res[str(n)] = dict(ms_per_step=round(ms, 4), images_per_s=round(n * 1e3 / ms, 1),
+                           tflops=round(3.628e9 * n / (ms * 1e-3) / 1e12, 1))
+        log("batch_sweep", n, json.dumps(res[str(n)]))
         task.destroy()
     return res
 

@@ -252,6 +252,37 @@ def test_config4_batch64_bf16_sampled_against_oracle(full_pool):
     task.destroy()
 
 
+# ------------------------------------------------------------- other batch sizes
+@pytest.mark.parametrize("dtype,n,cus", [
+    (S.SGPRS_BF16, 8, 0), (S.SGPRS_BF16, 16, 0), (S.SGPRS_BF16, 5, 32), (S.SGPRS_F32, 8, 0), (S.SGPRS_F32, 3, 64),
+], ids=["bf16-n8-256cu", "bf16-n16-256cu", "bf16-n5-32cu", "f32-n8-256cu", "f32-n3-64cu"])
+def test_whole_network_at_other_batch_sizes(full_pool, dtype, n, cus):
+    """Batches between the one-image tasks and the batch-64 run take other planner choices (tile
+    shapes, split-K, fused or unfused head): every logit of every image against the oracle, on the
+    whole chip (cus = 0) or on a partition of `cus` CUs; an odd batch leaves ragged row tiles."""
+    bf16 = dtype == S.SGPRS_BF16
+    seed = 2    # with these weights the oracle's best class leads the second by 6 % of max|logit| on every image
+    params = make_resnet18_params(5, seed, bf16=bf16)
+    x = make_input(5, seed, (n, 3, 224, 224), bf16=bf16)
+    pool = full_pool if cus == 0 else S.Pool(2, cus)
+    part = 0 if cus == 0 else 1
+    task = S.Task(params, dtype, n, BN_EPS)
+    xd = dev_nhwc(x, dtype)
+    lg = torch.full((n, 1000), float("nan"), dtype=torch.float32, device="cuda")
+    for _ in range(3):      # eager, capture, replay
+        task.run(n, xd.data_ptr(), lg.data_ptr(), pool, part)
+    pool.sync()
+    got = lg.cpu().numpy().astype(np.float64)
+    ref = oracle.resnet18(params, BN_EPS, x)
+    top2 = np.sort(ref, axis=1)[:, -2:]
+    assert np.min((top2[:, 1] - top2[:, 0]) / np.max(np.abs(ref), axis=1)) > 2 * TOL[dtype]   # the top class is decided
+    e = assert_close(got, ref, dtype, f"batch {n} logits")
+    check_argmax(got, ref, e, f"batch {n}")
+    task.destroy()
+    if cus:
+        pool.destroy()
+
+
 def test_task_run_graph_replay_matches_eager(full_pool, cfg1):
     """sgprs_task_run captures a task into a HIP graph on the second call with the same arguments
     and replays it afterwards.  Replays are interleaved with eager work on the same stream, with
