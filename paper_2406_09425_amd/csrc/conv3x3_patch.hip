@@ -843,8 +843,8 @@ void patch_force(int variant, int splits) { g_force_variant = variant; g_force_s
 // Picks the tile variant: the candidate with the smallest estimated time
 // rounds(items / CUs) * (chunks * cost-per-chunk + cost-per-item); the costs (in
 // microseconds, whole-GPU measurements at batch 64) only rank candidates.
-// When a shape offers too few work items to fill the partition this kernel
-// declines and the implicit-GEMM path (with its split-K) takes over.
+// When a shape offers too few work items to fill the partition and is deep in K
+// this kernel declines and the implicit-GEMM path (with its split-K) takes over.
 bool plan_patch(const sgprs_conv_desc_t& d, int cus, int* variant, int* splits)
 {
     if (!patch_eligible(d)) return false;
@@ -866,7 +866,11 @@ bool plan_patch(const sgprs_conv_desc_t& d, int cus, int* variant, int* splits)
         for (int sp = 1; sp <= 2; ++sp) {
             if (!patch_geometry(d, c.v, sp, &a)) continue;
             const long long items = (long long)a.n_mtiles * a.n_ntiles * sp;
-            if (items * 3 < cus) continue;
+            // far fewer items than CUs: the partition's time is one workgroup's serial K loop. A shallow
+            // one (up to four chunks, Cin <= 128) is over before a split implicit GEMM plus its reduction
+            // pass would be (batch 1 on 256 CUs: 6.0 against 6.9-9.8 us at 56x56x64, 7.8 against 10.2 us
+            // at 28x28x128); a deep one is left to the implicit GEMM's wider split-K
+            if (items * 3 < cus && (sp > 1 || a.chunks_per_split > 4)) continue;
             const long long rounds = (items + cus - 1) / cus;
             double cost = rounds * (a.chunks_per_split * c.step + c.item);
             if (sp > 1) cost += 9.0 + (double)d.n * d.h * d.w * d.cout * 4.0 * (sp + 1) / (3.0e6 * cus / 256.0);
