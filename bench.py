@@ -73,7 +73,7 @@ def main():
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--no-extras", action="store_true", help="skip batch-1, CU sweep and multi-tenant legs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle CPU baseline")
-    ap.add_argument("--cpu-sample", type=int, default=24, help="images of the batch the oracle is timed on")
+    ap.add_argument("--cpu-sample", type=int, default=64, help="images of the batch the oracle is timed on")
     ap.add_argument("--periodic-only", action="store_true", help="only the periodic-task scheduler experiment")
     ap.add_argument("--batch-sweep-only", action="store_true", help="only the bf16 throughput at batches 1..32")
     ap.add_argument("--probes-only", action="store_true", help="only the sustained MFMA and load-path probes")
@@ -243,7 +243,8 @@ def main():
         got = logits[:ns].cpu().numpy().astype(np.float64)
         err = float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
         cpu = dict(value=round(ns / dt, 3), unit="images/s", cores=oracle.max_threads(), kind="oracle",
-                   sample=f"first {ns} images of the batch-{n} workload, fp64 direct loops, {dt:.1f} s",
+                   sample=(f"all {ns} images" if ns == n else f"first {ns} images") +
+                          f" of the batch-{n} workload, fp64 direct loops, {dt:.1f} s",
                    gpu_vs_oracle_max_rel_err=err,
                    argmax_equal=bool(np.array_equal(np.argmax(got, 1), np.argmax(ref, 1))))
         log("cpu_baseline:", json.dumps(cpu))
