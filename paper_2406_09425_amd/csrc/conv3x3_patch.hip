@@ -395,6 +395,7 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
 
         {   // epilogue through the patch area of buffer 1 (the next item's first step sits in buffer 0)
             float* scr = (float*)(smem + P_PITCH) + wave * SCR_ROWS * SROW;
+            const unsigned relu_floor = a.relu ? kReluFloor : kNoReluFloor;
             if constexpr (!SPLIT && !EARLY_RES) {  // registers are scarce here: the operands are fetched now, the other wavefronts of the CU cover the wait
                 sc0 = *(const f32x4_t*)(a.scale + nbase); sc1 = *(const f32x4_t*)(a.scale + nbase + 4);
                 sh0 = *(const f32x4_t*)(a.shift + nbase); sh1 = *(const f32x4_t*)(a.shift + nbase + 4);
@@ -438,12 +439,9 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
                         u32x4_t ov;
 #pragma unroll
                         for (int u = 0; u < 4; ++u) {
-                            float lo = v[2 * u] + __uint_as_float(rv[u] << 16);
-                            float hi = v[2 * u + 1] + __uint_as_float(rv[u] & 0xffff0000u);
-                            if (a.relu) { lo = fmaxf(lo, 0.f); hi = fmaxf(hi, 0.f); }
-                            const __bf16 l16 = (__bf16)lo, h16 = (__bf16)hi;
-                            ov[u] = (unsigned)__builtin_bit_cast(unsigned short, l16) |
-                                    ((unsigned)__builtin_bit_cast(unsigned short, h16) << 16);
+                            const float lo = v[2 * u] + __uint_as_float(rv[u] << 16);
+                            const float hi = v[2 * u + 1] + __uint_as_float(rv[u] & 0xffff0000u);
+                            ov[u] = pack_bf16x2_relu(lo, hi, relu_floor);
                         }
                         __builtin_amdgcn_raw_buffer_store_b128(ov, y_rs, out_off(px), 0, 0);  // rows past the item: dropped
                     }
@@ -718,11 +716,7 @@ __global__ __launch_bounds__(NW * 64, 1) void conv3x3s2_patch_kernel(const S2Arg
                                 u32x4_t ov;
 #pragma unroll
                                 for (int u = 0; u < 4; ++u) {
-                                    float lo = v[2 * u], hi = v[2 * u + 1];
-                                    if (relu) { lo = fmaxf(lo, 0.f); hi = fmaxf(hi, 0.f); }
-                                    const __bf16 l16 = (__bf16)lo, h16 = (__bf16)hi;
-                                    ov[u] = (unsigned)__builtin_bit_cast(unsigned short, l16) |
-                                            ((unsigned)__builtin_bit_cast(unsigned short, h16) << 16);
+                                    ov[u] = pack_bf16x2_relu(v[2 * u], v[2 * u + 1], relu ? kReluFloor : kNoReluFloor);
                                 }
                                 *(u32x4_t*)(y + (m * a.Cout + nbase) * 2) = ov;
                             }

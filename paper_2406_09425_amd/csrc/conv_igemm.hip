@@ -280,6 +280,7 @@ __device__ __forceinline__ void igemm_tile(const IgemmArgs& a, int bx, int by, i
     constexpr int RV = DT == SGPRS_F32 ? 2 : 1;
     u32x4_t rres[TM][NPASS][RV];
     const bool has_res = !SPLIT && a.res != nullptr;
+    const unsigned relu_floor = a.relu ? kReluFloor : kNoReluFloor;
     if (has_res) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -331,10 +332,9 @@ __device__ __forceinline__ void igemm_tile(const IgemmArgs& a, int bx, int by, i
                     u32x4_t ov;
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
-                        float lo = v[2 * u] + __uint_as_float(rv[u] << 16);
-                        float hi = v[2 * u + 1] + __uint_as_float(rv[u] & 0xffff0000u);
-                        if (a.relu) { lo = fmaxf(lo, 0.f); hi = fmaxf(hi, 0.f); }
-                        ov[u] = (unsigned)f32_to_bf16(lo) | ((unsigned)f32_to_bf16(hi) << 16);
+                        const float lo = v[2 * u] + __uint_as_float(rv[u] << 16);
+                        const float hi = v[2 * u + 1] + __uint_as_float(rv[u] & 0xffff0000u);
+                        ov[u] = pack_bf16x2_relu(lo, hi, relu_floor);
                     }
                     *(u32x4_t*)(a.y + o * 2) = ov;
                 }

@@ -54,6 +54,22 @@ int resolve(sgprs_pool_t* pool, int partition, hipStream_t* stream, int* cus);
 inline size_t dtype_size(int dtype) { return dtype == SGPRS_BF16 ? 2 : 4; }
 inline bool dtype_ok(int dtype) { return dtype == SGPRS_F32 || dtype == SGPRS_BF16; }
 
+// Device side: two fp32 values to one dword of bf16 (round to nearest even, a single packed
+// conversion), then the optional ReLU on the packed pair as a signed 16-bit maximum against
+// `floor16x2`: 0 for a ReLU (negative values and -0 carry the sign bit, read as negative integers
+// and become +0; rounding keeps the sign, so this equals clamping before the conversion),
+// 0x80008000 for none (the smallest 16-bit integer twice: every pattern passes unchanged).
+__device__ __forceinline__ unsigned pack_bf16x2_relu(float lo, float hi, unsigned floor16x2)
+{
+    typedef float pk_f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 pk_bf16x2 __attribute__((ext_vector_type(2)));
+    typedef short pk_s16x2 __attribute__((ext_vector_type(2)));
+    const pk_f32x2 f = {lo, hi};
+    const pk_s16x2 b = __builtin_bit_cast(pk_s16x2, __builtin_convertvector(f, pk_bf16x2));
+    return __builtin_bit_cast(unsigned, __builtin_elementwise_max(b, __builtin_bit_cast(pk_s16x2, floor16x2)));
+}
+constexpr unsigned kReluFloor = 0u, kNoReluFloor = 0x80008000u;
+
 // host bf16 conversion, round to nearest even
 inline uint16_t f32_to_bf16_bits(float f)
 {
