@@ -330,11 +330,16 @@ __device__ __forceinline__ void igemm_tile(const IgemmArgs& a, int bx, int by, i
                     u32x4_t rv = {0u, 0u, 0u, 0u};
                     if (has_res) rv = rres[i][pass][0];
                     u32x4_t ov;
+                    if (has_res) {  // uniform: launches without a residual skip its unpacking and additions
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const float lo = v[2 * u] + __uint_as_float(rv[u] << 16);
-                        const float hi = v[2 * u + 1] + __uint_as_float(rv[u] & 0xffff0000u);
-                        ov[u] = pack_bf16x2_relu(lo, hi, relu_floor);
+                        for (int u = 0; u < 4; ++u) {
+                            const float lo = v[2 * u] + __uint_as_float(rv[u] << 16);
+                            const float hi = v[2 * u + 1] + __uint_as_float(rv[u] & 0xffff0000u);
+                            ov[u] = pack_bf16x2_relu(lo, hi, relu_floor);
+                        }
+                    } else {
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) ov[u] = pack_bf16x2_relu(v[2 * u], v[2 * u + 1], relu_floor);
                     }
                     *(u32x4_t*)(a.y + o * 2) = ov;
                 }
