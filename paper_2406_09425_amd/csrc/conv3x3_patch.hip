@@ -887,7 +887,7 @@ static int launch_patch_dl(const PatchArgs& a, int grid, hipStream_t stream)
                                     : 2 * (2 * BM * 32 + 64 * 9 * 32);
     static_assert(kLds <= 160 * 1024, "LDS of one CU");
     constexpr bool kStatOk = KC == 32;  // resident weights need room for every chunk
-    static bool raised = false;
+    static std::atomic<bool> raised{false};
     if (!raised) {
         if constexpr (kStatOk)
             SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3_patch_dl_kernel<BM, KC, kStatOk, false, NW>,
@@ -1052,7 +1052,7 @@ static int launch_s2_variant(const S2Args& a, int grid, hipStream_t stream)
 {
     constexpr int kLds = 2 * (s2_patch_cap(BM) * 32 + 64 * 9 * 32 + 64 * 32);
     static_assert(kLds <= 160 * 1024, "LDS of one CU");
-    static bool raised = false;
+    static std::atomic<bool> raised{false};
     if (!raised) {
         SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3s2_patch_kernel<BM, NW, true>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
         SGPRS_HIP(hipFuncSetAttribute((const void*)conv3x3s2_patch_kernel<BM, NW, false>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds));

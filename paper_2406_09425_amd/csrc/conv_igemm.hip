@@ -413,7 +413,7 @@ static int launch_variant(const IgemmArgs& a, const ConvPlan& p, hipStream_t str
 {
     const dim3 grid(p.grid_m, p.grid_n, p.splits), block(256);
     const size_t lds = (size_t)IgemmStages<BM, BN>::value * (BM + BN) * 128;
-    static bool raised = false;  // more than the default 64 KiB of dynamic LDS needs an opt-in per kernel
+    static std::atomic<bool> raised{false};  // more than the default 64 KiB of dynamic LDS needs an opt-in per kernel
     if (!raised) {
         SGPRS_HIP(hipFuncSetAttribute((const void*)conv_igemm_kernel<DT, BM, BN, WM, WN, true>,
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -447,7 +447,7 @@ static int launch_pair_variant(const IgemmArgs& a0, const ConvPlan& p0, const Ig
 {
     const int tiles0 = p0.grid_m * p0.grid_n, tiles1 = p1.grid_m * p1.grid_n;
     const size_t lds = (size_t)IgemmStages<BM, BN>::value * (BM + BN) * 128;
-    static bool raised = false;
+    static std::atomic<bool> raised{false};
     if (!raised) {
         SGPRS_HIP(hipFuncSetAttribute((const void*)conv_igemm_pair_kernel<DT, BM, BN, WM, WN>,
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));

@@ -163,7 +163,7 @@ static int launch_stem_variant(const StemArgs& a, int grid, hipStream_t stream)
     constexpr int ES = DT == SGPRS_BF16 ? 2 : 4;
     constexpr int PATCH_BYTES = (((2 * TP + 5) * kPatchW * 4 * ES + 15) / 16) * 16;
     const size_t lds = 64 * (kStemK * ES + 16) + PATCH_BYTES;
-    static bool raised = false;  // more than 64 KB of dynamic LDS needs an explicit opt-in
+    static std::atomic<bool> raised{false};  // more than 64 KB of dynamic LDS needs an explicit opt-in
     if (lds > 65536 && !raised) {
         SGPRS_HIP(hipFuncSetAttribute((const void*)conv_stem_kernel<DT, TP>,
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));

@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <hip/hip_ext.h>
 
 #include <cstdarg>

@@ -277,7 +277,7 @@ int launch_stem_pool(int dtype, int n, int h, int w, const void* x, const void* 
     const double bytes = ((double)n * h * w * 3 + 64.0 * 147 + (double)n * a.PP * a.PQ * 64) * es;
     int rc;
     if (prof && prof->on && (rc = prof->begin(stream, kKindStemPool, dtype, flops, bytes))) return rc;
-    static bool raised[2] = {false, false};
+    static std::atomic<bool> raised[2] = {{false}, {false}};
     if (dtype == SGPRS_BF16) {
         if (!raised[1]) {
             SGPRS_HIP(hipFuncSetAttribute((const void*)stem_pool_kernel<SGPRS_BF16>,
