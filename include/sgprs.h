@@ -95,7 +95,10 @@ int sgprs_build_cu_mask(int total_cus, int n_xcd, int cus, int partition, int bl
  * OVERSUBSCRIBED if n_p*cus exceeds the device without the flag. */
 int sgprs_pool_create(int device, int n_p, int cus_per_partition, unsigned flags,
                       sgprs_pool_t **out);
-/* Same with caller-chosen masks: masks[p*words_per_mask .. +words_per_mask) HOST. */
+/* Same with caller-chosen masks: masks[p*words_per_mask .. +words_per_mask) HOST.
+ * Mask bit i selects a CU of die i % n_xcd; INVALID_ARG for a mask that selects
+ * no CU at all or leaves one of the dies without a CU (workgroups are handed to
+ * the dies in turn, so such a stream could not run). */
 int sgprs_pool_create_masks(int device, int n_p, const uint32_t *masks, int words_per_mask,
                             sgprs_pool_t **out);
 /* Synchronises and destroys all partition streams. */

@@ -20,6 +20,7 @@
 // e(g) = g + 2*(g/H) + 1 and needs extended rows e-1, e, e+1; a run of output
 // rows therefore needs a contiguous run of extended rows, even across images.
 #include "internal.h"
+#include "patch_items.h"
 
 namespace sgprs {
 
@@ -48,42 +49,6 @@ struct PatchArgs {
 };
 
 __device__ __forceinline__ unsigned fdiv(unsigned x, unsigned magic) { return __umulhi(x, magic); }
-
-// Work-item index -> (split, channel block, row tile).  Workgroup b of a launch
-// runs on die b % 8 and keeps that die for all its items (the grid is a
-// multiple of 8).  With up to kRowTilePerDieMaxBlocks channel blocks, row tile
-// 8g + die and all its channel blocks run on one die at about the same time:
-// the input rows they share come from HBM once and hit in that die's L2, and
-// the weights of all channel blocks fit there as well (measured 5-7% faster on
-// the 128- and 256-channel layers).  With more channel blocks the weights would
-// not fit, so each die keeps one channel block (xcd_groups = 8 / n_ntiles) and
-// the input patches stream through.
-constexpr int kRowTilePerDieMaxBlocks = 4;
-struct PatchItem { int split, ntile, mtile; bool valid; };
-template <class Args> __device__ __forceinline__ PatchItem decode_item(const Args& a, int item)
-{
-    PatchItem r;
-    if (a.xcd_groups > 0) {
-        const int x = item & 7, s = item >> 3;
-        r.split = 0;
-        if (a.n_ntiles <= kRowTilePerDieMaxBlocks) {
-            r.ntile = s % a.n_ntiles;
-            r.mtile = (s / a.n_ntiles) * 8 + x;
-            r.valid = r.mtile < a.n_mtiles;
-        } else {
-            r.ntile = x % a.n_ntiles;
-            r.mtile = s * a.xcd_groups + x / a.n_ntiles;
-            r.valid = item < a.n_slots && r.mtile < a.n_mtiles;
-        }
-    } else {
-        r.split = item % a.splits;
-        const int t2 = item / a.splits;
-        r.ntile = t2 % a.n_ntiles;
-        r.mtile = t2 / a.n_ntiles;
-        r.valid = item < a.n_slots;
-    }
-    return r;
-}
 
 // ---- the kernel --------------------------------------------------------------------
 // Tiles of 512, 256 or 128 rows x 64 channels, chunks of 32 (or 16) channels.  The
@@ -164,7 +129,7 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
     // Work items blockIdx.x + k * gridDim.x; an item is n_chunks steps (n_chunks is
     // even, so every item starts on buffer 0 and ends on buffer 1).
     int item = blockIdx.x;
-    PatchItem cur = decode_item(a, item);
+    PatchItem cur = next_item(a, item, (int)gridDim.x);
     if (!cur.valid) return;
 
     const __amdgpu_buffer_rsrc_t w_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, (int)a.w_bytes, 0x00020000);
@@ -273,7 +238,8 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
                 for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
         // the item after this one (its first step is loaded during this item's last step)
-        const PatchItem nxt = decode_item(a, item + (int)gridDim.x);
+        int nxt_index = item + (int)gridDim.x;
+        const PatchItem nxt = next_item(a, nxt_index, (int)gridDim.x);
         if (nxt.valid) patch_offsets(nxt.mtile, p_next);
         // this item's chunks [cb, ce): an even count, so it starts on buffer 0 and ends on buffer 1
         const int cb = SPLIT ? cur.split * a.chunks_per_split : 0;
@@ -450,7 +416,7 @@ __global__ __launch_bounds__(NW * 64, (KC == 16 ? 2 : 1)) void conv3x3_patch_dl_
         }
         if (!nxt.valid) break;
         __syncthreads();  // the scratch area is free again before the next item's loads target it
-        item += gridDim.x;
+        item = nxt_index;
         cur = nxt;
     }
 #endif
@@ -516,7 +482,7 @@ __global__ __launch_bounds__(NW * 64, 1) void conv3x3s2_patch_kernel(const S2Arg
     const int wm = wave / WNW, wn = wave % WNW;
 
     int item = blockIdx.x;
-    PatchItem cur = decode_item(a, item);
+    PatchItem cur = next_item(a, item, (int)gridDim.x);
     if (!cur.valid) return;
 
     // weight loaders: 16-byte unit u is slot u % 2 of tap (u / 2) % 9 of row u / 18 (shortcut: slot u % 2 of row u / 2)
@@ -623,7 +589,8 @@ __global__ __launch_bounds__(NW * 64, 1) void conv3x3s2_patch_kernel(const S2Arg
                     if constexpr (PAIR) acc2[i][j][e] = 0.f;
                 }
 
-        const PatchItem nxt = decode_item(a, item + (int)gridDim.x);
+        int nxt_index = item + (int)gridDim.x;
+        const PatchItem nxt = next_item(a, nxt_index, (int)gridDim.x);
         if (nxt.valid) patch_offsets(nxt.mtile, p_next);
 
         if (first_item) {
@@ -728,7 +695,7 @@ __global__ __launch_bounds__(NW * 64, 1) void conv3x3s2_patch_kernel(const S2Arg
         }
         if (!nxt.valid) break;
         __syncthreads();
-        item += gridDim.x;
+        item = nxt_index;
         cur = nxt;
     }
 #endif
@@ -824,10 +791,7 @@ static bool patch_geometry_uncached(const sgprs_conv_desc_t& d, int v, int split
     a->mW = magic_for(d.w); a->mPW = magic_for(d.w + 2); a->mHE = magic_for(d.h + 2); a->mH = magic_for(d.h);
     a->TR = TR; a->n_mtiles = n_mtiles; a->n_ntiles = d.cout / pv.bn; a->n_chunks = n_chunks;
     a->chunks_per_split = cps; a->splits = splits; a->relu = d.relu;
-    a->xcd_groups = (splits == 1 && a->n_ntiles <= 8 && 8 % a->n_ntiles == 0) ? 8 / a->n_ntiles : 0;
-    a->n_slots = !a->xcd_groups ? n_mtiles * a->n_ntiles * splits
-                 : a->n_ntiles <= kRowTilePerDieMaxBlocks ? (n_mtiles + 7) / 8 * 8 * a->n_ntiles
-                                                          : 8 * ((n_mtiles + a->xcd_groups - 1) / a->xcd_groups);
+    patch_index_space(n_mtiles, a->n_ntiles, splits, &a->xcd_groups, &a->n_slots);
     return true;
 }
 
@@ -1025,10 +989,7 @@ static bool s2patch_geometry_uncached(const sgprs_conv_desc_t& d, int v, S2Args*
     a->mWo = magic_for(Wo); a->mPWh = magic_for(PWh); a->mHE = magic_for(d.h + 2); a->mHo = magic_for(Ho);
     a->TR = TR; a->n_mtiles = n_mtiles; a->n_ntiles = d.cout / 64; a->n_chunks = d.cin / 16; a->splits = 1;
     a->relu = d.relu;
-    a->xcd_groups = (a->n_ntiles <= 8 && 8 % a->n_ntiles == 0) ? 8 / a->n_ntiles : 0;
-    a->n_slots = !a->xcd_groups ? n_mtiles * a->n_ntiles
-                 : a->n_ntiles <= kRowTilePerDieMaxBlocks ? (n_mtiles + 7) / 8 * 8 * a->n_ntiles
-                                                          : 8 * ((n_mtiles + a->xcd_groups - 1) / a->xcd_groups);
+    patch_index_space(n_mtiles, a->n_ntiles, 1, &a->xcd_groups, &a->n_slots);
     return true;
 }
 

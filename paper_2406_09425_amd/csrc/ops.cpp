@@ -109,6 +109,8 @@ int sgprs_bn_relu(int dtype, size_t pixels, int c, const void* x, const float* s
     if (!dtype_ok(dtype)) return fail(SGPRS_ERR_UNSUPPORTED, "dtype %d", dtype);
     if (pixels == 0 || c <= 0) return fail(SGPRS_ERR_INVALID_ARG, "empty tensor");
     if (c % (dtype == SGPRS_BF16 ? 8 : 4)) return fail(SGPRS_ERR_UNSUPPORTED, "c %d not a multiple of the vector width", c);
+    if (pixels >= (1ull << 31) / (size_t)c || c / (dtype == SGPRS_BF16 ? 8 : 4) >= 65536)
+        return fail(SGPRS_ERR_UNSUPPORTED, "tensor with 2^31 or more elements, or 65536 or more channel vectors");
     if (!x || !y || !scale || !shift || !aligned16(x) || !aligned16(y))
         return fail(SGPRS_ERR_INVALID_ARG, "pointers must be non-NULL and 16-byte aligned");
     return launch_bn_relu(dtype, pixels, c, x, scale, shift, y, stream, cus, nullptr);
@@ -122,6 +124,7 @@ int sgprs_add_relu(int dtype, size_t count, const void* a, const void* b, void* 
     if ((rc = resolve(pool, partition, &stream, &cus))) return rc;
     if (!dtype_ok(dtype)) return fail(SGPRS_ERR_UNSUPPORTED, "dtype %d", dtype);
     if (count == 0 || count % 8) return fail(SGPRS_ERR_INVALID_ARG, "count %zu must be a positive multiple of 8", count);
+    if (count >= (1ull << 31)) return fail(SGPRS_ERR_UNSUPPORTED, "tensor with 2^31 or more elements");
     if (!a || !b || !y || !aligned16(a) || !aligned16(b) || !aligned16(y))
         return fail(SGPRS_ERR_INVALID_ARG, "pointers must be non-NULL and 16-byte aligned");
     return launch_add_relu(dtype, count, a, b, y, relu, stream, cus, nullptr);
@@ -135,6 +138,8 @@ int sgprs_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void* x,
     if ((rc = resolve(pool, partition, &stream, &cus))) return rc;
     if (!dtype_ok(dtype)) return fail(SGPRS_ERR_UNSUPPORTED, "dtype %d", dtype);
     if (n <= 0 || hw <= 0 || cout <= 0) return fail(SGPRS_ERR_INVALID_ARG, "non-positive dimension");
+    if (n > 65535 || cout > (1 << 20) || (long long)n * hw * cin >= (1ll << 31))
+        return fail(SGPRS_ERR_UNSUPPORTED, "more than 65535 images, 2^20 outputs or 2^31 input elements");
     if (cin != 512 && cin != 1024 && cin != 2048)
         return fail(SGPRS_ERR_UNSUPPORTED, "cin %d: supported are 512, 1024, 2048", cin);
     if (!x || !w || !logits || !workspace || !aligned16(x) || !aligned16(w) || !aligned16(workspace))

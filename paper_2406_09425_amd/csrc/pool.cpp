@@ -188,6 +188,17 @@ int sgprs_pool_create_masks(int device, int n_p, const uint32_t* masks, int word
         }
         if (popcount_mask(m[p]) == 0)
             return fail(SGPRS_ERR_INVALID_ARG, "mask of partition %d selects no CU", p);
+        // The hardware hands the workgroups of a launch to the dies in turn, and mask bit i selects a
+        // CU of die i % n_xcd: a stream whose mask leaves a die without CUs cannot run there (the
+        // driver refuses to create it), so it is rejected here with a message that says why.
+        const int n_xcd = guess_xcds(total);
+        for (int x = 0; x < n_xcd; ++x) {
+            bool any = false;
+            for (int bit = x; bit < total && !any; bit += n_xcd) any = (m[p][bit >> 5] >> (bit & 31)) & 1u;
+            if (!any)
+                return fail(SGPRS_ERR_INVALID_ARG, "mask of partition %d selects no CU on die %d (bits %d, %d, ...): every one of the %d dies needs one",
+                            p, x, x, x + n_xcd, n_xcd);
+        }
     }
     return make_pool(device, total, m, 0, out);
 }

@@ -18,6 +18,7 @@ from gpu_util import (DevConv, assert_close, dev_empty, dev_f32, dev_nhwc, host_
 pytestmark = pytest.mark.gpu
 DTYPES = [S.SGPRS_F32, S.SGPRS_BF16]
 DT_ID = {S.SGPRS_F32: "f32", S.SGPRS_BF16: "bf16"}
+PART_SIZES = (8, 64, "full")   # keys of the `pools` fixture
 
 
 @pytest.fixture(scope="module")
@@ -131,10 +132,11 @@ def test_maxpool_parity_exact(pools, dtype, shape):
     x = make_input(91, 0, shape, bf16=dtype == S.SGPRS_BF16)  # has negatives: padding must not win
     ref = oracle.maxpool2d(x)
     xd = dev_nhwc(x, dtype)
-    yd = dev_empty((n, ref.shape[2], ref.shape[3], c), dtype)
-    S.sgprs_maxpool2d(dtype, n, h, w, c, xd.data_ptr(), yd.data_ptr(), pools["full"], 0)
-    pools["full"].sync()
-    assert np.array_equal(host_nchw(yd), ref)  # selection only: bit exact
+    for cus in PART_SIZES:   # the partition sizes the per-operator sweep times
+        yd = dev_empty((n, ref.shape[2], ref.shape[3], c), dtype)
+        S.sgprs_maxpool2d(dtype, n, h, w, c, xd.data_ptr(), yd.data_ptr(), pools[cus], 0)
+        pools[cus].sync()
+        assert np.array_equal(host_nchw(yd), ref), cus  # selection only: bit exact
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=DT_ID.get)
@@ -145,11 +147,12 @@ def test_bn_relu_parity(pools, dtype):
     ref = oracle.relu(oracle.bn(x, g, b, m, v, BN_EPS))
     sc, sh = S.sgprs_fold_bn(g, b, m, v, BN_EPS)
     xd, scd, shd = dev_nhwc(x, dtype), dev_f32(sc), dev_f32(sh)
-    yd = dev_empty((1, 28, 28, 128), dtype)
-    S.sgprs_bn_relu(dtype, 28 * 28, 128, xd.data_ptr(), scd.data_ptr(), shd.data_ptr(), yd.data_ptr(),
-                    pools["full"], 0)
-    pools["full"].sync()
-    assert_close(host_nchw(yd), ref, dtype, "bn_relu")
+    for cus in PART_SIZES:
+        yd = dev_empty((1, 28, 28, 128), dtype)
+        S.sgprs_bn_relu(dtype, 28 * 28, 128, xd.data_ptr(), scd.data_ptr(), shd.data_ptr(), yd.data_ptr(),
+                        pools[cus], 0)
+        pools[cus].sync()
+        assert_close(host_nchw(yd), ref, dtype, f"bn_relu on {cus} CUs")
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=DT_ID.get)
@@ -162,12 +165,13 @@ def test_add_parity(pools, dtype, relu):
     if relu:
         ref = oracle.relu(ref)
     ad, bd = dev_nhwc(a, dtype), dev_nhwc(b, dtype)
-    yd = dev_empty((1, 7, 7, 512), dtype)
-    S.sgprs_add_relu(dtype, a.size, ad.data_ptr(), bd.data_ptr(), yd.data_ptr(), relu, pools["full"], 0)
-    pools["full"].sync()
-    assert_close(host_nchw(yd), ref, dtype, "add")
-    if not relu:
-        assert np.min(host_nchw(yd)) < 0
+    for cus in PART_SIZES:
+        yd = dev_empty((1, 7, 7, 512), dtype)
+        S.sgprs_add_relu(dtype, a.size, ad.data_ptr(), bd.data_ptr(), yd.data_ptr(), relu, pools[cus], 0)
+        pools[cus].sync()
+        assert_close(host_nchw(yd), ref, dtype, f"add on {cus} CUs")
+        if not relu:
+            assert np.min(host_nchw(yd)) < 0
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=DT_ID.get)
@@ -182,12 +186,13 @@ def test_avgpool_fc_parity(pools, dtype, n):
     wd = torch.from_numpy(np.ascontiguousarray(w)).to(xd.dtype).cuda()
     bd = dev_f32(bias)
     ws = torch.empty(n * 512, dtype=torch.float32, device="cuda")
-    yd = torch.full((n, 1000), float("nan"), dtype=torch.float32, device="cuda")
-    S.sgprs_avgpool_fc(dtype, n, 49, 512, 1000, xd.data_ptr(), wd.data_ptr(), bd.data_ptr(), yd.data_ptr(),
-                       ws.data_ptr(), pools["full"], 0)
-    pools["full"].sync()
-    got = yd.cpu().numpy().astype(np.float64)
-    assert_close(got, ref, dtype, "avgpool_fc")
+    for cus in PART_SIZES:
+        yd = torch.full((n, 1000), float("nan"), dtype=torch.float32, device="cuda")
+        S.sgprs_avgpool_fc(dtype, n, 49, 512, 1000, xd.data_ptr(), wd.data_ptr(), bd.data_ptr(), yd.data_ptr(),
+                           ws.data_ptr(), pools[cus], 0)
+        pools[cus].sync()
+        got = yd.cpu().numpy().astype(np.float64)
+        assert_close(got, ref, dtype, f"avgpool_fc on {cus} CUs")
     # without bias
     S.sgprs_avgpool_fc(dtype, n, 49, 512, 1000, xd.data_ptr(), wd.data_ptr(), None, yd.data_ptr(),
                        ws.data_ptr(), pools["full"], 0)
@@ -199,11 +204,13 @@ def test_avgpool_fc_parity(pools, dtype, n):
 @pytest.mark.parametrize("cin,hw", [(512, 49), (1024, 21), (512, 3)])
 def test_avgpool_fc_one_launch_equals_two(pools, dtype, cin, hw):
     """Up to 8 images take the single fused launch, more take avg-pool then FC: the same bits."""
-    tdt = torch.bfloat16 if dtype == S.SGPRS_BF16 else torch.float32
-    g = torch.Generator().manual_seed(cin + hw)
-    xd = torch.randn((9, hw, cin), generator=g).to(tdt).cuda()
-    wd = (torch.randn((1000, cin), generator=g) * 0.05).to(tdt).cuda()
-    bd = torch.randn((1000,), generator=g).cuda()
+    bf = dtype == S.SGPRS_BF16
+    x = make_input(96, cin + hw, (9, cin, hw, 1), bf16=bf)
+    w = make_conv_weight(96, cin + hw, 1, 1000, cin, 1, bf16=bf)[:, :, 0, 0]
+    bias = make_input(96, cin + hw, (1000,), tensor_id=2).astype(np.float32)
+    xd = dev_nhwc(x, dtype).reshape(9, hw, cin)
+    wd = torch.from_numpy(np.ascontiguousarray(w)).to(xd.dtype).cuda()
+    bd = dev_f32(bias)
     ws = torch.empty(9 * cin, dtype=torch.float32, device="cuda")
     two = torch.full((9, 1000), float("nan"), dtype=torch.float32, device="cuda")
     one = torch.full((8, 1000), float("nan"), dtype=torch.float32, device="cuda")
@@ -214,8 +221,9 @@ def test_avgpool_fc_one_launch_equals_two(pools, dtype, cin, hw):
     pools["full"].sync()
     assert torch.isfinite(one).all()
     assert torch.equal(one, two[:8])
-    ref = (xd.double().mean(dim=1) @ wd.double().T + bd.double()).cpu()[:8]
-    assert (one.cpu().double() - ref).abs().max() <= 1e-4 * ref.abs().max()
+    ref = oracle.fc(oracle.global_avgpool(x), w, bias)
+    assert_close(two.cpu().numpy().astype(np.float64), ref, dtype, "two launches")
+    assert_close(one.cpu().numpy().astype(np.float64), ref[:8], dtype, "one launch")
 
 
 def test_error_paths_enqueue_nothing(pools):
@@ -291,6 +299,42 @@ def test_conv3x3s2_patch_variants_parity(pools, variant, shape):
         assert_close(got, ref, S.SGPRS_BF16, f"stride-2 with residual {shape}")
     finally:
         S.sgprs_conv_tuning_override(-1, 0, 1)
+
+
+def test_masks_that_leave_a_die_empty_are_rejected_and_odd_masks_work():
+    """Mask bit i selects a CU of die i % 8.  A mask without a CU on some die is refused with a
+    clear error; a mask of 9 CUs (two on die 0) is fine, and the forced patch kernels on it (a grid
+    of 8 workgroups walking the padded, die-keyed work-item space) match the oracle."""
+    n_xcd = S.Pool(1, 8).info()["n_xcd"]
+    for bits in ((1 << 1) - 1, (1 << 4) - 1, (1 << 7) - 1):
+        mask = np.zeros((1, 8), dtype=np.uint32)
+        mask[0, 0] = bits
+        if n_xcd > 1:
+            with pytest.raises(S.SgprsError) as e:
+                S.Pool(1, 0, masks=mask)
+            assert e.value.status == -1 and "die" in str(e.value)
+    mask = np.zeros((1, 8), dtype=np.uint32)
+    mask[0, 0] = (1 << 9) - 1
+    pool = S.Pool(1, 0, masks=mask)
+    assert pool.partition_cus(0) == 9
+    dtype = S.SGPRS_BF16
+    try:
+        for variant, shape in ((0, (1, 28, 28, 128, 128)), (1, (3, 14, 14, 64, 256)), (3, (2, 14, 14, 64, 512)),
+                               (4, (2, 28, 28, 64, 128))):
+            S.sgprs_conv_tuning_override(1, variant, 1)
+            n, h, w, cin, cout = shape
+            got, ref = conv_case(dtype, n, h, w, cin, cout, 3, 1, 1, relu=True, with_res=True, seed=120,
+                                 pool=pool, cus=9)
+            assert_close(got, ref, dtype, f"patch variant {variant} {shape} on 9 CUs")
+        for variant, shape in ((0, (3, 28, 28, 64, 128)), (1, (9, 14, 14, 64, 512))):
+            S.sgprs_conv_tuning_override(3, variant, 1)
+            n, h, w, cin, cout = shape
+            got, ref = conv_case(dtype, n, h, w, cin, cout, 3, 2, 1, relu=True, with_res=False, seed=130,
+                                 pool=pool, cus=9)
+            assert_close(got, ref, dtype, f"stride-2 patch variant {variant} {shape} on 9 CUs")
+    finally:
+        S.sgprs_conv_tuning_override(-1, 0, 1)
+        pool.destroy()
 
 
 def test_conv_planner_choices_agree(pools):

@@ -176,6 +176,32 @@ def test_downsample_block_runs_as_one_paired_launch(cfg1):
         pool.destroy()
 
 
+def test_stage0_fp32_fused_stem_pool_elementwise(cfg1):
+    """fp32 launches of at least two tiles per CU take the fused conv7x7 + max-pool kernel
+    (kind 9): its stage-0 output, element by element against the oracle, on 8 and 64 CUs, with a
+    ragged batch; the same images on the whole chip take the two-kernel path and agree."""
+    params = cfg1[0]
+    dtype = S.SGPRS_F32
+    nb = 3
+    x = make_input(1, 13, (nb, 3, 224, 224))
+    ref = oracle.resnet18_stage(0, params, BN_EPS, x)
+    total = S.Pool(1, 8).info()["total_cus"]
+    xd = dev_nhwc(x, dtype)
+    for cus, want_fused in ((8, True), (64, True), (total, False)):
+        pool = S.Pool(1, cus)
+        task = S.Task(params, dtype, nb, BN_EPS)
+        task.set_profiling(True)
+        o = dev_empty(stage_shape(0, nb), dtype)
+        task.stage_run(0, nb, xd.data_ptr(), o.data_ptr(), pool, 0)
+        pool.sync()
+        kinds = [r["kind"] for r in task.kernel_times(0)]
+        assert (kinds == [9]) == want_fused, (cus, kinds)
+        e = assert_close(host_nchw(o), ref, dtype, f"fp32 stage 0 on {cus} CUs")
+        assert e < 2e-5, (cus, e)
+        task.destroy()
+        pool.destroy()
+
+
 # ------------------------------------------------------------- config 3
 def test_config3_eight_bf16_instances_on_8x32_pool():
     dtype = S.SGPRS_BF16
@@ -212,7 +238,7 @@ def test_config3_eight_bf16_instances_on_8x32_pool():
 
 
 # ------------------------------------------------------------- config 4
-def test_config4_batch64_bf16_sampled_against_oracle(full_pool):
+def test_config4_batch64_bf16_every_image_against_oracle(full_pool):
     dtype = S.SGPRS_BF16
     n = 64
     params = make_resnet18_params(4, 0, bf16=True)
@@ -224,7 +250,7 @@ def test_config4_batch64_bf16_sampled_against_oracle(full_pool):
     full_pool.sync()
     got = lg.cpu().numpy().astype(np.float64)
     assert np.all(np.isfinite(got))
-    sample = [0, 1, 31, 62, 63]           # first, last and middle images (tile edges of the batch)
+    sample = list(range(n))    # every image: row tiles straddle image borders with a different phase in each
     ref, ref_stages = oracle.resnet18(params, BN_EPS, x[sample], want_stages=True)
     e = assert_close(got[sample], ref, dtype, "config 4 logits")
     check_argmax(got[sample], ref, e, "config 4")
