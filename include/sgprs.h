@@ -217,6 +217,21 @@ int sgprs_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void *x,
                      const float *bias, float *logits, float *workspace, sgprs_pool_t *pool,
                      int partition);
 
+/* The same operator for callers that cannot allocate device memory or pass a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  The pooled vectors go to a 512 KiB array that is part of
+ * the library's device image (one copy per GPU, held until the process ends);
+ * its address is looked up on the first call on a device, and no call
+ * allocates or frees anything.  n * cin must not exceed 131072 (64 * 2048)
+ * values: UNSUPPORTED beyond that.  Every call on a GPU shares that GPU's
+ * array, which keeps the last call's contents: calls that overlap in time on
+ * one GPU (different partitions, or threads) race on it, so serialise them.
+ * Nothing in it needs clearing: each call overwrites the n * cin values it
+ * reads.  Logits are bit-identical to sgprs_avgpool_fc's. */
+int sgprs_avgpool_fc_static(int dtype, int n, int hw, int cin, int cout, const void *x,
+                            const void *w, const float *bias, float *logits, sgprs_pool_t *pool,
+                            int partition);
+
 /* ------------------------------------------------------------------ task --
  * Task tau_i = one ResNet18 instance, split into the paper's six stages:
  *   0 conv7x7/2+BN+ReLU+maxpool3x3/2, 1..4 layer1..layer4 (two BasicBlocks

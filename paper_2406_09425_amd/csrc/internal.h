@@ -219,6 +219,11 @@ int launch_add_relu(int dtype, size_t count, const void* a, const void* b, void*
 int launch_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void* x, const void* w,
                       const float* bias, float* logits, float* ws, hipStream_t stream, int cus,
                       Profiler* prof);
+// Device address of this GPU's static pooled-vector scratch (kStaticScratchFloats fp32), looked up
+// on first use; nothing is allocated.
+constexpr size_t kStaticScratchFloats = 64 * 2048;
+constexpr int kMaxStaticScratchDevices = 16;
+int static_scratch(int device, float** out);
 int launch_probe(int n_blocks, int spin_cycles, uint32_t* out, hipStream_t stream);
 int launch_mfma_probe(int cus, int steps, int random_data, unsigned long long* out, hipStream_t stream);
 int launch_load_probe(int cus, const void* buf, size_t buf_bytes, unsigned region, int iters, unsigned* out, hipStream_t stream);

@@ -147,4 +147,26 @@ int sgprs_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void* x,
     return launch_avgpool_fc(dtype, n, hw, cin, cout, x, w, bias, logits, workspace, stream, cus, nullptr);
 }
 
+int sgprs_avgpool_fc_static(int dtype, int n, int hw, int cin, int cout, const void* x, const void* w, const float* bias,
+                            float* logits, sgprs_pool_t* pool, int partition)
+{
+    hipStream_t stream;
+    int cus = 0, rc;
+    if ((rc = resolve(pool, partition, &stream, &cus))) return rc;
+    if (!dtype_ok(dtype)) return fail(SGPRS_ERR_UNSUPPORTED, "dtype %d", dtype);
+    if (n <= 0 || hw <= 0 || cout <= 0) return fail(SGPRS_ERR_INVALID_ARG, "non-positive dimension");
+    if (n > 65535 || cout > (1 << 20) || (long long)n * hw * cin >= (1ll << 31))
+        return fail(SGPRS_ERR_UNSUPPORTED, "more than 65535 images, 2^20 outputs or 2^31 input elements");
+    if (cin != 512 && cin != 1024 && cin != 2048)
+        return fail(SGPRS_ERR_UNSUPPORTED, "cin %d: supported are 512, 1024, 2048", cin);
+    if ((size_t)n * (size_t)cin > kStaticScratchFloats)
+        return fail(SGPRS_ERR_UNSUPPORTED, "n * cin = %zu pooled values exceed the static scratch of %zu", (size_t)n * (size_t)cin,
+                    kStaticScratchFloats);
+    if (!x || !w || !logits || !aligned16(x) || !aligned16(w))
+        return fail(SGPRS_ERR_INVALID_ARG, "pointers must be non-NULL and 16-byte aligned");
+    float* ws = nullptr;
+    if ((rc = static_scratch(pool->device, &ws))) return rc;
+    return launch_avgpool_fc(dtype, n, hw, cin, cout, x, w, bias, logits, ws, stream, cus, nullptr);
+}
+
 }  // extern "C"

@@ -512,6 +512,34 @@ int launch_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void* x
     return SGPRS_OK;
 }
 
+// ---- pooled-vector scratch for callers that cannot allocate ------------------
+// One array per GPU, held until the process ends.  In host code the array's
+// name is only a stand-in: the device address is looked up once per device,
+// with that device current, and kept.
+static __device__ __align__(256) float scratch[kStaticScratchFloats];
+static std::mutex g_scratch_mu;
+static float* g_scratch_ptr[kMaxStaticScratchDevices];
+
+int static_scratch(int device, float** out)
+{
+    if (device < 0 || device >= kMaxStaticScratchDevices)
+        return fail(SGPRS_ERR_UNSUPPORTED, "device %d: the static scratch covers devices 0..%d", device, kMaxStaticScratchDevices - 1);
+    std::lock_guard<std::mutex> guard(g_scratch_mu);
+    if (!g_scratch_ptr[device]) {
+        int prev = 0;
+        SGPRS_HIP(hipGetDevice(&prev));
+        if (prev != device) SGPRS_HIP(hipSetDevice(device));
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (prev != device) (void)hipSetDevice(prev);
+        if (e != hipSuccess || !p)
+            return fail(SGPRS_ERR_HIP, "hipGetSymbolAddress(scratch) failed on device %d: %s", device, hipGetErrorString(e));
+        g_scratch_ptr[device] = (float*)p;
+    }
+    *out = g_scratch_ptr[device];
+    return SGPRS_OK;
+}
+
 int launch_probe(int n_blocks, int spin_cycles, uint32_t* out, hipStream_t stream)
 {
     SGPRS_LAUNCH(probe_kernel, dim3(n_blocks), dim3(64), 0, stream, out, spin_cycles);
