@@ -77,6 +77,10 @@ def main():
     ap.add_argument("--periodic-only", action="store_true", help="only the periodic-task scheduler experiment")
     ap.add_argument("--batch-sweep-only", action="store_true", help="only the bf16 throughput at batches 1..32")
     ap.add_argument("--probes-only", action="store_true", help="only the sustained MFMA and load-path probes")
+    ap.add_argument("--pool-scaling-only", default=None, metavar="N[,N...]",
+                    help="only the eight-instance throughput on pools of N equal partitions (for tracing which kernels "
+                         "run beside which), e.g. 8 or 4,8")
+    ap.add_argument("--pool-rounds", type=int, default=150, help="rounds of eight inferences per pool in that leg")
     ap.add_argument("--membound-only", action="store_true",
                     help="run only the memory-bound operator leg (for profiling it); prints its own JSON line")
     ap.add_argument("--copy-calib", action="store_true",
@@ -115,6 +119,13 @@ def main():
     if args.probes_only:
         print(json.dumps(dict(sustained_mfma=leg_mfma_probe(S, hip, torch, pool, stream, total_cus),
                               sustained_load_to_lds=leg_load_probe(S, hip, torch, pool, stream, total_cus))), flush=True)
+        pool.destroy()
+        return
+
+    if args.pool_scaling_only:
+        parts = tuple(int(v) for v in args.pool_scaling_only.split(","))
+        print(json.dumps(dict(pool_scaling=leg_pool_scaling(S, torch, total_cus, nhwc, rounds=args.pool_rounds, partitions=parts))),
+              flush=True)
         pool.destroy()
         return
 
@@ -586,14 +597,13 @@ def leg_oversubscribed(S, torch, total_cus, nhwc, headline_ips, rounds=300):
 
 
 def leg_periodic(S, hip, torch, total_cus, nhwc, n_list=(128, 256, 320, 384, 448, 512, 576), levels=(1.0, 1.5, 2.0),
-                 shapes=((2, 3), (4, 1)), fps=32.0, duration=0.5):
+                 shapes=((2, 4), (4, 1)), fps=32.0, duration=0.5):
     """'Simulation Results' in kind: N identical periodic ResNet18 tasks (bf16, batch 1, six stages,
     deadline = period = 1/32 s, releases spread evenly over the period) under the SGPRS scheduler
     (sgprs_sched_run_periodic), at over-subscription levels 1.0 / 1.5 / 2.0 (CUs of all contexts /
-    CUs of the GPU), on two pool shapes: two contexts with three lanes each (one for high-priority
-    stages, two for the others: the nearest to the paper's two-high-two-low that does not keep more
-    than four CU-masked streams busy at once, which collapses on this system), and four contexts
-    with one lane each.  Stage WCETs are measured first, on one lane with the rest of the GPU idle
+    CUs of the GPU), on two pool shapes: the paper's two contexts with four lanes each (two for
+    high-priority stages, two for the others; the run loop keeps at most four of the eight CU-masked
+    streams busy at once, because more collapse on this system), and four contexts with one lane each.  Stage WCETs are measured first, on one lane with the rest of the GPU idle
     (the paper's offline phase).  Reported: total FPS and deadline miss rate against the number of
     tasks, and the pivot point (the largest N without a miss)."""
     from workloads import BN_EPS, make_input, make_resnet18_params
@@ -653,7 +663,7 @@ def leg_periodic(S, hip, torch, total_cus, nhwc, n_list=(128, 256, 320, 384, 448
     return dict(task_fps=fps, duration_s=duration, pools=out)
 
 
-def leg_pool_scaling(S, torch, total_cus, nhwc, instances=8, rounds=150):
+def leg_pool_scaling(S, torch, total_cus, nhwc, instances=8, rounds=150, partitions=(1, 2, 3, 4, 8)):
     """Eight bf16 batch-1 instances spread round-robin over pools of 1, 2, 3, 4 and 8 equal
     partitions (the paper's question: how does throughput grow with the number of contexts?).
     Every instance is issued with sgprs_task_run from one host thread, i.e. replayed as a HIP
@@ -665,7 +675,7 @@ def leg_pool_scaling(S, torch, total_cus, nhwc, instances=8, rounds=150):
         xs.append(nhwc(make_input(3, i, (1, 3, 224, 224), bf16=True), torch.bfloat16))
         lgs.append(torch.empty((1, 1000), dtype=torch.float32, device="cuda"))
     res = []
-    for n_p in (1, 2, 3, 4, 8):
+    for n_p in partitions:
         cus = total_cus // n_p // 8 * 8
         pool = S.Pool(n_p, cus)
 
@@ -732,6 +742,12 @@ def leg_multi_tenant(S, hip, torch, total_cus, nhwc, n_p=8, rounds=100):
     pool.sync()
     dt = time.perf_counter() - t0
     conc = n_p * rounds / dt
+    # the same eight tasks on the same eight partitions through the library's static executor, which
+    # keeps at most four partitions busy at once (and without that gate, for comparison)
+    ptrs = ([x.data_ptr() for x in xs], [l.data_ptr() for l in lgs])
+    pool.run_static(tasks, ptrs[0], ptrs[1], 1, list(range(n_p)), 20, 4)
+    gated = n_p * rounds / pool.run_static(tasks, ptrs[0], ptrs[1], 1, list(range(n_p)), rounds, 4)
+    ungated = n_p * rounds / pool.run_static(tasks, ptrs[0], ptrs[1], 1, list(range(n_p)), rounds, 0)
     # context: the same eight images back to back on one full-GPU partition
     full = S.Pool(1, total_cus)
     t0 = time.perf_counter()
@@ -741,6 +757,7 @@ def leg_multi_tenant(S, hip, torch, total_cus, nhwc, n_p=8, rounds=100):
     full.sync()
     serial = n_p * rounds / (time.perf_counter() - t0)
     out = dict(instances=n_p, partition_cus=total_cus // n_p, aggregate_images_per_s=round(conc, 1),
+               run_static_max_4_busy_images_per_s=round(gated, 1), run_static_no_gate_images_per_s=round(ungated, 1),
                serial_full_gpu_images_per_s=round(serial, 1), issue="one host thread, round-robin over instances",
                stage_latency_ms_median=[[round(statistics.median(l), 4) for l in inst] for inst in lat])
     log("multi_tenant", json.dumps({k: v for k, v in out.items() if k != "stage_latency_ms_median"}))

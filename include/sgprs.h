@@ -188,7 +188,8 @@ int sgprs_conv2d_workspace(const sgprs_conv_desc_t *d, int partition_cus, size_t
 int sgprs_conv2d(const sgprs_conv_desc_t *d, const void *x, const void *w_packed,
                  const float *scale, const float *shift, const void *residual, void *y,
                  void *workspace, size_t workspace_bytes, sgprs_pool_t *pool, int partition);
-/* Measurement hook, process-wide, not thread-safe: which convolution kernel
+/* Measurement hook, process-wide (atomic settings, read by every thread that plans a
+ * launch; launches already planned keep their plan): which convolution kernel
  * sgprs_conv2d and the stages pick for 3x3 bf16 layers.  kind -1: automatic
  * (default); 0: implicit GEMM only; 1: the stride-1 LDS-patch kernel with the
  * given tile variant (0..4) and split factor where the shape allows it; 2:
@@ -363,6 +364,13 @@ int sgprs_sched_next(sgprs_sched_t *sched, double now, sgprs_dispatch_t *out);
  * job's next stage, if any, is released at `now`.  Error if it is not running. */
 int sgprs_sched_complete(sgprs_sched_t *sched, int task, int job, int stage, double now, int *missed);
 int sgprs_sched_get_stats(const sgprs_sched_t *sched, sgprs_sched_stats_t *out);
+/* Run loop only (sgprs_sched_run_periodic): at most max_busy lanes have a stage
+ * in flight at once; further stages wait in the scheduler's queues even if their
+ * lane is free.  Default 4: on MI355X more than four CU-masked streams busy at
+ * once cut the throughput of all of them by more than half, whatever their
+ * size (idle ones cost nothing).  0: no limit.  The scheduler's decisions
+ * (sgprs_sched_next) are not affected. */
+int sgprs_sched_set_max_busy(sgprs_sched_t *sched, int max_busy);
 
 /* The periodic-release experiment of "Simulation Results" on the real pool.
  * tasks[i] (HOST array of n_tasks handles, n_tasks = the scheduler's task
@@ -394,6 +402,20 @@ typedef struct {
 int sgprs_sched_run_periodic(sgprs_sched_t *sched, sgprs_pool_t *pool, sgprs_task_t *const *tasks,
                              int n_tasks, const void *const *inputs, float *const *logits, int batch,
                              const double *offsets, double duration_s, sgprs_run_report_t *report);
+
+/* Static, purely spatial execution of the task model's pool (every task keeps
+ * one partition: the comparison shape of "Simulation Results"): task i runs
+ * `rounds` inferences of `batch` images on partition partition_of_task[i]
+ * (HOST int[n_tasks]) through sgprs_task_run; inputs[i] / logits[i] DEVICE as
+ * there.  The calling thread hands out one inference at a time per task,
+ * round-robin, keeps at most max_busy partitions busy at once (0: no limit; see
+ * sgprs_sched_set_max_busy for why 4 is the useful value on MI355X), and polls
+ * one event per task.  Blocking; *elapsed_s (may be NULL) receives the wall time
+ * from the first launch to the last completion.  Tasks sharing a partition run
+ * one after the other. */
+int sgprs_pool_run_static(sgprs_pool_t *pool, sgprs_task_t *const *tasks, int n_tasks,
+                          const void *const *inputs, float *const *logits, int batch,
+                          const int *partition_of_task, int rounds, int max_busy, double *elapsed_s);
 
 #ifdef __cplusplus
 }

@@ -130,6 +130,8 @@ def lib():
         "sgprs_sched_next": (c_int, [vp, c_double, POINTER(Dispatch)]),
         "sgprs_sched_complete": (c_int, [vp, c_int, c_int, c_int, c_double, ip]),
         "sgprs_sched_get_stats": (c_int, [vp, POINTER(SchedStats)]),
+        "sgprs_sched_set_max_busy": (c_int, [vp, c_int]),
+        "sgprs_pool_run_static": (c_int, [vp, POINTER(vp), c_int, POINTER(vp), POINTER(vp), c_int, ip, c_int, c_int, POINTER(c_double)]),
         "sgprs_sched_run_periodic": (c_int, [vp, vp, POINTER(vp), c_int, POINTER(vp), POINTER(vp), c_int, POINTER(c_double), c_double,
                                              POINTER(RunReport)]),
     }
@@ -265,6 +267,17 @@ class Pool:
 
     def load_probe(self, p: int, buf_ptr: int, buf_bytes: int, region_bytes: int, iters: int, out_ptr: int) -> None:
         _check(lib().sgprs_load_probe(self.handle, p, buf_ptr, buf_bytes, region_bytes, iters, out_ptr))
+
+    def run_static(self, tasks, input_ptrs, logits_ptrs, batch: int, partition_of_task, rounds: int, max_busy: int = 4) -> float:
+        """sgprs_pool_run_static: seconds from the first launch to the last completion."""
+        n = len(tasks)
+        th = (c_void_p * n)(*[getattr(t.handle, "value", t.handle) for t in tasks])
+        ins = (c_void_p * n)(*input_ptrs)
+        outs = (c_void_p * n)(*logits_ptrs)
+        parts = (c_int * n)(*[int(p) for p in partition_of_task])
+        el = c_double()
+        _check(lib().sgprs_pool_run_static(self.handle, th, n, ins, outs, batch, parts, rounds, max_busy, ctypes.byref(el)))
+        return el.value
 
     def destroy(self) -> None:
         if self.handle:
@@ -436,6 +449,9 @@ class Sched:
         out = {k: getattr(rep, k) for k in ("elapsed_s", "releases", "dropped", "fps", "dmr", "mean_response_s", "max_response_s")}
         out.update({k: int(getattr(rep.sched, k)) for k, _ in SchedStats._fields_})
         return out
+
+    def set_max_busy(self, max_busy: int) -> None:
+        _check(lib().sgprs_sched_set_max_busy(self.handle, max_busy))
 
     def stats(self) -> dict:
         st = SchedStats()

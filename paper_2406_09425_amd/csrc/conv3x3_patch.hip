@@ -795,7 +795,7 @@ static bool patch_geometry_uncached(const sgprs_conv_desc_t& d, int v, int split
     return true;
 }
 
-static int g_force_variant = -1, g_force_splits = 0;
+static std::atomic<int> g_force_variant{-1}, g_force_splits{0};
 void patch_force(int variant, int splits) { g_force_variant = variant; g_force_splits = splits; }
 
 // Picks the tile variant: the candidate with the smallest estimated time
@@ -807,10 +807,10 @@ bool plan_patch(const sgprs_conv_desc_t& d, int cus, int* variant, int* splits)
 {
     if (!patch_eligible(d)) return false;
     PatchArgs a;
-    if (g_force_variant >= 0) {
-        if (g_force_variant >= kNumPatchVariants || !patch_geometry(d, g_force_variant, std::max(1, g_force_splits), &a))
-            return false;
-        *variant = g_force_variant; *splits = std::max(1, g_force_splits);
+    const int fv = g_force_variant.load(), fs = g_force_splits.load();
+    if (fv >= 0) {
+        if (fv >= kNumPatchVariants || !patch_geometry(d, fv, std::max(1, fs), &a)) return false;
+        *variant = fv; *splits = std::max(1, fs);
         return true;
     }
     // {variant, microseconds per chunk, microseconds per work item}
@@ -925,7 +925,7 @@ int launch_conv3x3_patch(const sgprs_conv_desc_t& d, int variant, int splits, co
 struct S2Variant { int bm, nw; };
 static const S2Variant kS2Variants[] = {{256, 8}, {128, 4}};
 constexpr int kNumS2Variants = 2;
-static int g_s2_force = -1;  // -1 automatic, 0 / 1 that tile where the shape allows it, 2 never
+static std::atomic<int> g_s2_force{-1};  // -1 automatic, 0 / 1 that tile where the shape allows it, 2 never
 void s2patch_force(int v) { g_s2_force = v; }
 int s2patch_num_variants() { return kNumS2Variants; }
 
@@ -1001,10 +1001,11 @@ static bool s2patch_geometry_uncached(const sgprs_conv_desc_t& d, int v, S2Args*
 bool plan_s2patch(const sgprs_conv_desc_t& d, int cus, int* variant)
 {
     (void)cus;
-    if (g_s2_force < 0 || g_s2_force >= kNumS2Variants || !s2patch_eligible(d)) return false;
+    const int force = g_s2_force.load();
+    if (force < 0 || force >= kNumS2Variants || !s2patch_eligible(d)) return false;
     S2Args a;
-    if (!s2patch_geometry(d, g_s2_force, &a)) return false;
-    *variant = g_s2_force;
+    if (!s2patch_geometry(d, force, &a)) return false;
+    *variant = force;
     return true;
 }
 

@@ -30,6 +30,11 @@ int fail(int status, const char* fmt, ...) __attribute__((format(printf, 2, 3)))
                                  hipGetErrorString(e_), __FILE__, __LINE__);              \
     } while (0)
 
+// CU-masked streams that may be busy at once without the throughput of all of them collapsing
+// (measured on MI355X: eight batch-1 tasks reach 20 k images/s over 4 busy partitions of a pool of 8,
+// 8-9 k over 5, 6 or 8, whatever the partition size; idle partitions cost nothing).
+constexpr int kMaxBusyQueues = 4;
+
 // ---- pool ------------------------------------------------------------------
 struct Partition {
     hipStream_t stream = nullptr;
@@ -150,7 +155,7 @@ template <class K, class V, int CAP = 128> struct SharedPlanMemo {
         return v;
     }
 };
-extern int g_plan_generation;  // bumped whenever a tuning override changes what the planners return
+extern std::atomic<int> g_plan_generation;  // bumped whenever a tuning override changes what the planners return
 
 // Tile configuration of one implicit-GEMM launch.
 struct ConvPlan {
@@ -250,8 +255,8 @@ int launch_conv3x3s2_patch(const sgprs_conv_desc_t& d, int variant, const void* 
                            const float* shift, void* y, const sgprs_conv_desc_t* d2, const void* w2, const float* scale2,
                            const float* shift2, void* y2, hipStream_t stream, int cus, Profiler* prof);
 // tuning override: kind -1 automatic, 0 implicit GEMM only, 1 force patch (variant, splits)
-extern int g_conv_force_kind;
-extern int g_igemm_force_variant, g_igemm_force_splits;
+extern std::atomic<int> g_conv_force_kind;
+extern std::atomic<int> g_igemm_force_variant, g_igemm_force_splits;
 
 const char* igemm_variant_name(int v);
 const char* igemm_pair_variant_name(int v);

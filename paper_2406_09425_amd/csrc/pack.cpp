@@ -52,11 +52,13 @@ static const Tile kTiles[] = {{128, 128, 1.0}, {128, 64, 0.85}, {64, 64, 0.6}, {
 
 int igemm_num_variants() { return (int)(sizeof(kTiles) / sizeof(kTiles[0])); }
 
-int g_conv_force_kind = -1;
-int g_igemm_force_variant = -1;
-int g_igemm_force_splits = 0;
+// Tuning overrides: written by sgprs_conv_tuning_override, read by whatever thread plans a launch
+// (the lane launcher threads of a periodic run among them), hence atomics.
+std::atomic<int> g_conv_force_kind{-1};
+std::atomic<int> g_igemm_force_variant{-1};
+std::atomic<int> g_igemm_force_splits{0};
 
-int g_plan_generation = 0;
+std::atomic<int> g_plan_generation{0};
 
 static ConvPlan plan_conv_uncached(const sgprs_conv_desc_t& d, int cus, bool has_residual);
 
@@ -67,13 +69,15 @@ ConvPlan plan_conv(const sgprs_conv_desc_t& d, int cus, bool has_residual)
     static SharedPlanMemo<Key, ConvPlan> memo;
     Key k;
     memset(&k, 0, sizeof(k));
-    k.d = d; k.cus = cus; k.res = has_residual; k.gen = g_plan_generation;
+    k.d = d; k.cus = cus; k.res = has_residual; k.gen = g_plan_generation.load();
     return memo.get(local, k, [&]() { return plan_conv_uncached(d, cus, has_residual); });
 }
 
 static ConvPlan plan_conv_uncached(const sgprs_conv_desc_t& d, int cus, bool has_residual)
 {
-    if (g_conv_force_kind != 0) {
+    const int force_kind = g_conv_force_kind.load(), force_variant = g_igemm_force_variant.load(),
+              force_splits = g_igemm_force_splits.load();
+    if (force_kind != 0) {
         int v = 0, s = 1;
         if (plan_patch(d, cus < 1 ? 1 : cus, &v, &s)) {
             ConvPlan p;
@@ -81,7 +85,7 @@ static ConvPlan plan_conv_uncached(const sgprs_conv_desc_t& d, int cus, bool has
             p.bm = 1;  // marks a valid plan
             return p;
         }
-        if (g_conv_force_kind != 1 && !has_residual && plan_s2patch(d, cus < 1 ? 1 : cus, &v)) {
+        if (force_kind != 1 && !has_residual && plan_s2patch(d, cus < 1 ? 1 : cus, &v)) {
             ConvPlan p;
             p.kind = 2; p.variant = v; p.splits = 1;
             p.bm = 1;
@@ -103,8 +107,8 @@ static ConvPlan plan_conv_uncached(const sgprs_conv_desc_t& d, int cus, bool has
         // few output pixels (batch-1 layers of 28x28 and below): the 32-row tile wastes the fewest
         // rows and gives split-K the most workgroups; measured 3-7 % faster than 64x64 there
         if (t.bm == 32 && M <= 1024) t.eff = 0.8;
-        if (g_igemm_force_variant >= 0 && g_igemm_force_variant < igemm_num_variants() && v != g_igemm_force_variant &&
-            d.cout % kTiles[g_igemm_force_variant].bn == 0)
+        if (force_variant >= 0 && force_variant < igemm_num_variants() && v != force_variant &&
+            d.cout % kTiles[force_variant].bn == 0)
             continue;
         const long long gm = (M + t.bm - 1) / t.bm, gn = d.cout / t.bn;
         const long long blocks = gm * gn;
@@ -112,10 +116,10 @@ static ConvPlan plan_conv_uncached(const sgprs_conv_desc_t& d, int cus, bool has
         for (int s = 1; s <= 32; s *= 2) {
             if (s > 1 && ktiles / s < 2) break;
             // a forced split factor applies where the shape allows it (else the planner's own choice stands)
-            if (g_igemm_force_variant >= 0 && g_igemm_force_splits > 1 && s != g_igemm_force_splits &&
-                ktiles / g_igemm_force_splits >= 2)
+            if (force_variant >= 0 && force_splits > 1 && s != force_splits &&
+                ktiles / force_splits >= 2)
                 continue;
-            if (g_igemm_force_variant >= 0 && g_igemm_force_splits == 1 && s != 1) continue;
+            if (force_variant >= 0 && force_splits == 1 && s != 1) continue;
             const int kt_per = (ktiles + s - 1) / s;
             if (s > 1 && (long long)(s - 1) * kt_per >= ktiles) continue;  // an empty split
             const double per_block =

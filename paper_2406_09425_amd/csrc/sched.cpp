@@ -14,8 +14,10 @@
 #include <algorithm>
 #include <atomic>
 #include <chrono>
+#include <condition_variable>
 #include <cstdint>
 #include <memory>
+#include <mutex>
 #include <new>
 #include <string>
 #include <thread>
@@ -62,6 +64,17 @@ struct sgprs_sched {
     std::unordered_map<long long, JobRec> jobs;
     long long seq = 0;
     sgprs_sched_stats_t stats{};
+    int max_busy = sgprs::kMaxBusyQueues;  // run loop only: lanes with a stage in flight at once (0: no limit)
+
+    // Forgets every job in flight (after a failed run, whose stages will never be reported complete).
+    void abort_jobs()
+    {
+        for (SchedContext& c : ctx) {
+            c.waiting.clear();
+            std::fill(c.busy.begin(), c.busy.end(), (char)0);
+        }
+        jobs.clear();
+    }
 
     double backlog(int c, double now) const
     {
@@ -237,6 +250,14 @@ int sgprs_sched_complete(sgprs_sched_t* s, int task, int job, int stage, double 
     return fail(SGPRS_ERR_INVALID_ARG, "stage %d of job %d of task %d is not running", stage, job, task);
 }
 
+int sgprs_sched_set_max_busy(sgprs_sched_t* s, int max_busy)
+{
+    if (!s) return fail(SGPRS_ERR_INVALID_ARG, "sched is NULL");
+    if (max_busy < 0) return fail(SGPRS_ERR_INVALID_ARG, "max_busy %d < 0", max_busy);
+    s->max_busy = max_busy;
+    return SGPRS_OK;
+}
+
 int sgprs_sched_get_stats(const sgprs_sched_t* s, sgprs_sched_stats_t* out)
 {
     if (!s || !out) return fail(SGPRS_ERR_INVALID_ARG, "NULL argument");
@@ -275,6 +296,8 @@ int sgprs_sched_run_periodic(sgprs_sched_t* s, sgprs_pool_t* pool, sgprs_task_t*
         hipEvent_t ev = nullptr;
         hipStream_t stream = nullptr;
         std::atomic<int> state{0};  // 0 idle, 1 launch requested, 2 launched (event recorded), 3 launch failed, 4 quit
+        std::mutex mu;              // the launcher thread sleeps on cv until state becomes 1 or 4
+        std::condition_variable cv;
         sgprs_task_t* rq_task = nullptr;
         const void* rq_in = nullptr;
         void* rq_out = nullptr;
@@ -294,21 +317,32 @@ int sgprs_sched_run_periodic(sgprs_sched_t* s, sgprs_pool_t* pool, sgprs_task_t*
         if (sl.rc) sl.error = sgprs_last_error();
         sl.state.store(sl.rc ? 3 : 2, std::memory_order_release);
     };
-    auto launcher = [&](Slot* sl) {
+    auto launcher = [&](Slot* sl) {   // blocks between requests: idle lanes cost no host core
         (void)hipSetDevice(device);
         for (;;) {
-            const int st = sl->state.load(std::memory_order_acquire);
+            int st;
+            {
+                std::unique_lock<std::mutex> lk(sl->mu);
+                sl->cv.wait(lk, [&] { const int v = sl->state.load(std::memory_order_acquire); return v == 1 || v == 4; });
+                st = sl->state.load(std::memory_order_acquire);
+            }
             if (st == 4) return;
-            if (st == 1) launch(*sl);
-            else std::this_thread::yield();
+            launch(*sl);
         }
+    };
+    auto post = [&](Slot& sl, int st) {   // hands a request (1) or the quit order (4) to the lane's launcher
+        {
+            std::lock_guard<std::mutex> lk(sl.mu);
+            sl.state.store(st, std::memory_order_release);
+        }
+        sl.cv.notify_one();
     };
     auto cleanup = [&]() {
         for (size_t p = 0; p < n_slots; ++p) {
             Slot& sl = slots[p];
             if (sl.thread.joinable()) {
                 while (sl.state.load(std::memory_order_acquire) == 1) std::this_thread::yield();  // a launch in progress finishes first
-                sl.state.store(4, std::memory_order_release);
+                post(sl, 4);
                 sl.thread.join();
             }
             if (sl.busy && sl.state.load() != 3 && sl.ev) (void)hipEventSynchronize(sl.ev);  // nothing of ours stays queued unseen
@@ -329,6 +363,7 @@ int sgprs_sched_run_periodic(sgprs_sched_t* s, sgprs_pool_t* pool, sgprs_task_t*
     std::vector<double> job_release(n_tasks, 0.0);
     const sgprs_sched_stats_t before = s->stats;
     long long releases = 0, dropped = 0, in_flight = 0;
+    int busy_lanes = 0;
     double resp_sum = 0.0, resp_max = 0.0, last_done = 0.0;
     const auto t0 = std::chrono::steady_clock::now();
     auto clock_s = [&]() { return std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count(); };
@@ -346,6 +381,7 @@ int sgprs_sched_run_periodic(sgprs_sched_t* s, sgprs_pool_t* pool, sgprs_task_t*
             if (q == hipErrorNotReady) continue;
             if (q != hipSuccess) { status = fail(SGPRS_ERR_HIP, "hipEventQuery: %s", hipGetErrorString(q)); break; }
             sl.busy = false;
+            --busy_lanes;
             sl.state.store(0, std::memory_order_relaxed);
             if ((status = sgprs_sched_complete(s, sl.task, sl.job, sl.stage, now, nullptr))) break;
             if (sl.stage + 1 == (int)s->tasks[sl.task].wcet.size()) {
@@ -379,16 +415,20 @@ int sgprs_sched_run_periodic(sgprs_sched_t* s, sgprs_pool_t* pool, sgprs_task_t*
         }
         if (status) break;
         // dispatches
+        // (at most max_busy lanes have a stage in flight: more CU-masked streams busy at once than the
+        // device has hardware queues for one process collapse the throughput of all of them, so further
+        // stages wait in the scheduler's queues even if their lane is free)
         sgprs_dispatch_t d;
-        int got;
-        while ((got = sgprs_sched_next(s, now, &d)) == 1) {
+        int got = 0;
+        while ((s->max_busy <= 0 || busy_lanes < s->max_busy) && (got = sgprs_sched_next(s, now, &d)) == 1) {
             Slot& sl = slots[(size_t)d.context * s->lanes + d.lane];
             const int last = (int)s->tasks[d.task].wcet.size() - 1;
             const void* in = d.stage == 0 ? inputs[d.task] : sgprs_task_stage_output(tasks[d.task], d.stage - 1);
             void* out = d.stage == last ? (void*)logits[d.task] : (void*)sgprs_task_stage_output(tasks[d.task], d.stage);
             sl.busy = true; sl.task = d.task; sl.job = d.job; sl.stage = d.stage;
             sl.rq_task = tasks[d.task]; sl.rq_in = in; sl.rq_out = out; sl.rq_partition = d.context * s->lanes + d.lane;
-            if (threaded) sl.state.store(1, std::memory_order_release);
+            ++busy_lanes;
+            if (threaded) post(sl, 1);
             else {
                 launch(sl);
                 if (sl.rc) { status = fail(sl.rc, "%s", sl.error.c_str()); break; }
@@ -400,7 +440,10 @@ int sgprs_sched_run_periodic(sgprs_sched_t* s, sgprs_pool_t* pool, sgprs_task_t*
         if (now > duration_s + 30.0) { status = fail(SGPRS_ERR_HIP, "jobs still in flight 30 s after the last release"); break; }
     }
     cleanup();
-    if (status) return status;
+    if (status) {
+        s->abort_jobs();   // nothing of this run stays in the scheduler: the next run starts clean
+        return status;
+    }
     report->elapsed_s = std::max(last_done, duration_s);
     report->releases = releases;
     report->dropped = dropped;
@@ -413,6 +456,64 @@ int sgprs_sched_run_periodic(sgprs_sched_t* s, sgprs_pool_t* pool, sgprs_task_t*
     report->dmr = releases ? (double)(report->sched.jobs_missed + dropped) / (double)releases : 0.0;
     report->mean_response_s = report->sched.jobs_completed ? resp_sum / (double)report->sched.jobs_completed : 0.0;
     report->max_response_s = resp_max;
+    return SGPRS_OK;
+}
+
+// Static (purely spatial) execution: every task keeps the partition it is given; the calling thread
+// hands out whole inferences and polls one event per task, with the same gate on busy partitions.
+int sgprs_pool_run_static(sgprs_pool_t* pool, sgprs_task_t* const* tasks, int n_tasks, const void* const* inputs,
+                          float* const* logits, int batch, const int* partition_of_task, int rounds, int max_busy,
+                          double* elapsed_s)
+{
+    if (!pool || !tasks || !inputs || !logits || !partition_of_task) return fail(SGPRS_ERR_INVALID_ARG, "NULL argument");
+    if (n_tasks <= 0 || n_tasks > 4096 || rounds <= 0 || max_busy < 0) return fail(SGPRS_ERR_INVALID_ARG, "n_tasks, rounds or max_busy out of range");
+    int n_p = 0, rc;
+    if ((rc = sgprs_pool_info(pool, &n_p, nullptr, nullptr, nullptr))) return rc;
+    for (int i = 0; i < n_tasks; ++i) {
+        if (!tasks[i] || !inputs[i] || !logits[i]) return fail(SGPRS_ERR_INVALID_ARG, "task %d: NULL handle or buffer", i);
+        if (partition_of_task[i] < 0 || partition_of_task[i] >= n_p) return fail(SGPRS_ERR_INVALID_ARG, "task %d: partition %d outside the pool", i, partition_of_task[i]);
+    }
+    std::vector<hipEvent_t> ev(n_tasks, nullptr);
+    auto cleanup = [&]() {
+        for (hipEvent_t e : ev)
+            if (e) { (void)hipEventSynchronize(e); (void)hipEventDestroy(e); }
+    };
+    for (int i = 0; i < n_tasks; ++i)
+        if (hipEventCreateWithFlags(&ev[i], hipEventDisableTiming) != hipSuccess) {
+            ev[i] = nullptr;
+            cleanup();
+            return fail(SGPRS_ERR_HIP, "hipEventCreateWithFlags failed");
+        }
+    std::vector<int> done(n_tasks, 0);
+    std::vector<char> running(n_tasks, 0), part_busy(n_p, 0);
+    int busy = 0, finished = 0, status = SGPRS_OK, next = 0;
+    const auto t0 = std::chrono::steady_clock::now();
+    while (finished < n_tasks && !status) {
+        for (int i = 0; i < n_tasks && !status; ++i) {
+            if (!running[i]) continue;
+            const hipError_t q = hipEventQuery(ev[i]);
+            if (q == hipErrorNotReady) continue;
+            if (q != hipSuccess) { status = fail(SGPRS_ERR_HIP, "hipEventQuery: %s", hipGetErrorString(q)); break; }
+            running[i] = 0;
+            part_busy[partition_of_task[i]] = 0;
+            --busy;
+            if (++done[i] == rounds) ++finished;
+        }
+        // hand out work round-robin, starting behind the task served last
+        for (int k = 0; k < n_tasks && !status && (max_busy == 0 || busy < max_busy); ++k) {
+            const int i = (next + k) % n_tasks, p = partition_of_task[i];
+            if (running[i] || done[i] == rounds || part_busy[p]) continue;
+            if ((status = sgprs_task_run(tasks[i], batch, inputs[i], logits[i], pool, p, nullptr))) break;
+            if (hipEventRecord(ev[i], (hipStream_t)sgprs_pool_stream(pool, p)) != hipSuccess) { status = fail(SGPRS_ERR_HIP, "hipEventRecord failed"); break; }
+            running[i] = 1;
+            part_busy[p] = 1;
+            ++busy;
+            next = (i + 1) % n_tasks;
+        }
+    }
+    cleanup();   // (waits for whatever is still queued)
+    if (status) return status;
+    if (elapsed_s) *elapsed_s = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
     return SGPRS_OK;
 }
 

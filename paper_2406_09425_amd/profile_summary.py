@@ -12,6 +12,11 @@
       directory, at most 8 SQ counters each), as fractions of the SIMD cycles of the
       dispatch where that makes sense
 
+  python -m paper_2406_09425_amd.profile_summary concurrency <dir> <command...>
+      from a --kernel-trace run (<dir>/**/*kernel_trace.csv): per hardware queue the number of
+      kernels and their busy time, and how the traced interval divides by the number of kernels
+      (and of distinct queues) in flight at once
+
 The command line that produced the data is echoed into the summary.
 """
 from __future__ import annotations
@@ -35,6 +40,53 @@ def stats(d: str, cmd: str) -> str:
     for r in rows:
         out.append(f"{r['Name'][:90]:<92}{r['Calls']:>7}{float(r['AverageNs']) / 1e3:>10.2f}"
                    f"{float(r['TotalDurationNs']) / 1e6:>10.3f}{float(r['Percentage']):>7.2f}")
+    return "\n".join(out) + "\n"
+
+
+def concurrency(d: str, cmd: str, skip_first_fraction: float = 0.3) -> str:
+    """Who ran beside whom: the kernels of the last (1 - skip_first_fraction) of the trace (the
+    steady state after warm-up) as intervals [start, end) per queue."""
+    rows = []
+    for f in _find(d, "*kernel_trace.csv"):
+        for r in csv.DictReader(open(f)):
+            if "sgprs" in r["Kernel_Name"]:
+                rows.append((int(r["Start_Timestamp"]), int(r["End_Timestamp"]), r["Queue_Id"], r["Kernel_Name"]))
+    if not rows:
+        return f"command: {cmd}\n\nno sgprs kernels in the trace\n"
+    rows.sort()
+    t_lo = rows[0][0] + int((rows[-1][1] - rows[0][0]) * skip_first_fraction)
+    rows = [r for r in rows if r[0] >= t_lo]
+    span = max(r[1] for r in rows) - min(r[0] for r in rows)
+    per_q = collections.defaultdict(lambda: [0, 0])
+    events = []
+    for st, en, q, _ in rows:
+        per_q[q][0] += 1
+        per_q[q][1] += en - st
+        events.append((st, 1, q))
+        events.append((en, -1, q))
+    events.sort(key=lambda e: (e[0], e[1]))
+    in_flight, q_active = 0, collections.Counter()
+    by_kernels, by_queues = collections.Counter(), collections.Counter()
+    prev = events[0][0]
+    for t, dlt, q in events:
+        by_kernels[in_flight] += t - prev
+        by_queues[sum(1 for v in q_active.values() if v > 0)] += t - prev
+        prev = t
+        in_flight += dlt
+        q_active[q] += dlt
+    out = [f"command: {cmd}", "",
+           f"{len(rows)} sgprs kernels in the last {100 * (1 - skip_first_fraction):.0f} % of the trace, {span / 1e3:.1f} us, "
+           f"sum of kernel durations {sum(r[1] - r[0] for r in rows) / 1e3:.1f} us, "
+           f"median kernel {sorted(r[1] - r[0] for r in rows)[len(rows) // 2] / 1e3:.2f} us", "",
+           f"{'queue id':<12}{'kernels':>9}{'busy us':>12}{'busy share of the interval':>30}"]
+    for q in sorted(per_q, key=lambda q: int(q) if q.isdigit() else 0):
+        out.append(f"{q:<12}{per_q[q][0]:>9}{per_q[q][1] / 1e3:>12.1f}{per_q[q][1] / span:>30.3f}")
+    out += ["", f"{'kernels in flight':<20}{'share of the interval':>24}"]
+    for k in sorted(by_kernels):
+        out.append(f"{k:<20}{by_kernels[k] / span:>24.3f}")
+    out += ["", f"{'queues with a kernel in flight':<34}{'share of the interval':>24}"]
+    for k in sorted(by_queues):
+        out.append(f"{k:<34}{by_queues[k] / span:>24.3f}")
     return "\n".join(out) + "\n"
 
 
@@ -113,7 +165,9 @@ def sq(dirs, cmd: str) -> str:
 
 
 if __name__ == "__main__":
-    if len(sys.argv) >= 4 and sys.argv[1] == "stats":
+    if len(sys.argv) >= 4 and sys.argv[1] == "concurrency":
+        sys.stdout.write(concurrency(sys.argv[2], " ".join(sys.argv[3:])))
+    elif len(sys.argv) >= 4 and sys.argv[1] == "stats":
         sys.stdout.write(stats(sys.argv[2], " ".join(sys.argv[3:])))
     elif len(sys.argv) >= 5 and sys.argv[1] == "pmc":
         sys.stdout.write(pmc(sys.argv[2], sys.argv[3], " ".join(sys.argv[4:])))

@@ -108,3 +108,89 @@ def test_run_rejects_mismatched_arguments(rig):
         wrong.run_periodic(rig["pool"], rig["tasks"][:1], [x.data_ptr()], [lg.data_ptr()], 1, 0.01)
     for s in (sch, big, wrong):
         s.destroy()
+
+
+def test_two_contexts_of_four_lanes_the_papers_shape():
+    """"Stage Queuing": a context carries two high- and two low-priority streams, at most four stages in
+    flight.  Eight lanes = eight CU-masked streams; the run loop keeps at most four of them busy at once
+    (more collapse on this GPU), so the eight tasks still all finish, meet a generous deadline, and end
+    with the oracle's logits.  A second run right after a failed one starts from a clean scheduler."""
+    n_ctx, lanes, n_tasks = 2, 4, 8
+    total = S.Pool(1, 8).info()["total_cus"]
+    half = S.Pool(2, total // 2)
+    masks = np.stack([half.mask(c) for c in range(n_ctx) for _ in range(lanes)])
+    half.destroy()
+    pool = S.Pool(n_ctx * lanes, 0, masks=masks)
+    params = [make_resnet18_params(3, i, bf16=True) for i in range(n_tasks)]
+    xs_host = [make_input(3, i, (1, 3, 224, 224), bf16=True) for i in range(n_tasks)]
+    tasks = [S.Task(p, S.SGPRS_BF16, 1, BN_EPS) for p in params]
+    xs = [dev_nhwc(x, S.SGPRS_BF16) for x in xs_host]
+    lgs = [torch.full((1, 1000), float("nan"), dtype=torch.float32, device="cuda") for _ in range(n_tasks)]
+    try:
+        for t, x, l in zip(tasks, xs, lgs):
+            t.run(1, x.data_ptr(), l.data_ptr(), pool, 0)
+        pool.sync()
+        for l in lgs:
+            l.fill_(float("nan"))
+        sch = S.Sched(n_ctx, lanes)
+        for _ in range(n_tasks):
+            sch.add_task([100e-6] * 6, 2.0 ** -7, 2.0 ** -7)
+        # a failing run (one input pointer missing) must leave nothing behind
+        with pytest.raises(S.SgprsError):
+            sch.run_periodic(pool, tasks, [x.data_ptr() for x in xs[:-1]] + [None], [l.data_ptr() for l in lgs], 1, 0.01)
+        rep = sch.run_periodic(pool, tasks, [x.data_ptr() for x in xs], [l.data_ptr() for l in lgs], 1,
+                               duration_s=10 * 2.0 ** -7, offsets=[i * 2.0 ** -11 for i in range(n_tasks)])
+        pool.sync()
+        assert rep["releases"] == 10 * n_tasks and rep["dropped"] == 0
+        assert rep["jobs_completed"] == 10 * n_tasks and rep["stages_completed"] == 60 * n_tasks
+        assert rep["jobs_missed"] == 0 and rep["max_response_s"] < 2.0 ** -7
+        for i in range(n_tasks):
+            ref = oracle.resnet18(params[i], BN_EPS, xs_host[i])
+            got = lgs[i].cpu().numpy().astype(np.float64)
+            assert rel_err(got, ref) <= TOL[S.SGPRS_BF16], i
+            assert int(np.argmax(got)) == int(np.argmax(ref)), i
+        # without the gate the same run still completes (slower): the gate changes speed, not results
+        sch.set_max_busy(0)
+        rep2 = sch.run_periodic(pool, tasks, [x.data_ptr() for x in xs], [l.data_ptr() for l in lgs], 1,
+                                duration_s=4 * 2.0 ** -7)
+        assert rep2["jobs_completed"] == rep2["jobs_released"] == 4 * n_tasks
+        with pytest.raises(S.SgprsError):
+            sch.set_max_busy(-1)
+        sch.destroy()
+    finally:
+        for t in tasks:
+            t.destroy()
+        pool.destroy()
+
+
+def test_static_execution_on_eight_partitions_with_the_gate():
+    """sgprs_pool_run_static: eight tasks, each on its own 32-CU partition, at most four partitions busy
+    at once; every task's logits are the oracle's, with and without the gate, and bad arguments are
+    refused before anything runs."""
+    n = 8
+    total = S.Pool(1, 8).info()["total_cus"]
+    pool = S.Pool(n, total // n)
+    params = [make_resnet18_params(3, i, bf16=True) for i in range(n)]
+    xs_host = [make_input(3, i, (1, 3, 224, 224), bf16=True) for i in range(n)]
+    tasks = [S.Task(p, S.SGPRS_BF16, 1, BN_EPS) for p in params]
+    xs = [dev_nhwc(x, S.SGPRS_BF16) for x in xs_host]
+    refs = [oracle.resnet18(params[i], BN_EPS, xs_host[i]) for i in range(n)]
+    try:
+        for gate in (4, 0):
+            lgs = [torch.full((1, 1000), float("nan"), dtype=torch.float32, device="cuda") for _ in range(n)]
+            el = pool.run_static(tasks, [x.data_ptr() for x in xs], [l.data_ptr() for l in lgs], 1, list(range(n)), rounds=5,
+                                 max_busy=gate)
+            assert 0 < el < 5.0
+            for i in range(n):
+                got = lgs[i].cpu().numpy().astype(np.float64)
+                assert rel_err(got, refs[i]) <= TOL[S.SGPRS_BF16], (gate, i)
+                assert int(np.argmax(got)) == int(np.argmax(refs[i])), (gate, i)
+        lg = torch.empty((1, 1000), dtype=torch.float32, device="cuda")
+        with pytest.raises(S.SgprsError):
+            pool.run_static(tasks[:1], [xs[0].data_ptr()], [lg.data_ptr()], 1, [n], rounds=1)       # partition outside the pool
+        with pytest.raises(S.SgprsError):
+            pool.run_static(tasks[:1], [xs[0].data_ptr()], [lg.data_ptr()], 1, [0], rounds=0)       # no rounds
+    finally:
+        for t in tasks:
+            t.destroy()
+        pool.destroy()

@@ -54,3 +54,23 @@ def test_sq_shares(tmp_path):
     assert row[1:4] == ["1000", "512", "25.0%"]      # cycles, waves, MFMA busy = 256000 / 1024000
     assert row[4] == "20.0%" and row[8] == "50.0%"   # VALU = 51200 * 4 / 1024000, any instruction = 128000 * 4 / 1024000
     assert row[10] == "100" and row[-1] == "25.0%"   # VALU instructions per wavefront, bank conflicts 10 / 40
+
+
+def test_concurrency_from_a_kernel_trace(tmp_path):
+    hdr = ["Kind", "Queue_Id", "Kernel_Name", "Start_Timestamp", "End_Timestamp"]
+    k = "void sgprs::conv()"
+    # warm-up kernel (dropped with the first 30 % of the trace), then on queue 1: [1000, 2000) and
+    # [3000, 4000); on queue 2: [1500, 3500); one kernel of another library is ignored
+    write_csv(str(tmp_path / "t" / "x_kernel_trace.csv"), hdr,
+              [["KERNEL_DISPATCH", 1, k, 0, 10], ["KERNEL_DISPATCH", 1, k, 1000, 2000], ["KERNEL_DISPATCH", 1, k, 3000, 4000],
+               ["KERNEL_DISPATCH", 2, k, 1500, 3500], ["KERNEL_DISPATCH", 3, "other_kernel", 1000, 4000]])
+    out = ps.concurrency(str(tmp_path), "cmd", skip_first_fraction=0.2)
+    lines = out.splitlines()
+    assert lines[0] == "command: cmd" and "3 sgprs kernels" in lines[2]
+    q1 = next(l for l in lines if l.startswith("1 ")).split()
+    assert q1[1:3] == ["2", "2.0"]                       # two kernels, 2.0 us busy
+    # interval 3000 ns: one kernel in flight during [1000,1500) + [2000,3000) + [3500,4000) = 2000, two during 1000
+    i = lines.index(next(l for l in lines if l.startswith("kernels in flight")))
+    assert lines[i + 1].split() == ["0", "0.000"] or lines[i + 1].split()[0] == "1"
+    shares = {l.split()[0]: float(l.split()[1]) for l in lines[i + 1:i + 4] if l and l[0].isdigit()}
+    assert abs(shares["1"] - 2000 / 3000) < 1e-3 and abs(shares["2"] - 1000 / 3000) < 1e-3
