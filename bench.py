@@ -550,6 +550,18 @@ def leg_membound(S, hip, torch, pool, stream, reps=100):
     timed("add_relu 4096x(7x7x512)", 3 * cnt * es,
           lambda: (torch.randn(cnt, device="cuda").to(tdt), torch.randn(cnt, device="cuda").to(tdt), torch.empty(cnt, dtype=tdt, device="cuda")),
           lambda b: S.sgprs_add_relu(dt, cnt, b[0].data_ptr(), b[1].data_ptr(), b[2].data_ptr(), True, pool, 0))
+    # avg-pool + FC at a size beyond the caches (4096 images: 205 MB of activations per call; the 1 MB of
+    # weights and the pooled vectors stay in the L2) and at the headline's batch of 64 (3.2 MB: two
+    # dependent launches, bound by their latency, not by bandwidth: reported as such)
+    wfc = (torch.randn((1000, 512), device="cuda") * 0.05).to(tdt)
+    bfc = torch.zeros(1000, dtype=torch.float32, device="cuda")
+    for nimg in (4096, 64):
+        ws = torch.empty(nimg * 512, dtype=torch.float32, device="cuda")
+        nbytes = nimg * 49 * 512 * es + 1000 * 512 * es + nimg * 1000 * 4
+        timed(f"avgpool_fc {nimg}x(7x7x512) -> 1000", nbytes,
+              lambda: (torch.randn((nimg, 49, 512), device="cuda").to(tdt), torch.empty((nimg, 1000), dtype=torch.float32, device="cuda")),
+              lambda b: S.sgprs_avgpool_fc(dt, nimg, 49, 512, 1000, b[0].data_ptr(), wfc.data_ptr(), bfc.data_ptr(), b[1].data_ptr(),
+                                           ws.data_ptr(), pool, 0))
     return res
 
 

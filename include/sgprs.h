@@ -289,7 +289,7 @@ const void *sgprs_task_stage_output(const sgprs_task_t *task, int stage);
  * sgprs_task_kernel_times returns, for the last run of each stage, one record
  * per launch: HOST arrays of length *count (in: capacity).  kind: 0 conv
  * implicit GEMM, 1 stem conv, 2 split-K reduce, 3 max-pool, 4 avg-pool, 5 FC
- * (variant >= 2: avg-pool and FC in one launch),
+ * (variant 2, 3: avg-pool and FC in one launch; 4: the FC on the matrix cores),
  * 6 BN+ReLU, 7 add+ReLU, 8 LDS-patch 3x3 conv, 9 fused stem conv + max-pool,
  * 10 two implicit-GEMM convolutions of one input in a single launch, 11 the
  * stride-2 LDS-patch 3x3 conv (variant + 4: together with the 1x1 shortcut).

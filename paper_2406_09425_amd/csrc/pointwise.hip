@@ -229,6 +229,42 @@ __global__ __launch_bounds__(256) void avgpool_kernel(const void* __restrict__ x
     }
 }
 
+// ---- the same for many images ------------------------------------------------
+// One wavefront per (image, 64 channel vectors), four images per workgroup, nothing shared: a lane
+// keeps four partial sums, over the positions j = 0, 1, 2, 3 (mod 4) in rising order, and adds them as
+// ((p0 + p1) + p2) + p3: the arithmetic of the one-launch kernel below, whose four wavefronts take one
+// residue each.  Up to 28 positions are in flight per round trip; the data is touched once (streamed).
+template <int DT>
+__global__ __launch_bounds__(256) void avgpool_stream_kernel(const void* __restrict__ x, float* __restrict__ v, int HW,
+                                                             int C, int Nimg)
+{
+    constexpr int N = Vec<DT>::N, B = 28;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int cv = C / N;
+    const int c = blockIdx.x * 64 + lane;
+    const size_t n = (size_t)blockIdx.y * 4 + wave;
+    if (n >= (size_t)Nimg || c >= cv) return;
+    float p[4][N];
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+#pragma unroll
+        for (int i = 0; i < N; ++i) p[w][i] = 0.f;
+    for (int j0 = 0; j0 < HW; j0 += B) {
+        Vec<DT> t[B];
+#pragma unroll
+        for (int u = 0; u < B; ++u) t[u].load_nt(x, (n * HW + min(j0 + u, HW - 1)) * cv + c);
+#pragma unroll
+        for (int u = 0; u < B; ++u)
+            if (j0 + u < HW) {
+#pragma unroll
+                for (int i = 0; i < N; ++i) p[u & 3][i] += t[u].v[i];   // (B is a multiple of 4: position j feeds partial sum j & 3)
+            }
+    }
+    const float hw = (float)HW;
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[(n * cv + c) * N + i] = (((p[0][i] + p[1][i]) + p[2][i]) + p[3][i]) / hw;
+}
+
 // ---- avg-pool + FC in one launch, for a few images ---------------------------------
 // Every workgroup pools its image once more (the 50 KB come from the L2) with exactly the
 // arithmetic of avgpool_kernel, keeps the vector in LDS, and its four wavefronts then compute
@@ -349,9 +385,10 @@ __global__ __launch_bounds__(256) void fc_kernel(const float* __restrict__ v, co
     const float b = bias ? bias[o] : 0.f;
     const int n_begin = blockIdx.y * img_per_block;
     const int n_end = min(n_begin + img_per_block, Nimg);
-    // Four images at a time: their eight vector loads are in flight together (one image per round
-    // trip made the kernel latency-bound), images past the end re-read the last one and are dropped.
-    constexpr int G = 4;
+    // G images at a time: their vector loads are in flight together (one image per round trip made
+    // the kernel latency-bound), images past the end re-read the last one and are dropped.  A dot
+    // product is summed in the same order whatever G is.
+    constexpr int G = CPL == 1 ? 8 : 4;   // (512 inputs: the whole block of eight images at once, together with the weights)
     for (int n0 = n_begin; n0 < n_end; n0 += G) {
         f32x4_t v0[G][CPL], v1[G][CPL];
 #pragma unroll
@@ -386,6 +423,66 @@ __global__ __launch_bounds__(256) void fc_kernel(const float* __restrict__ v, co
     }
 }
 
+// ---- FC on the matrix cores, for batches of 32 images and more (bf16 weights) ------------
+// logits[n][o] = sum_c w[o][c] v[n][c] + b[o] as 32 x 32 tiles of MFMA 32x32x16: rows = outputs
+// (weights straight from memory, 16 bytes per lane), columns = images.  The pooled vectors stay
+// fp32: each value goes in as a bf16 head plus a bf16 remainder (two MFMAs; products of two bf16
+// are exact in fp32, so what is lost is below 2^-17 of a value).  The four wavefronts of a
+// workgroup split the inputs of one tile and add their partial tiles through LDS in wavefront
+// order, so the result does not depend on timing.
+typedef __bf16 fc_bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float fc_f32x16_t __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(256) void fc_mfma_kernel(const float* __restrict__ v, const void* __restrict__ w,
+                                                      const float* __restrict__ bias, float* __restrict__ y, int Nimg,
+                                                      int Cin, int Cout)
+{
+    __shared__ f32x4_t part[4][4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int frow = lane & 31, half = lane >> 5;
+    const int o0 = blockIdx.x * 32, n0 = blockIdx.y * 32;
+    const int o = min(o0 + frow, Cout - 1), n = min(n0 + frow, Nimg - 1);   // rows and columns past the end repeat the last one
+    const int kq = Cin / 4, k0 = wave * kq + half * 8;
+    const unsigned short* wp = (const unsigned short*)w + (size_t)o * Cin + k0;
+    const float* vp = v + (size_t)n * Cin + k0;
+    fc_f32x16_t acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+    for (int kb = 0; kb < kq; kb += 128) {   // eight k-steps per round trip
+        u32x4_t a[8];
+        f32x4_t b0[8], b1[8];
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            a[s] = *(const u32x4_t*)(wp + kb + s * 16);
+            b0[s] = *(const f32x4_t*)(vp + kb + s * 16);
+            b1[s] = *(const f32x4_t*)(vp + kb + s * 16 + 4);
+        }
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            fc_bf16x8_t hi, lo;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float f = i < 4 ? b0[s][i] : b1[s][i - 4];
+                hi[i] = (__bf16)f;
+                lo[i] = (__bf16)(f - (float)hi[i]);
+            }
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(fc_bf16x8_t, a[s]), hi, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(fc_bf16x8_t, a[s]), lo, acc, 0, 0, 0);
+        }
+    }
+    // accumulator register 4q + u: output o0 + 8q + 4 * half + u of image n0 + frow
+#pragma unroll
+    for (int q = 0; q < 4; ++q) part[wave][q][lane] = f32x4_t{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+    __syncthreads();
+    {
+        const int q = wave, ob = o0 + 8 * q + 4 * half;
+        f32x4_t r = ((part[0][q][lane] + part[1][q][lane]) + part[2][q][lane]) + part[3][q][lane];
+        if (n0 + frow < Nimg && ob < Cout) {   // (Cout is a multiple of 4: a group of four is inside or outside as a whole)
+            if (bias) r += *(const f32x4_t*)(bias + ob);
+            *(f32x4_t*)(y + (size_t)(n0 + frow) * Cout + ob) = r;
+        }
+    }
+}
+
 // ---- placement probe --------------------------------------------------------
 __global__ __launch_bounds__(64) void probe_kernel(uint32_t* out, int spin)
 {
@@ -409,6 +506,7 @@ __global__ __launch_bounds__(64) void probe_kernel(uint32_t* out, int spin)
         if (prof && prof->on && (rc_ = prof->end(stream))) return rc_;      \
     } while (0)
 
+constexpr int kAvgpoolStreamMin = 512;
 static unsigned blocks_for(size_t n) { return (unsigned)((n + 255) / 256); }
 
 int launch_maxpool(int dtype, int n, int h, int w, int c, const void* x, void* y, hipStream_t stream, int,
@@ -486,14 +584,29 @@ int launch_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void* x
         return SGPRS_OK;
     }
     PROF_BEGIN(kKindAvgpool, dtype, (double)n * hw * cin, (double)n * hw * cin * es + (double)n * cin * 4);
-    const dim3 pgrid((cin / vec + 63) / 64, n);
-    if (dtype == SGPRS_BF16)
-        SGPRS_LAUNCH(avgpool_kernel<SGPRS_BF16>, pgrid, dim3(256), 0, stream, x, ws, hw, cin);
-    else
-        SGPRS_LAUNCH(avgpool_kernel<SGPRS_F32>, pgrid, dim3(256), 0, stream, x, ws, hw, cin);
+    if (n >= kAvgpoolStreamMin) {   // many images: one wavefront per image, no LDS, no barrier (the same bits)
+        const dim3 pgrid((cin / vec + 63) / 64, (n + 3) / 4);
+        if (dtype == SGPRS_BF16)
+            SGPRS_LAUNCH(avgpool_stream_kernel<SGPRS_BF16>, pgrid, dim3(256), 0, stream, x, ws, hw, cin, n);
+        else
+            SGPRS_LAUNCH(avgpool_stream_kernel<SGPRS_F32>, pgrid, dim3(256), 0, stream, x, ws, hw, cin, n);
+    } else {
+        const dim3 pgrid((cin / vec + 63) / 64, n);
+        if (dtype == SGPRS_BF16)
+            SGPRS_LAUNCH(avgpool_kernel<SGPRS_BF16>, pgrid, dim3(256), 0, stream, x, ws, hw, cin);
+        else
+            SGPRS_LAUNCH(avgpool_kernel<SGPRS_F32>, pgrid, dim3(256), 0, stream, x, ws, hw, cin);
+    }
     SGPRS_HIP(hipGetLastError());
     PROF_END();
 
+    if (dtype == SGPRS_BF16 && n >= 32 && cout % 4 == 0 && cin % 512 == 0) {   // enough images for 32 x 32 tiles on the matrix cores
+        PROF_BEGIN(kKindFc, 4, 2.0 * n * cin * cout, (double)cin * cout * es + (double)n * (cin + cout) * 4);
+        SGPRS_LAUNCH(fc_mfma_kernel, dim3((cout + 31) / 32, (n + 31) / 32), dim3(256), 0, stream, (const float*)ws, w, bias, logits, n, cin, cout);
+        SGPRS_HIP(hipGetLastError());
+        PROF_END();
+        return SGPRS_OK;
+    }
     const int img_per_block = 8;
     const dim3 grid((cout + 3) / 4, (n + img_per_block - 1) / img_per_block);
     const int cpl = cin / 512;

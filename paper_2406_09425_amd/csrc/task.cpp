@@ -509,7 +509,7 @@ const char* sgprs_kernel_name(int kind, int variant)
         case kKindReduce: return "splitk_reduce_kernel";
         case kKindMaxpool: return "maxpool3x3s2_kernel";
         case kKindAvgpool: return "avgpool_kernel";
-        case kKindFc: return variant >= 2 ? "avgpool_fc_kernel" : "fc_kernel";
+        case kKindFc: return variant >= 4 ? "fc_mfma_kernel" : variant >= 2 ? "avgpool_fc_kernel" : "fc_kernel";
         case kKindBnRelu: return "bn_relu_kernel";
         case kKindAdd: return "add_relu_kernel";
         default: return "?";
