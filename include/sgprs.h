@@ -197,7 +197,8 @@ int sgprs_conv2d(const sgprs_conv_desc_t *d, const void *x, const void *w_packed
  * wherever it divides cout, with split-K factor `splits` (0: planner's choice);
  * 3: automatic, plus the stride-2 LDS-patch kernel (not chosen otherwise) with
  * tile variant `variant` (0: 256 rows, 1: 128 rows) wherever the shape allows
- * it; variant 2 switches it off again. */
+ * it; variant 2 switches it off again; 4: automatic, but stage 0 of a bf16
+ * task uses the 4-slot stem+pool kernel instead of the packed-row one. */
 int sgprs_conv_tuning_override(int kind, int variant, int splits);
 /* Max pooling 3x3, stride 2, pad 1 (padding never wins): [n][h][w][c] ->
  * [n][(h-1)/2+1][(w-1)/2+1][c].  c % 8 == 0 (bf16) or c % 4 == 0 (fp32). */

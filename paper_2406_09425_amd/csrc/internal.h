@@ -234,8 +234,13 @@ int launch_mfma_probe(int cus, int steps, int random_data, unsigned long long* o
 int launch_load_probe(int cus, const void* buf, size_t buf_bytes, unsigned region, int iters, unsigned* out, hipStream_t stream);
 // stage 0 fused: conv7x7/2 + BN + ReLU + max-pool 3x3/2
 bool stem_pool_applicable(int dtype, int n, int h, int w, int cus);
-int launch_stem_pool(int dtype, int n, int h, int w, const void* x, const void* wts, const float* scale,
-                     const float* shift, void* y, hipStream_t stream, int cus, Profiler* prof);
+// wts: the stem layout of sgprs_pack_conv_weights; wts_rows: the bf16 [64][176] tap-row layout of
+// pack_stem_rows (may be NULL: then the kernel that reads wts runs)
+constexpr int kStemRowsK = 176;
+void pack_stem_rows(const float* oihw, uint16_t* out);
+void stem_pool_force(int v);  // -1 automatic, 1: never the packed-row kernel
+int launch_stem_pool(int dtype, int n, int h, int w, const void* x, const void* wts, const void* wts_rows,
+                     const float* scale, const float* shift, void* y, hipStream_t stream, int cus, Profiler* prof);
 
 // LDS-patch 3x3 kernel (bf16, stride 1)
 bool plan_patch(const sgprs_conv_desc_t& d, int cus, int* variant, int* splits);

@@ -28,6 +28,7 @@ typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
 typedef unsigned short u16x8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef short i16x2_t __attribute__((ext_vector_type(2)));
 
 struct StemPoolArgs {
     const unsigned char* x;
@@ -245,6 +246,245 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemPoolArgs a)
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// bf16 variant with packed input rows.
+//
+// The kernel above spends its time in the LDS pipe: every wavefront re-reads all weights for each
+// tile, the 4-slot pixel layout pads K from 147 to 224, and the patch goes through registers.
+// Here
+//  * the weights are stationary in registers (88 VGPRs: 2 channel tiles x 11 K-steps), loaded once
+//    per workgroup from a [64][176] layout prepared at task creation;
+//  * the input patch keeps the image's own 3-channel packing: 35 rows of 17 16-byte pieces are
+//    copied global -> LDS by the load unit itself (zero fill outside the image comes from the
+//    buffer bounds check), double buffered so that the next tile's patch lands during this
+//    tile's arithmetic;
+//  * a pixel's K-run for tap row r is the 24 consecutive bf16 that start one element before its
+//    first tap (elements 0, 22, 23 meet zero weights), so K = 7 x 24 = 168 (+8 zero) = 176 and
+//    the run starts on a 4-byte boundary;
+//  * BN scale / shift live in LDS, and there are two barriers per tile instead of four.
+// Element 0 / 22 / 23 of a run are real neighbouring inputs multiplied by zero weights: the
+// result equals the plain definition for finite inputs (a non-finite input pixel would also
+// reach the output columns next to its window).
+constexpr int kRowPitch = 272;                       // 17 pieces of 16 bytes per staged input row
+constexpr int kRowUnits = kInR * 17;                 // 595 pieces per patch
+constexpr int kPatchPitch = 640 * 16;                // 3 rounds of 256 lanes, the tail lands as zeros (row 35, 36)
+constexpr int kPackedK = 176;
+
+typedef unsigned int u32x4a4_t __attribute__((ext_vector_type(4), aligned(4)));
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+__global__ __launch_bounds__(256, 2) void stem_pool_packed_kernel(const StemPoolArgs a, const unsigned x_bytes)
+{
+    constexpr int SROWB = 64 * 2 + 16;
+    constexpr int STG_BASE = 2 * kPatchPitch;
+    constexpr int SC_BASE = STG_BASE + 256 * SROWB;
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int frow = lane & 31, fhalf = lane >> 5;
+
+    const __amdgpu_buffer_rsrc_t x_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.x, 0, (int)x_bytes, 0x00020000);
+    const int row_bytes = a.W * 6;
+    // A tile is (image n, tile row tp, tile column tq).  The walk tile += gridDim.x is kept in
+    // that form with carries, so that no tile costs an integer division.
+    struct TilePos { int n, tp, tq; };
+    const int per_image = a.tiles_p * a.tiles_q;
+    const int step_n = (int)gridDim.x / per_image, step_r = (int)gridDim.x - step_n * per_image;
+    const int step_p = step_r / a.tiles_q, step_q = step_r - step_p * a.tiles_q;
+    auto advance = [&](TilePos t) {
+        t.tq += step_q;
+        if (t.tq >= a.tiles_q) { t.tq -= a.tiles_q; ++t.tp; }
+        t.tp += step_p;
+        if (t.tp >= a.tiles_p) { t.tp -= a.tiles_p; ++t.n; }
+        t.n += step_n;
+        return t;
+    };
+    auto fetch_patch = [&](const TilePos t, int buf) {
+        const int n = t.n, pp0 = t.tp * kPoolTP, pq0 = t.tq * kPoolTQ;
+        const int h_base = 4 * pp0 - 5, b_base = 24 * pq0 - 32;  // first input row; byte of the first piece in its row
+#pragma unroll
+        for (int it = 0; it < 3; ++it) {
+            if (it == 2 && wave >= 2) break;         // 640 piece slots: the third round is half a round
+            const int u = it * 256 + tid;
+            const int row = u / 17, seg = u - row * 17;
+            const int ih = h_base + row, b = b_base + 16 * seg;
+            const bool ok = u < kRowUnits && seg < 16 && (unsigned)ih < (unsigned)a.H && (unsigned)b < (unsigned)row_bytes;
+            const unsigned off = ok ? (unsigned)((n * a.H + ih) * row_bytes + b) : 0x80000000u;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rs, (lds_ptr_t)(smem + buf * kPatchPitch + (it * 256 + wave * 64) * 16), 16,
+                                                     off, 0, 0, 0);
+        }
+    };
+    TilePos cur;
+    cur.n = (int)blockIdx.x / per_image;
+    cur.tp = ((int)blockIdx.x - cur.n * per_image) / a.tiles_q;
+    cur.tq = (int)blockIdx.x - cur.n * per_image - cur.tp * a.tiles_q;
+    if ((int)blockIdx.x < a.ntiles) fetch_patch(cur, 0);
+
+    if (tid < 32) {
+        const int c4 = (tid & 15) * 4;
+        const float* src = tid < 16 ? a.scale : a.shift;
+        *(f32x4_t*)(smem + SC_BASE + (tid < 16 ? 0 : 256) + c4 * 4) = *(const f32x4_t*)(src + c4);
+    }
+
+    // stationary weights: A fragment of channel tile i, K-step ks = 16 bytes at [32i + frow][(2ks + fhalf) * 8]
+    u32x4_t wreg[2][11];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int ks = 0; ks < 11; ++ks)
+            wreg[i][ks] = *(const u32x4_t*)(a.w + (size_t)(32 * i + frow) * (kPackedK * 2) + (2 * ks + fhalf) * 16);
+
+    // this lane's two conv pixels: byte offset of their K-run for tap row 0 inside a patch
+    int poff[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        int t = wave * 64 + j * 32 + frow;
+        if (t >= kConvR * kConvC) t = 0;             // the one padding row of the 256-row tile: computed, never used
+        const int cr = t / kConvC, cc = t - cr * kConvC;
+        poff[j] = (2 * cr) * kRowPitch + 12 * cc;
+    }
+
+    int buf = 0;
+    for (int tile = blockIdx.x; tile < a.ntiles; tile += gridDim.x, buf ^= 1) {
+        const int n = cur.n, pp0 = cur.tp * kPoolTP, pq0 = cur.tq * kPoolTQ;
+        cur = advance(cur);
+        const int cr0 = 2 * pp0 - 1, cc0 = 2 * pq0 - 1;
+
+        __builtin_amdgcn_s_waitcnt(0);               // this tile's patch has landed (and the last tile's stores have left)
+        __syncthreads();                             // ... for every wavefront; the last tile's pooling reads are done
+        if (tile + (int)gridDim.x < a.ntiles) fetch_patch(cur, buf ^ 1);
+
+        f32x16_t acc[2][2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+        // K group kg = 2ks + fhalf covers tap row kg / 3, 16-byte part kg % 3.  The upper half-wave
+        // is one group ahead: 16 bytes further, or 240 (next tap row, part 0) when kg % 3 == 2.
+        const unsigned char* P = smem + buf * kPatchPitch;
+        const unsigned char *b0[2], *bA[2], *bB[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            b0[j] = P + poff[j];
+            bA[j] = b0[j] + fhalf * 16;
+            bB[j] = b0[j] + fhalf * (kRowPitch - 32);
+        }
+        // B fragments are read one K-step ahead of the MFMAs that use them
+        auto read_b = [&](int ks, u32x4_t (&pf)[2]) {
+            const int kg = 2 * ks, off = (kg / 3) * kRowPitch + (kg % 3) * 16;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                // the last step's upper group (21) has zero weights: it re-reads group 20
+                const unsigned char* src = ks == 10 ? b0[j] : kg % 3 == 2 ? bB[j] : bA[j];
+                pf[j] = *(const u32x4a4_t*)(src + off);
+            }
+        };
+        constexpr int STEM_DEPTH = 1;   // deeper prefetch measured no faster
+        u32x4_t pf[STEM_DEPTH + 1][2];
+#pragma unroll
+        for (int d = 0; d < STEM_DEPTH; ++d) read_b(d, pf[d]);
+#pragma unroll
+        for (int ks = 0; ks < 11; ++ks) {
+            if (ks + STEM_DEPTH < 11) read_b(ks + STEM_DEPTH, pf[(ks + STEM_DEPTH) % (STEM_DEPTH + 1)]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wreg[i][ks]),
+                                                                      __builtin_bit_cast(bf16x8_t, pf[ks % (STEM_DEPTH + 1)][j]),
+                                                                      acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+
+        // Accumulator register e: column lane%32 = pixel, row 8*(e/4) + 4*(lane/32) + e%4 = channel.
+        // Scale and shift of the next channel group are read from LDS while this one is computed.
+        // ReLU is taken after the rounding, on the bf16 pair as signed 16-bit integers (rounding
+        // is monotone and keeps 0, so the order does not matter); the staged values are then
+        // non-negative bit patterns, which the pooling compares as unsigned integers.  Positions
+        // outside the conv output are cleared to 0 afterwards: each pooling window has a real pixel,
+        // so 0 never wins wrongly.
+        int tpix[2];
+        bool keep[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int t = wave * 64 + j * 32 + frow;
+            const int cr = t / kConvC, cc = t - cr * kConvC;
+            const int crow = cr0 + cr, ccol = cc0 + cc;
+            const bool ok = t < kConvR * kConvC && (unsigned)crow < (unsigned)a.P && (unsigned)ccol < (unsigned)a.Q;
+            keep[j] = ok;
+            tpix[j] = t;
+        }
+        const unsigned char* scp = smem + SC_BASE + 16 * fhalf;
+        f32x4_t sc_n = *(const f32x4_t*)scp, sh_n = *(const f32x4_t*)(scp + 256);
+#pragma unroll
+        for (int ig = 0; ig < 8; ++ig) {
+            const int i = ig >> 2, g = ig & 3;
+            const f32x4_t sc = sc_n, sh = sh_n;
+            if (ig + 1 < 8) {
+                sc_n = *(const f32x4_t*)(scp + (ig + 1) * 32);
+                sh_n = *(const f32x4_t*)(scp + 256 + (ig + 1) * 32);
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                float v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) v[u] = acc[i][j][4 * g + u] * sc[u] + sh[u];
+                const f32x2_t p0 = {v[0], v[1]}, p1 = {v[2], v[3]};
+                const i16x2_t zero = {0, 0};
+                const i16x2_t r0 = __builtin_elementwise_max(__builtin_bit_cast(i16x2_t, __builtin_convertvector(p0, bf16x2_t)), zero);
+                const i16x2_t r1 = __builtin_elementwise_max(__builtin_bit_cast(i16x2_t, __builtin_convertvector(p1, bf16x2_t)), zero);
+                u32x2_t o = {__builtin_bit_cast(unsigned, r0), __builtin_bit_cast(unsigned, r1)};
+                *(u32x2_t*)(smem + STG_BASE + tpix[j] * SROWB + (32 * i + 8 * g + 4 * fhalf) * 2) = o;
+            }
+        }
+        // border tiles only: a lane whose pixel lies outside the conv output clears what it staged
+        // (both half-waves of a pixel take the branch together and write the same zeros)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            if (!keep[j]) {
+                const u32x4_t z = {0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int q = 0; q < 8; ++q) *(u32x4_t*)(smem + STG_BASE + tpix[j] * SROWB + q * 16) = z;
+            }
+        __syncthreads();
+
+        // pooling: one item = (pooled pixel, 16-byte channel group); 448 items, two per thread (the
+        // second only for threads 0..191), the 18 LDS reads of both in flight together
+        {
+            constexpr int ITEMS = kPoolTP * kPoolTQ * 8;
+            u32x4_t m[2];
+            const unsigned char* base[2];
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int it = tid + 256 * k < ITEMS ? tid + 256 * k : tid;
+                const int px = it >> 3, lp = px / kPoolTQ, lq = px - lp * kPoolTQ;
+                base[k] = smem + STG_BASE + ((2 * lp) * kConvC + 2 * lq) * SROWB + (it & 7) * 16;
+                m[k] = *(const u32x4_t*)base[k];
+            }
+#pragma unroll
+            for (int rs = 1; rs < 9; ++rs)
+#pragma unroll
+                for (int k = 0; k < 2; ++k) {
+                    const u32x4_t t = *(const u32x4_t*)(base[k] + ((rs / 3) * kConvC + rs % 3) * SROWB);
+                    m[k] = __builtin_bit_cast(u32x4_t, __builtin_elementwise_max(__builtin_bit_cast(u16x8_t, m[k]), __builtin_bit_cast(u16x8_t, t)));
+                }
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int it = tid + 256 * k;
+                const int px = it >> 3, lp = px / kPoolTQ, lq = px - lp * kPoolTQ;
+                const int gp = pp0 + lp, gq = pq0 + lq;
+                if (it < ITEMS && gp < a.PP && gq < a.PQ)
+                    *(u32x4_t*)(a.y + (((size_t)(n * a.PP + gp) * a.PQ + gq) * 64) * 2 + (it & 7) * 16) = m[k];
+            }
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+}
+
 bool stem_pool_applicable(int dtype, int n, int h, int w, int cus)
 {
     const int P = out_dim(h, 7, 2, 3), Q = out_dim(w, 7, 2, 3);
@@ -255,8 +495,22 @@ bool stem_pool_applicable(int dtype, int n, int h, int w, int cus)
     return dtype == SGPRS_BF16 ? tiles >= 32 : tiles >= 2ll * cus;
 }
 
-int launch_stem_pool(int dtype, int n, int h, int w, const void* x, const void* wts, const float* scale,
-                     const float* shift, void* y, hipStream_t stream, int cus, Profiler* prof)
+std::atomic<int> g_stem_pool_force{-1};
+void stem_pool_force(int v) { g_stem_pool_force = v; }
+
+void pack_stem_rows(const float* oihw, uint16_t* out)
+{
+    // [64][176]: tap row r occupies 24 elements, element 1 + 3s + c is tap (r, s) of input channel c
+    std::fill(out, out + 64 * kPackedK, (uint16_t)0);
+    for (int k = 0; k < 64; ++k)
+        for (int c = 0; c < 3; ++c)
+            for (int r = 0; r < 7; ++r)
+                for (int s2 = 0; s2 < 7; ++s2)
+                    out[k * kPackedK + r * 24 + 1 + 3 * s2 + c] = f32_to_bf16_bits(oihw[((k * 3 + c) * 7 + r) * 7 + s2]);
+}
+
+int launch_stem_pool(int dtype, int n, int h, int w, const void* x, const void* wts, const void* wts_rows,
+                     const float* scale, const float* shift, void* y, hipStream_t stream, int cus, Profiler* prof)
 {
     StemPoolArgs a;
     a.x = (const unsigned char*)x; a.w = (const unsigned char*)wts; a.y = (unsigned char*)y;
@@ -276,9 +530,22 @@ int launch_stem_pool(int dtype, int n, int h, int w, const void* x, const void* 
     const double flops = 2.0 * n * a.P * a.Q * 64.0 * 147.0;
     const double bytes = ((double)n * h * w * 3 + 64.0 * 147 + (double)n * a.PP * a.PQ * 64) * es;
     int rc;
-    if (prof && prof->on && (rc = prof->begin(stream, kKindStemPool, dtype, flops, bytes))) return rc;
-    static std::atomic<bool> raised[2] = {{false}, {false}};
-    if (dtype == SGPRS_BF16) {
+    static std::atomic<bool> raised[3] = {{false}, {false}, {false}};
+    const long long x_bytes = (long long)n * h * w * 6;
+    const bool packed = dtype == SGPRS_BF16 && wts_rows && w % 8 == 0 && ((uintptr_t)x & 15) == 0 && x_bytes < (1ll << 31) &&
+                        g_stem_pool_force.load() != 1;
+    if (prof && prof->on && (rc = prof->begin(stream, kKindStemPool, packed ? 2 : dtype, flops, bytes))) return rc;
+    if (packed) {
+        a.w = (const unsigned char*)wts_rows;
+        constexpr int lds_rows = 2 * kPatchPitch + 256 * (64 * 2 + 16) + 512;
+        if (!raised[2]) {
+            SGPRS_HIP(hipFuncSetAttribute((const void*)stem_pool_packed_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                          lds_rows));
+            raised[2] = true;
+        }
+        SGPRS_LAUNCH(stem_pool_packed_kernel, dim3((int)std::min<long long>(nt, 2ll * cus)), dim3(256), lds_rows, stream, a,
+                     (unsigned)x_bytes);
+    } else if (dtype == SGPRS_BF16) {
         if (!raised[1]) {
             SGPRS_HIP(hipFuncSetAttribute((const void*)stem_pool_kernel<SGPRS_BF16>,
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));

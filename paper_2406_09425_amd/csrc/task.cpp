@@ -45,6 +45,7 @@ struct sgprs_task {
     ConvLayer conv[SGPRS_RESNET18_CONVS];
     void* fc_w = nullptr;
     float* fc_b = nullptr;
+    void* stem_w_rows = nullptr;  // bf16 only: the stem weights in the packed-row kernel's layout
     void* stem_out = nullptr;
     void* tmp[3] = {nullptr, nullptr, nullptr};
     void* stage_out[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
@@ -205,7 +206,7 @@ int run_stage(sgprs_task* t, int j, int batch, const void* in, void* out, hipStr
     int rc;
     if (j == 0) {
         if (stem_pool_applicable(t->dtype, batch, 224, 224, cus))
-            return launch_stem_pool(t->dtype, batch, 224, 224, in, t->conv[0].w, t->conv[0].scale, t->conv[0].shift, out, s,
+            return launch_stem_pool(t->dtype, batch, 224, 224, in, t->conv[0].w, t->stem_w_rows, t->conv[0].scale, t->conv[0].shift, out, s,
                                     cus, prof);
         if ((rc = run_conv(t, 0, batch, in, nullptr, t->stem_out, 1, s, cus, prof))) return rc;
         return launch_maxpool(t->dtype, batch, 112, 112, 64, t->stem_out, out, s, cus, prof);
@@ -286,7 +287,12 @@ int sgprs_task_create_resnet18(int device, int dtype, int max_batch, const sgprs
             break;
         if ((rc = upload(t, packed.data(), bytes, &t->conv[i].w))) break;
         if ((rc = upload(t, scale.data(), cs.cout * sizeof(float), (void**)&t->conv[i].scale))) break;
-        rc = upload(t, shift.data(), cs.cout * sizeof(float), (void**)&t->conv[i].shift);
+        if ((rc = upload(t, shift.data(), cs.cout * sizeof(float), (void**)&t->conv[i].shift))) break;
+        if (i == 0 && dtype == SGPRS_BF16) {
+            std::vector<uint16_t> rows((size_t)64 * kStemRowsK);
+            pack_stem_rows(hp->conv_w[0], rows.data());
+            rc = upload(t, rows.data(), rows.size() * 2, &t->stem_w_rows);
+        }
     }
     if (!rc) {
         const size_t n = (size_t)kFcOut * kFcIn;
@@ -505,7 +511,8 @@ const char* sgprs_kernel_name(int kind, int variant)
         case kKindPatch: return patch_variant_name(variant);
         case kKindS2Patch: return s2patch_variant_name(variant);
         case kKindStem: return "conv_stem_kernel";
-        case kKindStemPool: return variant == SGPRS_BF16 ? "stem_pool_kernel<1>" : "stem_pool_kernel<0>";
+        case kKindStemPool:
+            return variant == 2 ? "stem_pool_packed_kernel" : variant == SGPRS_BF16 ? "stem_pool_kernel<1>" : "stem_pool_kernel<0>";
         case kKindReduce: return "splitk_reduce_kernel";
         case kKindMaxpool: return "maxpool3x3s2_kernel";
         case kKindAvgpool: return "avgpool_kernel";

@@ -202,6 +202,42 @@ def test_stage0_fp32_fused_stem_pool_elementwise(cfg1):
         pool.destroy()
 
 
+def test_stage0_bf16_packed_row_and_four_slot_kernels_elementwise():
+    """bf16 stage 0 runs the packed-row stem + pool kernel (kernel name recorded by the task); the
+    tuning override switches to the 4-slot kernel.  Both, element by element against the oracle,
+    on 8 CUs (each workgroup walks many tiles through both patch buffers), 64 CUs and the whole
+    chip, with a ragged batch of 3 and a single image; the two kernels agree to accumulation order."""
+    dtype = S.SGPRS_BF16
+    params = make_resnet18_params(6, 1, bf16=True)
+    total = S.Pool(1, 8).info()["total_cus"]
+    for nb in (3, 1):
+        x = make_input(6, nb, (nb, 3, 224, 224), bf16=True)
+        ref = oracle.resnet18_stage(0, params, BN_EPS, x)
+        xd = dev_nhwc(x, dtype)
+        for cus in (8, 64, total):
+            pool = S.Pool(1, cus)
+            task = S.Task(params, dtype, nb, BN_EPS)
+            task.set_profiling(True)
+            outs = []
+            try:
+                for kind, name in ((-1, "stem_pool_packed_kernel"), (4, "stem_pool_kernel<1>")):
+                    S.sgprs_conv_tuning_override(kind, 0, 1)
+                    o = dev_empty(stage_shape(0, nb), dtype)
+                    o.fill_(float("nan"))
+                    task.stage_run(0, nb, xd.data_ptr(), o.data_ptr(), pool, 0)
+                    pool.sync()
+                    assert [r["name"] for r in task.kernel_times(0)] == [name], (cus, kind)
+                    assert_close(host_nchw(o), ref, dtype, f"bf16 stage 0, {name}, batch {nb} on {cus} CUs")
+                    outs.append(o.float().cpu().numpy())
+            finally:
+                S.sgprs_conv_tuning_override(-1, 0, 1)
+            # same bf16 grid, fp32 sums in another order: at most one bf16 step apart
+            d = np.abs(outs[0] - outs[1])
+            assert np.all(d <= np.maximum(np.abs(outs[1]), 1e-3) * 2.0 ** -7), float(d.max())
+            task.destroy()
+            pool.destroy()
+
+
 # ------------------------------------------------------------- config 3
 def test_config3_eight_bf16_instances_on_8x32_pool():
     dtype = S.SGPRS_BF16
