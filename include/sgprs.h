@@ -180,6 +180,13 @@ int sgprs_unpack_conv_weights(const sgprs_conv_desc_t *d, const void *w_packed, 
 /* Split-K scratch needed on a partition of partition_cus CUs (0 when the
  * launch is not split). */
 int sgprs_conv2d_workspace(const sgprs_conv_desc_t *d, int partition_cus, size_t *bytes);
+/* Which kernel sgprs_conv2d would launch for this shape on a partition of
+ * partition_cus CUs, with or without a residual (host logic only, nothing is
+ * enqueued).  family: 0 implicit GEMM, 1 LDS-patch 3x3, 2 stride-2 LDS-patch
+ * 3x3, 3 row-streaming 3x3 (64 -> 64 channels, 56-pixel rows), 4 the 7x7 stem;
+ * detail: the tile variant, or the output rows per stream and job of family 3. */
+int sgprs_conv2d_plan(const sgprs_conv_desc_t *d, int partition_cus, int has_residual, int *family,
+                      int *detail);
 /* y = act( scale[k] * conv(x, w)[.,k] + shift[k] (+ residual) ).
  * x: [n][h][w][cin]; w_packed: DEVICE copy of the packed weights; scale, shift:
  * DEVICE fp32[cout]; residual: NULL or [n][p][q][cout] in dtype; y: same shape.
@@ -198,7 +205,8 @@ int sgprs_conv2d(const sgprs_conv_desc_t *d, const void *x, const void *w_packed
  * 3: automatic, plus the stride-2 LDS-patch kernel (not chosen otherwise) with
  * tile variant `variant` (0: 256 rows, 1: 128 rows) wherever the shape allows
  * it; variant 2 switches it off again; 4: automatic, but stage 0 of a bf16
- * task uses the 4-slot stem+pool kernel instead of the packed-row one. */
+ * task uses the 4-slot stem+pool kernel instead of the packed-row one; 5:
+ * automatic, but without the row-streaming kernel of the 64 -> 64 layers. */
 int sgprs_conv_tuning_override(int kind, int variant, int splits);
 /* Max pooling 3x3, stride 2, pad 1 (padding never wins): [n][h][w][c] ->
  * [n][(h-1)/2+1][(w-1)/2+1][c].  c % 8 == 0 (bf16) or c % 4 == 0 (fp32). */
@@ -291,9 +299,11 @@ const void *sgprs_task_stage_output(const sgprs_task_t *task, int stage);
  * per launch: HOST arrays of length *count (in: capacity).  kind: 0 conv
  * implicit GEMM, 1 stem conv, 2 split-K reduce, 3 max-pool, 4 avg-pool, 5 FC
  * (variant 2, 3: avg-pool and FC in one launch; 4: the FC on the matrix cores),
- * 6 BN+ReLU, 7 add+ReLU, 8 LDS-patch 3x3 conv, 9 fused stem conv + max-pool,
+ * 6 BN+ReLU, 7 add+ReLU, 8 LDS-patch 3x3 conv, 9 fused stem conv + max-pool
+ * (variant 2: the bf16 kernel with packed input rows),
  * 10 two implicit-GEMM convolutions of one input in a single launch, 11 the
- * stride-2 LDS-patch 3x3 conv (variant + 4: together with the 1x1 shortcut).
+ * stride-2 LDS-patch 3x3 conv (variant + 4: together with the 1x1 shortcut),
+ * 12 the row-streaming 3x3 conv of the 64 -> 64 layers.
  * flops/bytes are the algorithmic work of the launch. */
 int sgprs_task_set_profiling(sgprs_task_t *task, int on);
 /* Graph replay of sgprs_task_run (see there): mode 1 always, 0 never (every

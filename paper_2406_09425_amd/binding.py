@@ -19,7 +19,7 @@ __all__ = [
     "sgprs_version", "sgprs_status_string", "sgprs_last_error", "sgprs_build_cu_mask",
     "sgprs_fold_bn", "sgprs_conv_packed_weight_bytes", "sgprs_pack_conv_weights",
     "sgprs_unpack_conv_weights", "sgprs_conv2d_workspace", "sgprs_conv2d", "sgprs_maxpool2d",
-    "sgprs_conv_tuning_override", "sgprs_bn_relu", "sgprs_add_relu", "sgprs_avgpool_fc", "sgprs_avgpool_fc_static",
+    "sgprs_conv_tuning_override", "sgprs_conv2d_plan", "sgprs_bn_relu", "sgprs_add_relu", "sgprs_avgpool_fc", "sgprs_avgpool_fc_static",
     "sgprs_kernel_name",
 ]
 
@@ -106,6 +106,7 @@ def lib():
         "sgprs_conv2d_workspace": (c_int, [POINTER(ConvDesc), c_int, POINTER(c_size_t)]),
         "sgprs_conv2d": (c_int, [POINTER(ConvDesc), vp, vp, vp, vp, vp, vp, vp, c_size_t, vp, c_int]),
         "sgprs_conv_tuning_override": (c_int, [c_int, c_int, c_int]),
+        "sgprs_conv2d_plan": (c_int, [POINTER(ConvDesc), c_int, c_int, POINTER(c_int), POINTER(c_int)]),
         "sgprs_maxpool2d": (c_int, [c_int, c_int, c_int, c_int, c_int, vp, vp, vp, c_int]),
         "sgprs_bn_relu": (c_int, [c_int, c_size_t, c_int, vp, vp, vp, vp, vp, c_int]),
         "sgprs_add_relu": (c_int, [c_int, c_size_t, vp, vp, vp, c_int, vp, c_int]),
@@ -216,6 +217,13 @@ def sgprs_conv2d_workspace(desc: ConvDesc, partition_cus: int) -> int:
     n = c_size_t(0)
     _check(lib().sgprs_conv2d_workspace(ctypes.byref(desc), partition_cus, ctypes.byref(n)))
     return n.value
+
+
+def sgprs_conv2d_plan(desc: ConvDesc, partition_cus: int, has_residual: bool = False):
+    """(family, detail) of the kernel sgprs_conv2d would launch."""
+    fam, det = c_int(-1), c_int(-1)
+    _check(lib().sgprs_conv2d_plan(ctypes.byref(desc), partition_cus, int(has_residual), ctypes.byref(fam), ctypes.byref(det)))
+    return fam.value, det.value
 
 
 class Pool:

@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libsgprs.so")
 OBJ_DIR = os.path.join(PKG, "_build")
 
-SOURCES = ["pool.cpp", "pack.cpp", "ops.cpp", "task.cpp", "sched.cpp", "conv_igemm.hip", "conv_stem.hip", "conv3x3_patch.hip", "stem_pool.hip",
+SOURCES = ["pool.cpp", "pack.cpp", "ops.cpp", "task.cpp", "sched.cpp", "conv_igemm.hip", "conv_stem.hip", "conv3x3_patch.hip", "conv3x3_rows.hip", "stem_pool.hip",
            "pointwise.hip", "mfma_probe.hip", "load_probe.hip"]
 
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-variable", "-I", os.path.join(ROOT, "include"),

@@ -596,6 +596,7 @@ int launch_conv(const sgprs_conv_desc_t& d, const void* x, const void* w, const 
     if (p.kind == 1)
         return launch_conv3x3_patch(d, p.variant, p.splits, x, w, scale, shift, residual, y, ws, ws_bytes, stream, cus,
                                     prof);
+    if (p.kind == 3) return launch_conv3x3_rows(d, p.variant, x, w, scale, shift, residual, y, stream, cus, prof);
     if (p.kind == 2) {
         return launch_conv3x3s2_patch(d, p.variant, x, w, scale, shift, y, nullptr, nullptr, nullptr, nullptr, nullptr, stream, cus,
                                       prof);

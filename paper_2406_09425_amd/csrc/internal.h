@@ -159,8 +159,8 @@ extern std::atomic<int> g_plan_generation;  // bumped whenever a tuning override
 
 // Tile configuration of one implicit-GEMM launch.
 struct ConvPlan {
-    int kind = 0;      // 0: implicit GEMM, 1: LDS-patch 3x3 kernel, 2: its stride-2 variant
-    int variant = 0;   // index into the kernel's tile table
+    int kind = 0;      // 0: implicit GEMM, 1: LDS-patch 3x3 kernel, 2: its stride-2 variant, 3: row streaming
+    int variant = 0;   // index into the kernel's tile table (row streaming: output rows per stream and job)
     int bm = 0, bn = 0;
     int splits = 1;    // split-K factor (grid.z)
     int ktiles = 0;    // total k-tiles of 128 bytes
@@ -207,7 +207,7 @@ struct Profiler {
 
 enum KernelKind { kKindIgemm = 0, kKindStem = 1, kKindReduce = 2, kKindMaxpool = 3, kKindAvgpool = 4,
                   kKindFc = 5, kKindBnRelu = 6, kKindAdd = 7, kKindPatch = 8, kKindStemPool = 9,
-                  kKindIgemmPair = 10, kKindS2Patch = 11 };
+                  kKindIgemmPair = 10, kKindS2Patch = 11, kKindRows = 12 };
 
 // launchers (device pointers; validated by callers)
 int launch_conv(const sgprs_conv_desc_t& d, const void* x, const void* w, const float* scale,
@@ -259,6 +259,11 @@ const char* s2patch_variant_name(int variant);
 int launch_conv3x3s2_patch(const sgprs_conv_desc_t& d, int variant, const void* x, const void* w, const float* scale,
                            const float* shift, void* y, const sgprs_conv_desc_t* d2, const void* w2, const float* scale2,
                            const float* shift2, void* y2, hipStream_t stream, int cus, Profiler* prof);
+// row-streaming 3x3 kernel (bf16, 64 -> 64 channels, 56-pixel rows)
+bool plan_rows(const sgprs_conv_desc_t& d, int cus, int* rows_per_stream);
+void rows_force_off(bool off);
+int launch_conv3x3_rows(const sgprs_conv_desc_t& d, int rows_per_stream, const void* x, const void* w, const float* scale,
+                        const float* shift, const void* residual, void* y, hipStream_t stream, int cus, Profiler* prof);
 // tuning override: kind -1 automatic, 0 implicit GEMM only, 1 force patch (variant, splits)
 extern std::atomic<int> g_conv_force_kind;
 extern std::atomic<int> g_igemm_force_variant, g_igemm_force_splits;

@@ -73,12 +73,13 @@ int sgprs_conv2d(const sgprs_conv_desc_t* d, const void* x, const void* w_packed
 
 int sgprs_conv_tuning_override(int kind, int variant, int splits)
 {
-    if (kind < -1 || kind > 4) return fail(SGPRS_ERR_INVALID_ARG, "kind %d outside [-1,4]", kind);
+    if (kind < -1 || kind > 5) return fail(SGPRS_ERR_INVALID_ARG, "kind %d outside [-1,5]", kind);
     if (kind == 3 && (variant < 0 || variant > s2patch_num_variants()))
         return fail(SGPRS_ERR_INVALID_ARG, "stride-2 patch variant %d outside [0,%d]", variant, s2patch_num_variants());
     g_plan_generation.fetch_add(1);
     s2patch_force(kind == 3 ? variant : kind == 0 ? 2 : -1);
     stem_pool_force(kind == 4 ? 1 : -1);
+    rows_force_off(kind == 5);
     g_conv_force_kind = kind >= 2 ? -1 : kind;
     g_igemm_force_variant = kind == 2 ? variant : -1;
     g_igemm_force_splits = kind == 2 ? splits : 0;

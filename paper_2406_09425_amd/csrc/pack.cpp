@@ -77,6 +77,15 @@ static ConvPlan plan_conv_uncached(const sgprs_conv_desc_t& d, int cus, bool has
 {
     const int force_kind = g_conv_force_kind.load(), force_variant = g_igemm_force_variant.load(),
               force_splits = g_igemm_force_splits.load();
+    if (force_kind == -1) {
+        int rows = 0;
+        if (plan_rows(d, cus < 1 ? 1 : cus, &rows)) {
+            ConvPlan p;
+            p.kind = 3; p.variant = rows; p.splits = 1;
+            p.bm = 1;  // marks a valid plan
+            return p;
+        }
+    }
     if (force_kind != 0) {
         int v = 0, s = 1;
         if (plan_patch(d, cus < 1 ? 1 : cus, &v, &s)) {
@@ -226,6 +235,22 @@ int sgprs_conv2d_workspace(const sgprs_conv_desc_t* d, int partition_cus, size_t
     // the plan may depend on whether a residual is passed: enough for either
     *bytes = is_stem(*d) ? 0 : std::max(conv_workspace_bytes(*d, plan_conv(*d, partition_cus, false)),
                                         conv_workspace_bytes(*d, plan_conv(*d, partition_cus, true)));
+    return SGPRS_OK;
+}
+
+int sgprs_conv2d_plan(const sgprs_conv_desc_t* d, int partition_cus, int has_residual, int* family, int* detail)
+{
+    int rc = check_conv_desc(d);
+    if (rc) return rc;
+    if (!family || !detail) return fail(SGPRS_ERR_INVALID_ARG, "family or detail is NULL");
+    if (partition_cus <= 0) return fail(SGPRS_ERR_INVALID_ARG, "partition_cus %d <= 0", partition_cus);
+    if (is_stem(*d)) {
+        *family = 4; *detail = 0;
+        return SGPRS_OK;
+    }
+    const ConvPlan p = plan_conv(*d, partition_cus, has_residual != 0);
+    if (p.bm == 0) return fail(SGPRS_ERR_UNSUPPORTED, "no tile shape fits cout %d", d->cout);
+    *family = p.kind; *detail = p.variant;
     return SGPRS_OK;
 }
 

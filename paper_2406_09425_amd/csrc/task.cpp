@@ -510,6 +510,7 @@ const char* sgprs_kernel_name(int kind, int variant)
         case kKindIgemmPair: return igemm_pair_variant_name(variant);
         case kKindPatch: return patch_variant_name(variant);
         case kKindS2Patch: return s2patch_variant_name(variant);
+        case kKindRows: return "conv3x3_rows_kernel";
         case kKindStem: return "conv_stem_kernel";
         case kKindStemPool:
             return variant == 2 ? "stem_pool_packed_kernel" : variant == SGPRS_BF16 ? "stem_pool_kernel<1>" : "stem_pool_kernel<0>";

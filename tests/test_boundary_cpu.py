@@ -128,7 +128,7 @@ def test_memoised_plans_follow_tuning_overrides():
         S.sgprs_conv_tuning_override(-1, 0, 1)
         assert S.sgprs_conv2d_workspace(d, 256) == auto
         with pytest.raises(S.SgprsError):
-            S.sgprs_conv_tuning_override(5, 0, 1)
+            S.sgprs_conv_tuning_override(6, 0, 1)
         with pytest.raises(S.SgprsError):
             S.sgprs_conv_tuning_override(3, 7, 1)
     finally:
@@ -156,3 +156,32 @@ def test_null_handles_rejected():
     assert L.sgprs_pool_stream(None, 0) is None
     assert L.sgprs_stage_run(None, 0, 1, None, None, None, 0) == -1
     assert "NULL" in S.sgprs_last_error()
+
+
+def test_conv_plan_query_and_row_streaming_eligibility():
+    """sgprs_conv2d_plan is host logic.  The row-streaming kernel is chosen only for bf16 64 -> 64
+    layers on 56-pixel rows when every CU gets whole jobs of at least 7 rows per stream; the
+    override switches it off; other shapes keep their kernels."""
+    def plan(n, cus, **kw):
+        a = dict(h=56, w=56, cin=64, cout=64, k=3, stride=1, pad=1, dtype=S.SGPRS_BF16)
+        a.update(kw)
+        d = S.ConvDesc(n, a["h"], a["w"], a["cin"], a["cout"], a["k"], a["k"], a["stride"], a["pad"], a["dtype"], 1)
+        return S.sgprs_conv2d_plan(d, cus, True)
+    assert plan(64, 256) == (3, 7)       # the benchmark's layer1: 256 jobs of 2 x 7 rows
+    assert plan(64, 64) == (3, 28)       # whole images per job
+    assert plan(16, 64) == (3, 7)
+    assert plan(4, 8) == (3, 14)
+    assert plan(1, 32)[0] == 1           # one image on 32 CUs: 4 jobs would leave 28 CUs idle
+    assert plan(3, 8)[0] == 1            # 12 jobs on 8 CUs: a half-empty second round
+    assert plan(64, 256, dtype=S.SGPRS_F32)[0] == 0
+    assert plan(64, 256, cout=128, stride=2)[0] != 3
+    assert plan(64, 256, h=28, w=28)[0] == 1
+    assert plan(1, 256, h=224, w=224, cin=3, k=7, stride=2, pad=3) == (4, 0)
+    try:
+        S.sgprs_conv_tuning_override(5, 0, 1)
+        assert plan(64, 256)[0] == 1
+    finally:
+        S.sgprs_conv_tuning_override(-1, 0, 1)
+    assert plan(64, 256) == (3, 7)
+    with pytest.raises(S.SgprsError):
+        S.sgprs_conv2d_plan(S.ConvDesc(1, 56, 56, 64, 64, 3, 3, 1, 1, S.SGPRS_BF16, 1), 0, False)
