@@ -285,11 +285,22 @@ __global__ __launch_bounds__(256, 2) void stem_pool_packed_kernel(const StemPool
 
     const __amdgpu_buffer_rsrc_t x_rs = __builtin_amdgcn_make_buffer_rsrc((void*)a.x, 0, (int)x_bytes, 0x00020000);
     const int row_bytes = a.W * 6;
-    // A tile is (image n, tile row tp, tile column tq).  The walk tile += gridDim.x is kept in
+    // Workgroup b runs on die b % 8 (whole chip; on a masked partition the dies of the mask take
+    // turns the same way).  Each die walks its own contiguous eighth of the tiles, so neighbouring
+    // tiles, whose input patches overlap by a quarter, meet in one L2 and the overlap is fetched
+    // from HBM once.
+    int first_tile = blockIdx.x, tile_step = gridDim.x, tile_end = a.ntiles;
+    if (gridDim.x % 8 == 0) {
+        const int per_die = (a.ntiles + 7) / 8, die = blockIdx.x & 7;
+        first_tile = die * per_die + ((int)blockIdx.x >> 3);
+        tile_step = (int)gridDim.x >> 3;
+        tile_end = min((die + 1) * per_die, a.ntiles);
+    }
+    // A tile is (image n, tile row tp, tile column tq).  The walk tile += tile_step is kept in
     // that form with carries, so that no tile costs an integer division.
     struct TilePos { int n, tp, tq; };
     const int per_image = a.tiles_p * a.tiles_q;
-    const int step_n = (int)gridDim.x / per_image, step_r = (int)gridDim.x - step_n * per_image;
+    const int step_n = tile_step / per_image, step_r = tile_step - step_n * per_image;
     const int step_p = step_r / a.tiles_q, step_q = step_r - step_p * a.tiles_q;
     auto advance = [&](TilePos t) {
         t.tq += step_q;
@@ -315,10 +326,10 @@ __global__ __launch_bounds__(256, 2) void stem_pool_packed_kernel(const StemPool
         }
     };
     TilePos cur;
-    cur.n = (int)blockIdx.x / per_image;
-    cur.tp = ((int)blockIdx.x - cur.n * per_image) / a.tiles_q;
-    cur.tq = (int)blockIdx.x - cur.n * per_image - cur.tp * a.tiles_q;
-    if ((int)blockIdx.x < a.ntiles) fetch_patch(cur, 0);
+    cur.n = first_tile / per_image;
+    cur.tp = (first_tile - cur.n * per_image) / a.tiles_q;
+    cur.tq = first_tile - cur.n * per_image - cur.tp * a.tiles_q;
+    if (first_tile < tile_end) fetch_patch(cur, 0);
 
     if (tid < 32) {
         const int c4 = (tid & 15) * 4;
@@ -345,14 +356,14 @@ __global__ __launch_bounds__(256, 2) void stem_pool_packed_kernel(const StemPool
     }
 
     int buf = 0;
-    for (int tile = blockIdx.x; tile < a.ntiles; tile += gridDim.x, buf ^= 1) {
+    for (int tile = first_tile; tile < tile_end; tile += tile_step, buf ^= 1) {
         const int n = cur.n, pp0 = cur.tp * kPoolTP, pq0 = cur.tq * kPoolTQ;
         cur = advance(cur);
         const int cr0 = 2 * pp0 - 1, cc0 = 2 * pq0 - 1;
 
         __builtin_amdgcn_s_waitcnt(0);               // this tile's patch has landed (and the last tile's stores have left)
         __syncthreads();                             // ... for every wavefront; the last tile's pooling reads are done
-        if (tile + (int)gridDim.x < a.ntiles) fetch_patch(cur, buf ^ 1);
+        if (tile + tile_step < tile_end) fetch_patch(cur, buf ^ 1);
 
         f32x16_t acc[2][2];
 #pragma unroll
