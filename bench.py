@@ -81,6 +81,9 @@ def main():
                     help="only the eight-instance throughput on pools of N equal partitions (for tracing which kernels "
                          "run beside which), e.g. 8 or 4,8")
     ap.add_argument("--pool-rounds", type=int, default=150, help="rounds of eight inferences per pool in that leg")
+    ap.add_argument("--multi-tenant-only", action="store_true",
+                    help="only the eight-instance leg on the 8 x 32-CU pool (stage by stage, static executor with and "
+                         "without the busy-partition gate, sweeps over partitions in use and over the gate)")
     ap.add_argument("--membound-only", action="store_true",
                     help="run only the memory-bound operator leg (for profiling it); prints its own JSON line")
     ap.add_argument("--copy-calib", action="store_true",
@@ -136,6 +139,11 @@ def main():
 
     if args.periodic_only:
         print(json.dumps(dict(periodic_tasks=leg_periodic(S, hip, torch, total_cus, nhwc))), flush=True)
+        pool.destroy()
+        return
+
+    if args.multi_tenant_only:
+        print(json.dumps(dict(multi_tenant=leg_multi_tenant(S, hip, torch, total_cus, nhwc))), flush=True)
         pool.destroy()
         return
 
@@ -760,6 +768,16 @@ def leg_multi_tenant(S, hip, torch, total_cus, nhwc, n_p=8, rounds=100):
     pool.run_static(tasks, ptrs[0], ptrs[1], 1, list(range(n_p)), 20, 4)
     gated = n_p * rounds / pool.run_static(tasks, ptrs[0], ptrs[1], 1, list(range(n_p)), rounds, 4)
     ungated = n_p * rounds / pool.run_static(tasks, ptrs[0], ptrs[1], 1, list(range(n_p)), rounds, 0)
+    # Where the collapse sets in: the same eight tasks pinned to the first k of the eight partitions
+    # (the other queues exist but stay idle), no gate; and all eight partitions with the gate at m.
+    busy_sweep = []
+    for k in range(1, n_p + 1):
+        ips = n_p * rounds / pool.run_static(tasks, ptrs[0], ptrs[1], 1, [i % k for i in range(n_p)], rounds, 0)
+        busy_sweep.append(dict(partitions_in_use=k, images_per_s=round(ips, 1)))
+    gate_sweep = []
+    for m in range(1, n_p + 1):
+        ips = n_p * rounds / pool.run_static(tasks, ptrs[0], ptrs[1], 1, list(range(n_p)), rounds, m)
+        gate_sweep.append(dict(max_busy=m, images_per_s=round(ips, 1)))
     # context: the same eight images back to back on one full-GPU partition
     full = S.Pool(1, total_cus)
     t0 = time.perf_counter()
@@ -771,6 +789,7 @@ def leg_multi_tenant(S, hip, torch, total_cus, nhwc, n_p=8, rounds=100):
     out = dict(instances=n_p, partition_cus=total_cus // n_p, aggregate_images_per_s=round(conc, 1),
                run_static_max_4_busy_images_per_s=round(gated, 1), run_static_no_gate_images_per_s=round(ungated, 1),
                serial_full_gpu_images_per_s=round(serial, 1), issue="one host thread, round-robin over instances",
+               no_gate_by_partitions_in_use=busy_sweep, all_partitions_by_gate=gate_sweep,
                stage_latency_ms_median=[[round(statistics.median(l), 4) for l in inst] for inst in lat])
     log("multi_tenant", json.dumps({k: v for k, v in out.items() if k != "stage_latency_ms_median"}))
     for t in tasks:
