@@ -617,13 +617,16 @@ def leg_oversubscribed(S, torch, total_cus, nhwc, headline_ips, rounds=300):
 
 
 def leg_periodic(S, hip, torch, total_cus, nhwc, n_list=(128, 256, 320, 384, 448, 512, 576), levels=(1.0, 1.5, 2.0),
-                 shapes=((2, 4), (4, 1)), fps=32.0, duration=0.5):
+                 shapes=((2, 4, 2), (4, 1, 4)), fps=32.0, duration=0.5):
     """'Simulation Results' in kind: N identical periodic ResNet18 tasks (bf16, batch 1, six stages,
     deadline = period = 1/32 s, releases spread evenly over the period) under the SGPRS scheduler
     (sgprs_sched_run_periodic), at over-subscription levels 1.0 / 1.5 / 2.0 (CUs of all contexts /
     CUs of the GPU), on two pool shapes: the paper's two contexts with four lanes each (two for
-    high-priority stages, two for the others; the run loop keeps at most four of the eight CU-masked
-    streams busy at once, because more collapse on this system), and four contexts with one lane each.  Stage WCETs are measured first, on one lane with the rest of the GPU idle
+    high-priority stages, two for the others), and four contexts with one lane each.  The third
+    number of a shape is the run loop's limit on lanes busy at once: CU-masked streams that take
+    turns on the hardware's dispatch pipes slow each other down, and with eight lanes carrying
+    10-50 us stages a limit of two measured best (6.7 k FPS against 5.6 k with three, 4.6 k with
+    four and 4.4 k with none).  Stage WCETs are measured first, on one lane with the rest of the GPU idle
     (the paper's offline phase).  Reported: total FPS and deadline miss rate against the number of
     tasks, and the pivot point (the largest N without a miss)."""
     from workloads import BN_EPS, make_input, make_resnet18_params
@@ -634,7 +637,7 @@ def leg_periodic(S, hip, torch, total_cus, nhwc, n_list=(128, 256, 320, 384, 448
     x = nhwc(make_input(3, 0, (1, 3, 224, 224), bf16=True), torch.bfloat16)
     lgs = [torch.empty((1, 1000), dtype=torch.float32, device="cuda") for _ in range(n_max)]
     out = []
-    for (n_ctx, lanes) in shapes:
+    for (n_ctx, lanes, max_busy) in shapes:
         res = {}
         for level in levels:
             cus = min(total_cus, int(round(total_cus / n_ctx * level)) // 8 * 8)
@@ -661,6 +664,7 @@ def leg_periodic(S, hip, torch, total_cus, nhwc, n_list=(128, 256, 320, 384, 448
             rows, pivot = [], 0
             for n in n_list:
                 sch = S.Sched(n_ctx, lanes)
+                sch.set_max_busy(max_busy)
                 for _ in range(n):
                     sch.add_task(wcet, period, period)
                 rep = sch.run_periodic(pool, tasks[:n], [x.data_ptr()] * n, [l.data_ptr() for l in lgs[:n]], 1, duration,
@@ -677,7 +681,7 @@ def leg_periodic(S, hip, torch, total_cus, nhwc, n_list=(128, 256, 320, 384, 448
             res[f"SGPRS_{level}"] = dict(cus_per_context=cus, stage_wcet_us=[round(w * 1e6, 1) for w in wcet], pivot_tasks=pivot,
                                          points=rows)
             pool.destroy()
-        out.append(dict(contexts=n_ctx, lanes_per_context=lanes, results=res))
+        out.append(dict(contexts=n_ctx, lanes_per_context=lanes, max_busy_lanes=max_busy, results=res))
     for t in tasks:
         t.destroy()
     return dict(task_fps=fps, duration_s=duration, pools=out)
