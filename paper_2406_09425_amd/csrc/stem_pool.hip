@@ -310,26 +310,36 @@ __global__ __launch_bounds__(256, 2) void stem_pool_packed_kernel(const StemPool
         t.n += step_n;
         return t;
     };
-    auto fetch_patch = [&](const TilePos t, int buf) {
+    // The patch of a tile: 16-byte piece u = it * 256 + tid is piece u % 17 of input row u / 17.  Offsets
+    // first (vector arithmetic), then one load instruction per round, so that the loads can be
+    // placed between the MFMAs of the tile before (issued back to back they stall on the address queue).
+    auto patch_offsets = [&](const TilePos t, unsigned (&off)[3]) {
         const int n = t.n, pp0 = t.tp * kPoolTP, pq0 = t.tq * kPoolTQ;
         const int h_base = 4 * pp0 - 5, b_base = 24 * pq0 - 32;  // first input row; byte of the first piece in its row
 #pragma unroll
         for (int it = 0; it < 3; ++it) {
-            if (it == 2 && wave >= 2) break;         // 640 piece slots: the third round is half a round
             const int u = it * 256 + tid;
             const int row = u / 17, seg = u - row * 17;
             const int ih = h_base + row, b = b_base + 16 * seg;
             const bool ok = u < kRowUnits && seg < 16 && (unsigned)ih < (unsigned)a.H && (unsigned)b < (unsigned)row_bytes;
-            const unsigned off = ok ? (unsigned)((n * a.H + ih) * row_bytes + b) : 0x80000000u;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rs, (lds_ptr_t)(smem + buf * kPatchPitch + (it * 256 + wave * 64) * 16), 16,
-                                                     off, 0, 0, 0);
+            off[it] = ok ? (unsigned)((n * a.H + ih) * row_bytes + b) : 0x80000000u;
         }
+    };
+    auto patch_load = [&](int it, const unsigned (&off)[3], int buf) {
+        if (it == 2 && wave >= 2) return;            // 640 piece slots: the third round is half a round
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rs, (lds_ptr_t)(smem + buf * kPatchPitch + (it * 256 + wave * 64) * 16), 16,
+                                                 off[it], 0, 0, 0);
     };
     TilePos cur;
     cur.n = first_tile / per_image;
     cur.tp = (first_tile - cur.n * per_image) / a.tiles_q;
     cur.tq = first_tile - cur.n * per_image - cur.tp * a.tiles_q;
-    if (first_tile < tile_end) fetch_patch(cur, 0);
+    unsigned poffs[3];
+    if (first_tile < tile_end) {
+        patch_offsets(cur, poffs);
+#pragma unroll
+        for (int it = 0; it < 3; ++it) patch_load(it, poffs, 0);
+    }
 
     if (tid < 32) {
         const int c4 = (tid & 15) * 4;
@@ -363,7 +373,8 @@ __global__ __launch_bounds__(256, 2) void stem_pool_packed_kernel(const StemPool
 
         __builtin_amdgcn_s_waitcnt(0);               // this tile's patch has landed (and the last tile's stores have left)
         __syncthreads();                             // ... for every wavefront; the last tile's pooling reads are done
-        if (tile + tile_step < tile_end) fetch_patch(cur, buf ^ 1);
+        const bool has_next = tile + tile_step < tile_end;
+        if (has_next) patch_offsets(cur, poffs);
 
         f32x16_t acc[2][2];
 #pragma unroll
@@ -400,6 +411,7 @@ __global__ __launch_bounds__(256, 2) void stem_pool_packed_kernel(const StemPool
 #pragma unroll
         for (int ks = 0; ks < 11; ++ks) {
             if (ks + STEM_DEPTH < 11) read_b(ks + STEM_DEPTH, pf[(ks + STEM_DEPTH) % (STEM_DEPTH + 1)]);
+            if (has_next && ks % 3 == 1 && ks < 9) patch_load(ks / 3, poffs, buf ^ 1);   // the next tile's patch: K-steps 1, 4, 7
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < 2; ++i)
