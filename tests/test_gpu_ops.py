@@ -175,8 +175,11 @@ def test_add_parity(pools, dtype, relu):
 
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=DT_ID.get)
-@pytest.mark.parametrize("n", [1, 5, 33])
+@pytest.mark.parametrize("n", [1, 5, 33, 515])
 def test_avgpool_fc_parity(pools, dtype, n):
+    """1 and 5 images: one launch; 33: two launches, in bf16 the FC on the matrix cores; 515 (ragged
+    against the 4 images per workgroup of the streaming avg-pool and the 32 of the FC tiles): the
+    many-image avg-pool kernel."""
     bf = dtype == S.SGPRS_BF16
     x = make_input(94, n, (n, 512, 7, 7), bf16=bf)
     w = make_conv_weight(94, n, 1, 1000, 512, 1, bf16=bf)[:, :, 0, 0]
