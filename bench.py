@@ -563,6 +563,10 @@ def leg_membound(S, hip, torch, pool, stream, reps=100):
     # dependent launches, bound by their latency, not by bandwidth: reported as such)
     wfc = (torch.randn((1000, 512), device="cuda") * 0.05).to(tdt)
     bfc = torch.zeros(1000, dtype=torch.float32, device="cuda")
+    # the average pool alone (the memory-bound half; the FC at 4096 images is a 4096 x 512 x 1000 GEMM)
+    timed("global_avgpool 4096x(7x7x512)", 4096 * 49 * 512 * es + 4096 * 512 * 4,
+          lambda: (torch.randn((4096, 49, 512), device="cuda").to(tdt), torch.empty((4096, 512), dtype=torch.float32, device="cuda")),
+          lambda b: S.sgprs_global_avgpool(dt, 4096, 49, 512, b[0].data_ptr(), b[1].data_ptr(), pool, 0))
     for nimg in (4096, 64):
         ws = torch.empty(nimg * 512, dtype=torch.float32, device="cuda")
         nbytes = nimg * 49 * 512 * es + 1000 * 512 * es + nimg * 1000 * 4

@@ -226,6 +226,13 @@ int sgprs_add_relu(int dtype, size_t count, const void *a, const void *b, void *
 int sgprs_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void *x, const void *w,
                      const float *bias, float *logits, float *workspace, sgprs_pool_t *pool,
                      int partition);
+/* Global average pool alone (paper: the average-pooling row of the GPU speedup
+ * analysis): pooled[n][c] = mean over the hw positions of x[n][hw][c], fp32,
+ * summed in a fixed order (the first half of sgprs_avgpool_fc, same kernels,
+ * same bits as its workspace).  c in {512, 1024, 2048}; x and pooled DEVICE,
+ * 16-byte aligned, distinct.  UNSUPPORTED beyond 65535 images or 2^31 elements. */
+int sgprs_global_avgpool(int dtype, int n, int hw, int c, const void *x, float *pooled,
+                         sgprs_pool_t *pool, int partition);
 
 /* The same operator for callers that cannot allocate device memory or pass a
  * workspace: code under HIP graph capture, tight serving loops, harnesses that

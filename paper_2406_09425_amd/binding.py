@@ -19,7 +19,7 @@ __all__ = [
     "sgprs_version", "sgprs_status_string", "sgprs_last_error", "sgprs_build_cu_mask",
     "sgprs_fold_bn", "sgprs_conv_packed_weight_bytes", "sgprs_pack_conv_weights",
     "sgprs_unpack_conv_weights", "sgprs_conv2d_workspace", "sgprs_conv2d", "sgprs_maxpool2d",
-    "sgprs_conv_tuning_override", "sgprs_conv2d_plan", "sgprs_bn_relu", "sgprs_add_relu", "sgprs_avgpool_fc", "sgprs_avgpool_fc_static",
+    "sgprs_conv_tuning_override", "sgprs_conv2d_plan", "sgprs_bn_relu", "sgprs_add_relu", "sgprs_avgpool_fc", "sgprs_global_avgpool", "sgprs_avgpool_fc_static",
     "sgprs_kernel_name",
 ]
 
@@ -112,6 +112,7 @@ def lib():
         "sgprs_add_relu": (c_int, [c_int, c_size_t, vp, vp, vp, c_int, vp, c_int]),
         "sgprs_avgpool_fc": (c_int, [c_int, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp, vp, c_int]),
         "sgprs_avgpool_fc_static": (c_int, [c_int, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp, c_int]),
+        "sgprs_global_avgpool": (c_int, [c_int, c_int, c_int, c_int, vp, vp, vp, c_int]),
         "sgprs_task_create_resnet18": (c_int, [c_int, c_int, c_int, POINTER(_Params), POINTER(vp)]),
         "sgprs_task_destroy": (c_int, [vp]),
         "sgprs_task_num_stages": (c_int, [vp]),
@@ -329,6 +330,10 @@ def sgprs_add_relu(dtype: int, count: int, a: int, b: int, y: int, relu: bool, p
 def sgprs_avgpool_fc(dtype: int, n: int, hw: int, cin: int, cout: int, x: int, w: int, bias: int | None,
                      logits: int, workspace: int, pool, partition: int) -> None:
     _check(lib().sgprs_avgpool_fc(dtype, n, hw, cin, cout, x, w, bias, logits, workspace, _h(pool), partition))
+
+
+def sgprs_global_avgpool(dtype: int, n: int, hw: int, c: int, x: int, pooled: int, pool, partition: int) -> None:
+    _check(lib().sgprs_global_avgpool(dtype, n, hw, c, x, pooled, _h(pool), partition))
 
 
 def sgprs_avgpool_fc_static(dtype: int, n: int, hw: int, cin: int, cout: int, x: int, w: int, bias: int | None,

@@ -221,6 +221,7 @@ int launch_bn_relu(int dtype, size_t pixels, int c, const void* x, const float* 
                    const float* shift, void* y, hipStream_t stream, int cus, Profiler* prof);
 int launch_add_relu(int dtype, size_t count, const void* a, const void* b, void* y, int relu,
                     hipStream_t stream, int cus, Profiler* prof);
+int launch_avgpool(int dtype, int n, int hw, int cin, const void* x, float* pooled, hipStream_t stream, Profiler* prof);
 int launch_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void* x, const void* w,
                       const float* bias, float* logits, float* ws, hipStream_t stream, int cus,
                       Profiler* prof);

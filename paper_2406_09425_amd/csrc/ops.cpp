@@ -149,6 +149,21 @@ int sgprs_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void* x,
     return launch_avgpool_fc(dtype, n, hw, cin, cout, x, w, bias, logits, workspace, stream, cus, nullptr);
 }
 
+int sgprs_global_avgpool(int dtype, int n, int hw, int c, const void* x, float* pooled, sgprs_pool_t* pool, int partition)
+{
+    hipStream_t stream;
+    int cus = 0, rc;
+    if ((rc = resolve(pool, partition, &stream, &cus))) return rc;
+    if (!dtype_ok(dtype)) return fail(SGPRS_ERR_UNSUPPORTED, "dtype %d", dtype);
+    if (n <= 0 || hw <= 0) return fail(SGPRS_ERR_INVALID_ARG, "non-positive dimension");
+    if (n > 65535 || (long long)n * hw * c >= (1ll << 31))
+        return fail(SGPRS_ERR_UNSUPPORTED, "more than 65535 images or 2^31 input elements");
+    if (c != 512 && c != 1024 && c != 2048) return fail(SGPRS_ERR_UNSUPPORTED, "c %d: supported are 512, 1024, 2048", c);
+    if (!x || !pooled || !aligned16(x) || !aligned16(pooled) || (const void*)pooled == x)
+        return fail(SGPRS_ERR_INVALID_ARG, "x and pooled must be distinct, non-NULL and 16-byte aligned");
+    return launch_avgpool(dtype, n, hw, c, x, pooled, stream, nullptr);
+}
+
 int sgprs_avgpool_fc_static(int dtype, int n, int hw, int cin, int cout, const void* x, const void* w, const float* bias,
                             float* logits, sgprs_pool_t* pool, int partition)
 {

@@ -563,6 +563,30 @@ int launch_add_relu(int dtype, size_t count, const void* a, const void* b, void*
     return SGPRS_OK;
 }
 
+// Global average pool alone: x [n][hw][c] -> v fp32 [n][c].
+int launch_avgpool(int dtype, int n, int hw, int cin, const void* x, float* ws, hipStream_t stream, Profiler* prof)
+{
+    const int vec = dtype == SGPRS_BF16 ? 8 : 4;
+    const size_t es = dtype_size(dtype);
+    PROF_BEGIN(kKindAvgpool, dtype, (double)n * hw * cin, (double)n * hw * cin * es + (double)n * cin * 4);
+    if (n >= kAvgpoolStreamMin) {   // many images: one wavefront per image, no LDS, no barrier (the same bits)
+        const dim3 pgrid((cin / vec + 63) / 64, (n + 3) / 4);
+        if (dtype == SGPRS_BF16)
+            SGPRS_LAUNCH(avgpool_stream_kernel<SGPRS_BF16>, pgrid, dim3(256), 0, stream, x, ws, hw, cin, n);
+        else
+            SGPRS_LAUNCH(avgpool_stream_kernel<SGPRS_F32>, pgrid, dim3(256), 0, stream, x, ws, hw, cin, n);
+    } else {
+        const dim3 pgrid((cin / vec + 63) / 64, n);
+        if (dtype == SGPRS_BF16)
+            SGPRS_LAUNCH(avgpool_kernel<SGPRS_BF16>, pgrid, dim3(256), 0, stream, x, ws, hw, cin);
+        else
+            SGPRS_LAUNCH(avgpool_kernel<SGPRS_F32>, pgrid, dim3(256), 0, stream, x, ws, hw, cin);
+    }
+    SGPRS_HIP(hipGetLastError());
+    PROF_END();
+    return SGPRS_OK;
+}
+
 int launch_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void* x, const void* w,
                       const float* bias, float* logits, float* ws, hipStream_t stream, int, Profiler* prof)
 {
@@ -583,22 +607,8 @@ int launch_avgpool_fc(int dtype, int n, int hw, int cin, int cout, const void* x
         PROF_END();
         return SGPRS_OK;
     }
-    PROF_BEGIN(kKindAvgpool, dtype, (double)n * hw * cin, (double)n * hw * cin * es + (double)n * cin * 4);
-    if (n >= kAvgpoolStreamMin) {   // many images: one wavefront per image, no LDS, no barrier (the same bits)
-        const dim3 pgrid((cin / vec + 63) / 64, (n + 3) / 4);
-        if (dtype == SGPRS_BF16)
-            SGPRS_LAUNCH(avgpool_stream_kernel<SGPRS_BF16>, pgrid, dim3(256), 0, stream, x, ws, hw, cin, n);
-        else
-            SGPRS_LAUNCH(avgpool_stream_kernel<SGPRS_F32>, pgrid, dim3(256), 0, stream, x, ws, hw, cin, n);
-    } else {
-        const dim3 pgrid((cin / vec + 63) / 64, n);
-        if (dtype == SGPRS_BF16)
-            SGPRS_LAUNCH(avgpool_kernel<SGPRS_BF16>, pgrid, dim3(256), 0, stream, x, ws, hw, cin);
-        else
-            SGPRS_LAUNCH(avgpool_kernel<SGPRS_F32>, pgrid, dim3(256), 0, stream, x, ws, hw, cin);
-    }
-    SGPRS_HIP(hipGetLastError());
-    PROF_END();
+    int rc = launch_avgpool(dtype, n, hw, cin, x, ws, stream, prof);
+    if (rc) return rc;
 
     if (dtype == SGPRS_BF16 && n >= 32 && cout % 4 == 0 && cin % 512 == 0) {   // enough images for 32 x 32 tiles on the matrix cores
         PROF_BEGIN(kKindFc, 4, 2.0 * n * cin * cout, (double)cin * cout * es + (double)n * (cin + cout) * 4);

@@ -196,6 +196,13 @@ def test_avgpool_fc_parity(pools, dtype, n):
         pools[cus].sync()
         got = yd.cpu().numpy().astype(np.float64)
         assert_close(got, ref, dtype, f"avgpool_fc on {cus} CUs")
+    # the average pool alone: against the oracle, and the same bits as the two-kernel path's workspace
+    pd = torch.full((n, 512), float("nan"), dtype=torch.float32, device="cuda")
+    S.sgprs_global_avgpool(dtype, n, 49, 512, xd.data_ptr(), pd.data_ptr(), pools["full"], 0)
+    pools["full"].sync()
+    assert rel_err(pd.cpu().numpy().astype(np.float64), oracle.global_avgpool(x).reshape(n, 512)) < (1e-6 if not bf else 1e-6)
+    if n > 8:
+        assert torch.equal(pd.flatten(), ws)
     # without bias
     S.sgprs_avgpool_fc(dtype, n, 49, 512, 1000, xd.data_ptr(), wd.data_ptr(), None, yd.data_ptr(),
                        ws.data_ptr(), pools["full"], 0)
