@@ -249,9 +249,8 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemPoolArgs a)
 // ---------------------------------------------------------------------------------------------
 // bf16 variant with packed input rows.
 //
-// The kernel above spends its time in the LDS pipe: every wavefront re-reads all weights for each
-// tile, the 4-slot pixel layout pads K from 147 to 224, and the patch goes through registers.
-// Here
+// In the kernel above every wavefront re-reads all weights from LDS for each tile, the 4-slot pixel
+// layout pads K from 147 to 224, and the patch goes through registers and LDS stores.  Here
 //  * the weights are stationary in registers (88 VGPRs: 2 channel tiles x 11 K-steps), loaded once
 //    per workgroup from a [64][176] layout prepared at task creation;
 //  * the input patch keeps the image's own 3-channel packing: 35 rows of 17 16-byte pieces are
