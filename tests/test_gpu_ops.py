@@ -313,30 +313,31 @@ def test_conv3x3s2_patch_variants_parity(pools, variant, shape):
 
 # ---- the row-streaming 3x3 kernel of the 64 -> 64 layers -----------------------------
 ROWS_CASES = [
-    # batch, partition, rows per stream and job the planner picks: one job per CU, jobs that cross the middle of
-    # an image (7, 14) or cover whole images (28), several jobs per workgroup (batch 16 on 8 CUs)
-    (2, 8, 7), (4, 8, 14), (8, 8, 28), (16, 64, 7), (16, 8, 28),
+    # batch, image height, partition, rows per stream and job the planner picks: one job per CU, jobs that cross
+    # the middle of an image (7, 14) or cover whole images (28), several jobs per workgroup (batch 16 on 8 CUs),
+    # and a 28-row image (two jobs of 2 x 7 rows)
+    (2, 56, 8, 7), (4, 56, 8, 14), (8, 56, 8, 28), (16, 56, 64, 7), (16, 56, 8, 28), (4, 28, 8, 7),
 ]
 
 
-@pytest.mark.parametrize("case", ROWS_CASES, ids=lambda c: "n%d-%dcu-S%d" % c)
+@pytest.mark.parametrize("case", ROWS_CASES, ids=lambda c: "n%d-h%d-%dcu-S%d" % c)
 def test_conv3x3_rows_parity(pools, case):
-    """56 x 56, 64 -> 64 channels in bf16 on partitions where every CU gets whole jobs: the planner
+    """56-pixel rows, 64 -> 64 channels in bf16 on partitions where every CU gets whole jobs: the planner
     picks the row-streaming kernel; element by element against the oracle with and without residual
     and ReLU, and against the LDS-patch kernel (tuning override 5) on the same inputs."""
-    n, cus, rows = case
+    n, h, cus, rows = case
     pool = pools[cus]
     dtype = S.SGPRS_BF16
-    d = S.ConvDesc(n, 56, 56, 64, 64, 3, 3, 1, 1, dtype, 1)
+    d = S.ConvDesc(n, h, 56, 64, 64, 3, 3, 1, 1, dtype, 1)
     assert S.sgprs_conv2d_plan(d, cus, True) == (3, rows)
     assert S.sgprs_conv2d_plan(d, cus, False) == (3, rows)
     for with_res, relu in ((True, True), (False, True), (False, False), (True, False)):
-        got, ref = conv_case(dtype, n, 56, 56, 64, 64, 3, 1, 1, relu=relu, with_res=with_res, seed=70 + n, pool=pool, cus=cus)
+        got, ref = conv_case(dtype, n, h, 56, 64, 64, 3, 1, 1, relu=relu, with_res=with_res, seed=70 + n, pool=pool, cus=cus)
         assert_close(got, ref, dtype, f"rows kernel {case} res {with_res} relu {relu}")
         try:
             S.sgprs_conv_tuning_override(5, 0, 1)
             assert S.sgprs_conv2d_plan(d, cus, with_res)[0] == 1
-            other, _ = conv_case(dtype, n, 56, 56, 64, 64, 3, 1, 1, relu=relu, with_res=with_res, seed=70 + n, pool=pool, cus=cus)
+            other, _ = conv_case(dtype, n, h, 56, 64, 64, 3, 1, 1, relu=relu, with_res=with_res, seed=70 + n, pool=pool, cus=cus)
         finally:
             S.sgprs_conv_tuning_override(-1, 0, 1)
         # the same bf16 inputs, fp32 sums in another order: at most a bf16 step apart
