@@ -22,8 +22,11 @@
 //  * one barrier per step, in the middle of its MFMAs; what a step waits for was requested two
 //    steps earlier.
 //
-// Ring pixel pitch is 144 bytes (128 of channels + 16 of padding): a shift by one pixel or by 32
-// channels is a constant address offset, and 16 consecutive pixels spread over all LDS banks.
+// Ring pixel pitch is 160 bytes (128 of channels + 32 of padding): a shift by one pixel or by 32
+// channels is a constant address offset, and the fragment read of 16 consecutive pixels x 4 K groups
+// is free of bank conflicts (measured: 2.1 ns per wavefront-instruction, as for contiguous
+// addresses; 3.6 ns with a pitch of 144 or 272 bytes, whatever the order of pixels and K groups).
+// The two streams of a row share the zero pixel between them: [0][56 pixels][0][56 pixels][0].
 #include "internal.h"
 
 namespace sgprs {
@@ -45,9 +48,9 @@ struct RowsArgs {
 };
 
 constexpr int kRowsWidth = 56, kRowsStreams = 2, kRowsVRow = kRowsWidth * kRowsStreams;
-constexpr int kRowsPixB = 144;
-constexpr int kRowsSlotUnits = (kRowsWidth + 2) * 9;                       // 16-byte units of one ring row with halo pixels
-constexpr int kRowsStepUnits = kRowsStreams * kRowsSlotUnits;
+constexpr int kRowsPixB = 160, kRowsPixUnits = kRowsPixB / 16;
+constexpr int kRowsSlotPix = kRowsWidth + 1;                               // pixel slots from one stream to the next (one zero pixel between)
+constexpr int kRowsStepUnits = (kRowsStreams * kRowsSlotPix + 1) * kRowsPixUnits;   // 16-byte units of the rows of one step
 constexpr int kRowsStepStride = (kRowsStepUnits + 63) / 64 * 1024;         // whole 1 KiB load instructions
 constexpr int kRowsRowBytes = kRowsVRow * 128;
 constexpr int kRowsRsBase = 4 * kRowsStepStride, kRowsOsBase = kRowsRsBase + 4 * kRowsRowBytes;
@@ -73,7 +76,7 @@ __device__ __forceinline__ void rows_body(const RowsArgs& a, unsigned char* smem
 {
 #if __HIP_DEVICE_COMPILE__
     constexpr int WIDTH = kRowsWidth, NS = kRowsStreams, VROW = kRowsVRow, PIXB = kRowsPixB;
-    constexpr int SLOT_UNITS = kRowsSlotUnits, SLOT_BYTES = SLOT_UNITS * 16;
+    constexpr int SLOT_BYTES = kRowsSlotPix * PIXB, UPP = kRowsPixUnits;
     constexpr int STEP_UNITS = kRowsStepUnits, LOAD_IT = (STEP_UNITS + 511) / 512, STEP_STRIDE = kRowsStepStride;
     constexpr int RS_BASE = kRowsRsBase, OS_BASE = kRowsOsBase, DUMMY_BASE = kRowsDummyBase;
     typedef __attribute__((address_space(3))) void* lds_ptr_t;
@@ -92,16 +95,16 @@ __device__ __forceinline__ void rows_body(const RowsArgs& a, unsigned char* smem
         for (int ks = 0; ks < 2; ++ks)
             wf[tap][ks] = __builtin_amdgcn_raw_buffer_load_b128(w_rs, (unsigned)((((q * 16 + j16) * 9 + tap) * 64 + ks * 32 + g * 8) * 2), 0, 0);
 
-    // loader table: unit u = it * 512 + tid of a step's rows is slot u % 9 of pixel (u % SLOT_UNITS) / 9 of stream
-    // u / SLOT_UNITS; packed as stream << 16 | byte offset inside the image row, all ones for no data (halo
-    // pixels, the padding slot)
+    // loader table: unit u = it * 512 + tid of a step's rows is 16-byte piece u % UPP of pixel slot u / UPP; slot
+    // k * (WIDTH + 1) is a zero pixel, the WIDTH slots behind it are stream k; packed as stream << 16 | byte offset
+    // inside the image row, all ones for no data (zero pixels, the padding pieces)
     unsigned ld_tab[LOAD_IT];
 #pragma unroll
     for (int it = 0; it < LOAD_IT; ++it) {
         const int u = it * 512 + tid;
-        const int k = u / SLOT_UNITS, rem = u - k * SLOT_UNITS;
-        const int px = rem / 9, cg = rem - px * 9;
-        const bool ok = u < STEP_UNITS && px >= 1 && px <= WIDTH && cg < 8;
+        const int slot = u / UPP, cg = u - slot * UPP;
+        const int k = slot / kRowsSlotPix, px = slot - k * kRowsSlotPix;   // px 0: the zero pixel in front of stream k
+        const bool ok = u < STEP_UNITS && k < NS && px >= 1 && cg < 8;
         ld_tab[it] = ok ? (unsigned)(k << 16) | (unsigned)(((px - 1) * 64 + cg * 8) * 2) : 0xffffffffu;
     }
     unsigned boff[NSUB];   // B fragment address for filter column 0, channels 0-31; + PIXB per column, + 64 for channels 32-63
