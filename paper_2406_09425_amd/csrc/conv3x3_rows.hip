@@ -168,10 +168,12 @@ __device__ __forceinline__ void rows_body(const RowsArgs& a, unsigned char* smem
         // acc0 / acc1 / acc2: partial sums of output rows t / t - 1 / t - 2 at step t
         f32x4_t acc0[NSUB], acc1[NSUB], acc2[NSUB];
         u32x4_t bfr[NSUB];
-        // where in a step the stores, the requests and the epilogue arithmetic go: right after the barrier
-        // for the wavefront with four tiles, two MFMA groups later for the one with three, so that the two
-        // wavefronts of a SIMD do their vector work at different times
-        constexpr int TAIL_GI = NSUB == 3 ? 4 : 2;
+        // where in a step the stores, the requests and the epilogue arithmetic go: one MFMA group after the
+        // barrier for the wavefront with four tiles, three groups after it (the step's last group) for the one
+        // with three, so that the two wavefronts of a SIMD do their vector work at different times (measured
+        // inside the network, same box: 22.4 us per launch against 23.1 us for groups 2 and 4, 22.7-23.5 us
+        // for 2/3, 2/5, 2/2, 3/4, 4/2, 5/3 and 5/5, 22.3-22.5 us for 4/5)
+        constexpr int TAIL_GI = NSUB == 3 ? 5 : 3;
 #pragma unroll
         for (int sub = 0; sub < NSUB; ++sub) {
             acc0[sub] = acc1[sub] = acc2[sub] = f32x4_t{0.f, 0.f, 0.f, 0.f};
